@@ -1,0 +1,150 @@
+"""Pins for the oracle's KV repartition / pack / unpack (Section 6.3, Eq. 10:
+the migrated cache is the union of the per-GPU caches multiplied element-wise
+by the token validity mask).  The expected placement is recomputed here by an
+independent per-token index walk over Python dictionaries, not by the oracle's
+copy loop."""
+import numpy as np
+import pytest
+
+import oracle
+from oracle import KVView, Shape
+from paper_2510_11938_amd import synth
+
+SH = Shape(hidden=64, n_q_heads=4, n_kv_heads=2, head_dim=8, ffn=64, kv_block_size=4)
+SH16 = Shape(hidden=256, n_q_heads=4, n_kv_heads=4, head_dim=64, ffn=688, kv_block_size=16)
+
+
+def random_stage_caches(shape, ranges, lens, seed, junk=True, spare=2):
+    """One KVView per layer range with a random table; pools filled with random
+    16-bit words everywhere (also in invalid slots and unowned blocks)."""
+    rng = np.random.default_rng(seed)
+    views = []
+    for s, (a, b) in enumerate(ranges):
+        table, nblk = synth.block_table(lens, shape.kv_block_size, seed=seed, salt=10 + s, spare_blocks=spare)
+        pool = oracle.new_pool(shape, b - a, nblk, dtype=np.uint16)
+        if junk:
+            pool[...] = rng.integers(1, 65536, size=pool.shape, dtype=np.uint16)
+        views.append(KVView(pool, a, b, table))
+    return views
+
+
+def token_dict(shape, views, lens):
+    """{(layer, seq, token, kv, head): tuple(row)} by walking every valid token."""
+    bs = shape.kv_block_size
+    out = {}
+    for v in views:
+        for layer in range(v.layer_begin, v.layer_end):
+            for i, c in enumerate(lens):
+                for r in range(int(c)):
+                    blk = v.block_table[i, r // bs]
+                    for kv in range(2):
+                        for h in range(shape.n_kv_heads):
+                            out[(layer, i, r, kv, h)] = tuple(v.pool[layer - v.layer_begin, blk, kv, h, r % bs])
+    return out
+
+
+@pytest.mark.parametrize("src_ranges,dst_ranges", [
+    ([(0, 2)], [(0, 1), (1, 2)]),                 # split
+    ([(0, 1), (1, 2)], [(0, 2)]),                 # merge
+    ([(3, 5), (5, 9)], [(3, 6), (6, 7), (7, 9)]), # re-split at other boundaries, model numbering
+    ([(0, 3)], [(0, 3)]),                         # same boundaries, fresh table
+])
+def test_repartition_preserves_every_valid_token_and_zeroes_invalid_slots(src_ranges, dst_ranges):
+    lens = np.array([5, 8, 1, 0, 11], dtype=np.int32)      # ragged tail, exact multiple, single, empty
+    src = random_stage_caches(SH, src_ranges, lens, seed=1)
+    dst = random_stage_caches(SH, dst_ranges, lens, seed=2, spare=3)
+    before_dst = [v.pool.copy() for v in dst]
+    want = token_dict(SH, src, lens)
+    oracle.kv_repartition(SH, src, dst, lens)
+    assert token_dict(SH, dst, lens) == want
+    bs = SH.kv_block_size
+    for v, before in zip(dst, before_dst):
+        owned = np.zeros(v.pool.shape[1], dtype=bool)
+        for i, c in enumerate(lens):
+            nb = (c + bs - 1) // bs
+            owned[v.block_table[i, :nb]] = True
+            if c % bs:
+                last = v.block_table[i, nb - 1]
+                assert np.all(v.pool[:, last, :, :, c % bs:, :] == 0)        # masked-out slots arrive as zero
+        assert np.array_equal(v.pool[:, ~owned], before[:, ~owned])          # unowned blocks untouched
+    # the sources are not modified
+    src2 = random_stage_caches(SH, src_ranges, lens, seed=1)
+    assert all(np.array_equal(a.pool, b.pool) for a, b in zip(src, src2))
+
+
+def test_split_then_merge_round_trip_is_identity_on_valid_tokens():
+    lens = synth.draw_lengths(("uniform", 32, 128), 4, seed=0)
+    a = random_stage_caches(SH16, [(0, 2)], lens, seed=3)
+    b = random_stage_caches(SH16, [(0, 1), (1, 2)], lens, seed=4)
+    c = random_stage_caches(SH16, [(0, 2)], lens, seed=5, junk=False)
+    c[0].block_table = a[0].block_table.copy()               # same placement as the origin
+    c[0].pool = oracle.new_pool(SH16, 2, a[0].pool.shape[1], dtype=np.uint16)
+    oracle.kv_repartition(SH16, a, b, lens)
+    oracle.kv_repartition(SH16, b, c, lens)
+    assert token_dict(SH16, c, lens) == token_dict(SH16, a, lens)
+    # whole blocks are identical iff the source tails were zero: zero them and compare
+    bs = SH16.kv_block_size
+    masked = a[0].pool.copy()
+    owned = np.zeros(masked.shape[1], dtype=bool)
+    for i, n in enumerate(lens):
+        nb = (n + bs - 1) // bs
+        owned[a[0].block_table[i, :nb]] = True
+        if n % bs:
+            masked[:, a[0].block_table[i, nb - 1], :, :, n % bs:, :] = 0
+    assert np.array_equal(c[0].pool[:, owned], masked[:, owned])
+
+
+def test_repartition_brute_force_tiny():
+    # one sequence of 6 tokens, block size 4, one head of dim 8: write the expected pool by hand
+    sh = Shape(hidden=8, n_q_heads=1, n_kv_heads=1, head_dim=8, ffn=8, kv_block_size=4)
+    src_pool = np.arange(1, 1 + 2 * 3 * 2 * 1 * 4 * 8, dtype=np.uint16).reshape(2, 3, 2, 1, 4, 8)
+    src = [KVView(src_pool, 0, 2, np.array([[2, 0]], dtype=np.int32))]
+    d0 = KVView(np.full((1, 2, 2, 1, 4, 8), 7, dtype=np.uint16), 0, 1, np.array([[1, 0]], dtype=np.int32))
+    d1 = KVView(np.full((1, 4, 2, 1, 4, 8), 9, dtype=np.uint16), 1, 2, np.array([[3, 1]], dtype=np.int32))
+    oracle.kv_repartition(sh, src, [d0, d1], [6])
+    e0 = np.full((1, 2, 2, 1, 4, 8), 7, dtype=np.uint16)
+    e0[0, 1] = src_pool[0, 2]                       # logical block 0: src phys 2 -> dst phys 1
+    e0[0, 0] = src_pool[0, 0]; e0[0, 0, :, :, 2:, :] = 0   # logical block 1 holds tokens 4,5 only
+    e1 = np.full((1, 4, 2, 1, 4, 8), 9, dtype=np.uint16)
+    e1[0, 3] = src_pool[1, 2]
+    e1[0, 1] = src_pool[1, 0]; e1[0, 1, :, :, 2:, :] = 0
+    assert np.array_equal(d0.pool, e0) and np.array_equal(d1.pool, e1)
+
+
+def test_repartition_rejects_ranges_that_do_not_tile_the_same_layers():
+    lens = np.array([4], dtype=np.int32)
+    src = random_stage_caches(SH, [(0, 2)], lens, seed=6)
+    for bad in ([(0, 1)], [(0, 1), (2, 3)], [(1, 3)], [(0, 1), (1, 1), (1, 2)]):
+        with pytest.raises(ValueError):
+            oracle.kv_repartition(SH, src, random_stage_caches(SH, bad, lens, seed=7), lens)
+
+
+def test_pack_layout_and_unpack_inverse():
+    lens = np.array([5, 0, 9], dtype=np.int32)
+    src = random_stage_caches(SH, [(2, 5)], lens, seed=8)[0]
+    lb, le = 3, 5
+    packed = oracle.kv_pack(SH, src, lb, le, lens)
+    bs = SH.kv_block_size
+    nblk = (lens + bs - 1) // bs
+    assert packed.size == nblk.sum() * (le - lb) * SH.block_elems
+    # independent walk of the documented order [seq][layer][block][K,V][head][slot][dim]
+    expect = []
+    for i, c in enumerate(lens):
+        for layer in range(lb, le):
+            for j in range(nblk[i]):
+                blk = src.pool[layer - 2, src.block_table[i, j]].copy()      # [2][Hkv][bs][D]
+                valid = min(bs, c - j * bs)
+                blk[:, :, valid:, :] = 0
+                expect.append(blk.reshape(-1))
+    assert np.array_equal(packed, np.concatenate(expect))
+    # unpack into a fresh stage that owns exactly [3,5), then compare with direct repartition
+    dst = random_stage_caches(SH, [(3, 5)], lens, seed=9)[0]
+    dst2 = KVView(dst.pool.copy(), 3, 5, dst.block_table.copy())
+    oracle.kv_unpack(SH, packed, dst, lb, le, lens)
+    want = {k: v for k, v in token_dict(SH, [src], lens).items() if lb <= k[0] < le}
+    assert token_dict(SH, [dst], lens) == want
+    # element size is a parameter: the same movement on float32 pools
+    srcf = KVView(src.pool.astype(np.float32), 2, 5, src.block_table)
+    dstf = KVView(dst2.pool.astype(np.float32), 3, 5, dst2.block_table)
+    oracle.kv_unpack(SH, oracle.kv_pack(SH, srcf, lb, le, lens), dstf, lb, le, lens)
+    assert np.array_equal(dstf.pool, dst.pool.astype(np.float32))
