@@ -1,0 +1,183 @@
+/*
+ * flexstage — C ABI of the MI355X (gfx950) stage-forward and KV-repartition library.
+ *
+ * The library executes the GPU work of ONE fine-grained pipeline stage of the
+ * FlexPipe serving method: the forward step of a contiguous decoder-layer range
+ * over a dynamic batch, and the movement of the stage's per-layer KV cache when
+ * inflight refactoring merges or splits stage boundaries.
+ *
+ * General conventions
+ *   - Every function returns FXP_OK (0) or a negative FXP_E* code; after a
+ *     failure fxp_last_error() holds a message (thread-local, static storage).
+ *     No exception or abort crosses this boundary.
+ *   - Pointers marked DEVICE are HIP device pointers owned by the caller; the
+ *     library borrows them for the duration of the call (the weight arena: for
+ *     the life of the stage handle).  Pointers marked HOST are ordinary host
+ *     memory.  The library allocates no device memory, ever.
+ *   - All GPU work is enqueued on `hip_stream` (a hipStream_t passed as void*,
+ *     NULL = the default stream) and the call returns without synchronising.
+ *   - Host-side arguments are validated; the CONTENTS of device-side tables
+ *     (block ids, lengths) are trusted and must be consistent with the sizes
+ *     given on the host side.
+ *   - bf16 = the 16-bit brain-float format (1 sign, 8 exponent, 7 mantissa bits).
+ *   - Results are deterministic: the same inputs give bit-identical outputs,
+ *     independent of the physical block placement and of how many layers the
+ *     stage holds.
+ */
+#ifndef FLEXSTAGE_H
+#define FLEXSTAGE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FXP_OK       0
+#define FXP_EINVAL  (-1)   /* null pointer, bad layer range, unsupported shape            */
+#define FXP_ENOSPC  (-2)   /* workspace, weight arena or packed buffer too small           */
+#define FXP_EHIP    (-3)   /* a HIP call or kernel launch failed                           */
+
+typedef struct fxp_stage fxp_stage;           /* opaque, library-owned host object */
+
+/* A stage is a contiguous subset of the model's layers (Section 5: each stage
+ * S_k is a subset of operators, the stages are disjoint and cover the graph). */
+typedef struct {
+    int32_t layer_begin, layer_end;           /* [l0, l1) in model numbering, l0 < l1   */
+    int32_t hidden;                           /* H, multiple of 16                       */
+    int32_t n_q_heads, n_kv_heads;            /* n_q_heads % n_kv_heads == 0             */
+    int32_t head_dim;                         /* D: 64 or 128                            */
+    int32_t ffn;                              /* F, multiple of 16                       */
+    float   rms_eps;
+    float   rope_base;
+    int32_t kv_block_size;                    /* tokens per cache block: must be 16      */
+} fxp_stage_desc;
+
+/* One decoder layer's parameters.  DEVICE, bf16, every matrix row-major
+ * [out_features][in_features]; gains are [hidden]. */
+typedef struct {
+    const void *g_attn;                       /* [H]            attention RMSNorm gain   */
+    const void *wq, *wk, *wv;                 /* [Hq*D][H], [Hkv*D][H], [Hkv*D][H]       */
+    const void *wo;                           /* [H][Hq*D]                               */
+    const void *g_ffn;                        /* [H]            feed-forward RMSNorm gain*/
+    const void *w_gate, *w_up;                /* [F][H]                                  */
+    const void *w_down;                       /* [H][F]                                  */
+} fxp_layer_weights;
+
+/* A stage's paged KV cache.  DEVICE, bf16, caller-owned, logical shape
+ *   [layer - layer_begin][block][2: K,V][n_kv_heads][kv_block_size][head_dim].
+ * K rows are stored after the rotary embedding. */
+typedef struct {
+    void   *base;
+    int64_t num_blocks;                       /* physical blocks per layer               */
+    int32_t layer_begin, layer_end;           /* model layers the pool holds             */
+} fxp_kv_pool;
+
+/* One step's dynamic batch (Section 7: stages serve dynamically batched
+ * requests).  Sequence i contributes the tokens cu_seqlens_q[i] ..
+ * cu_seqlens_q[i+1]-1 of the packed hidden matrix; its j-th new token has
+ * absolute position ctx_lens[i] + j; ctx_lens[i] tokens are already cached.
+ * Row i of the block table lists the physical blocks of sequence i and must
+ * have room for ctx_lens[i] + q_len_i tokens.  One table per stage, shared by
+ * the stage's layers. */
+typedef struct {
+    int32_t num_seqs;
+    int32_t num_tokens;                       /* T = cu_seqlens_q[num_seqs]              */
+    int32_t max_q_len;                        /* max over i of q_len_i (1 for decode)    */
+    int32_t max_blocks_per_seq;               /* row pitch of block_table                */
+    const int32_t *cu_seqlens_q;              /* DEVICE [num_seqs + 1]                   */
+    const int32_t *ctx_lens;                  /* DEVICE [num_seqs]                       */
+    const int32_t *block_table;               /* DEVICE [num_seqs][max_blocks_per_seq]   */
+} fxp_batch;
+
+/* A stage's cache as seen by the repartition calls: pool + that stage's table. */
+typedef struct {
+    const fxp_kv_pool *pool;                  /* HOST pointer to the pool descriptor     */
+    const int32_t *block_table;               /* DEVICE [num_seqs][max_blocks_per_seq]   */
+    int32_t max_blocks_per_seq;
+} fxp_kv_view;
+
+/* ---- stage lifetime -------------------------------------------------------
+ * Section 5 asks that the parameters of one logical group stay contiguous in
+ * memory so that merged or split stages reuse the layout.  fxp_stage_create
+ * therefore re-tiles each layer's matrices into ONE contiguous per-layer
+ * record inside `weight_arena` (DEVICE, caller-owned, at least
+ * fxp_stage_weight_arena_bytes(desc) bytes, 256-byte aligned); a stage
+ * covering any sub-range of layers can point into the same arena.
+ * `layers` is a HOST array of layer_end - layer_begin entries.  The packing
+ * kernels run on `hip_stream`; the caller's source tensors may be released once
+ * that work has completed, the arena must outlive the handle. */
+size_t fxp_stage_weight_arena_bytes(const fxp_stage_desc *desc);
+int    fxp_stage_create(const fxp_stage_desc *desc, const fxp_layer_weights *layers,
+                        void *weight_arena, size_t weight_arena_bytes, void *hip_stream,
+                        fxp_stage **out);
+int    fxp_stage_destroy(fxp_stage *stage);
+
+/* ---- stage forward (Section 3.2, Table 2 "Compute": per-stage inference) ---
+ * hidden_out = layers [l0,l1) applied to hidden_in, both DEVICE bf16
+ * [num_tokens][hidden] (they may be the same buffer).  Each layer is the
+ * pre-norm decoder layer: RMSNorm, q/k/v projections, rotary embedding
+ * (rotate-half pairing), append of K,V to the paged cache, causal softmax
+ * attention over the cached prefix plus the new tokens, output projection +
+ * residual, RMSNorm, SwiGLU feed-forward + residual.  The pool's layer range
+ * must equal the stage's.  `workspace` is DEVICE scratch of at least
+ * fxp_stage_workspace_bytes(...) bytes for the given bounds, 256-byte aligned;
+ * its contents are undefined afterwards. */
+size_t fxp_stage_workspace_bytes(const fxp_stage *stage, int32_t max_tokens, int32_t max_seqs,
+                                 int32_t max_blocks_per_seq);
+int    fxp_stage_forward(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_batch *batch,
+                         const void *hidden_in, void *hidden_out,
+                         void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Test-only variant: additionally writes the attention probabilities the
+ * kernels computed, DEVICE float [n_layers][num_tokens][n_q_heads][probs_stride],
+ * entries 0..position of each token (the rest is left untouched).  Meant for
+ * small shapes. */
+int    fxp_stage_forward_debug(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_batch *batch,
+                               const void *hidden_in, void *hidden_out,
+                               void *workspace, size_t workspace_bytes,
+                               float *probs, int64_t probs_stride, void *hip_stream);
+
+/* ---- KV repartition (Section 6.3, Eq. 10; Algorithm 1, migration step) -----
+ * When stage boundaries move, the cache of every layer moves to the stage that
+ * now owns the layer, multiplied element-wise by the token validity mask: for
+ * every destination view d, layer l in its range, sequence i, logical block
+ * j < ceil(ctx_lens[i]/16): the K and V block is copied from the source view
+ * that holds layer l (block src_table[i][j]) to dst_table_d[i][j]; slots at or
+ * beyond ctx_lens[i] arrive as zero; destination blocks that no listed
+ * sequence maps to are not written.  Bit-exact on the 16-bit words.
+ * `src` and `dst` are HOST arrays; each list must tile the same layer range in
+ * ascending order without gaps; source and destination pools must not overlap.
+ * ctx_lens: DEVICE [num_seqs], the tokens valid after the last completed step.
+ * Only desc->n_kv_heads, head_dim and kv_block_size are read. */
+int    fxp_kv_repartition(const fxp_stage_desc *desc,
+                          const fxp_kv_view *src, int32_t n_src,
+                          const fxp_kv_view *dst, int32_t n_dst,
+                          const int32_t *ctx_lens, int32_t num_seqs, void *hip_stream);
+
+/* The two halves of a repartition that crosses devices: pack gathers layers
+ * [layer_begin, layer_end) of ONE source view into a contiguous DEVICE buffer
+ *   [sequence][layer - layer_begin][logical block][2: K,V][kv_head][slot][head_dim]
+ * (invalid slots zero); unpack scatters such a buffer into ONE destination
+ * view through its own table.  fxp_kv_packed_bytes takes the lengths from HOST
+ * memory; pack/unpack return FXP_ENOSPC when packed_bytes is smaller than
+ * max_total_blocks * (layers) * block bytes, where max_total_blocks is the
+ * caller's bound on sum_i ceil(ctx_lens[i]/16) implied by packed_bytes. */
+size_t fxp_kv_packed_bytes(const fxp_stage_desc *desc, int32_t layer_begin, int32_t layer_end,
+                           const int32_t *ctx_lens_host, int32_t num_seqs);
+int    fxp_kv_pack(const fxp_stage_desc *desc, const fxp_kv_view *src,
+                   int32_t layer_begin, int32_t layer_end,
+                   const int32_t *ctx_lens, int32_t num_seqs,
+                   void *packed, size_t packed_bytes, void *hip_stream);
+int    fxp_kv_unpack(const fxp_stage_desc *desc, const void *packed, size_t packed_bytes,
+                     const fxp_kv_view *dst, int32_t layer_begin, int32_t layer_end,
+                     const int32_t *ctx_lens, int32_t num_seqs, void *hip_stream);
+
+const char *fxp_last_error(void);
+const char *fxp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLEXSTAGE_H */

@@ -1,0 +1,246 @@
+"""Thin ctypes binding over the C ABI declared in ``include/flexstage.h``.
+
+Argument marshalling only: torch tensors supply device memory and the current
+HIP stream; every step of the path runs inside ``libflexstage.so``.  The
+library must have been built (``python -m paper_2510_11938_amd.build``); a
+missing library is an error, there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Dict, List, Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libflexstage.so")
+
+FXP_OK, FXP_EINVAL, FXP_ENOSPC, FXP_EHIP = 0, -1, -2, -3
+
+EXPORTS = (
+    "fxp_stage_weight_arena_bytes", "fxp_stage_create", "fxp_stage_destroy",
+    "fxp_stage_workspace_bytes", "fxp_stage_forward", "fxp_stage_forward_debug",
+    "fxp_kv_repartition", "fxp_kv_packed_bytes", "fxp_kv_pack", "fxp_kv_unpack",
+    "fxp_last_error", "fxp_version",
+)
+
+
+class FxpError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"flexstage error {code}: {message}")
+        self.code = code
+
+
+class StageDesc(C.Structure):
+    _fields_ = [
+        ("layer_begin", C.c_int32), ("layer_end", C.c_int32), ("hidden", C.c_int32),
+        ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+        ("ffn", C.c_int32), ("rms_eps", C.c_float), ("rope_base", C.c_float),
+        ("kv_block_size", C.c_int32),
+    ]
+
+
+LAYER_TENSORS = ("g_attn", "wq", "wk", "wv", "wo", "g_ffn", "w_gate", "w_up", "w_down")
+
+
+class LayerWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in LAYER_TENSORS]
+
+
+class KvPool(C.Structure):
+    _fields_ = [("base", C.c_void_p), ("num_blocks", C.c_int64),
+                ("layer_begin", C.c_int32), ("layer_end", C.c_int32)]
+
+
+class Batch(C.Structure):
+    _fields_ = [
+        ("num_seqs", C.c_int32), ("num_tokens", C.c_int32), ("max_q_len", C.c_int32),
+        ("max_blocks_per_seq", C.c_int32),
+        ("cu_seqlens_q", C.c_void_p), ("ctx_lens", C.c_void_p), ("block_table", C.c_void_p),
+    ]
+
+
+class KvView(C.Structure):
+    _fields_ = [("pool", C.POINTER(KvPool)), ("block_table", C.c_void_p),
+                ("max_blocks_per_seq", C.c_int32)]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Open libflexstage.so (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2510_11938_amd.build` "
+                "(there is no CPU fallback)")
+        l = C.CDLL(LIB_PATH)
+        l.fxp_last_error.restype = C.c_char_p
+        l.fxp_version.restype = C.c_char_p
+        l.fxp_stage_weight_arena_bytes.restype = C.c_size_t
+        l.fxp_stage_weight_arena_bytes.argtypes = [C.POINTER(StageDesc)]
+        l.fxp_stage_create.argtypes = [C.POINTER(StageDesc), C.POINTER(LayerWeights), C.c_void_p, C.c_size_t,
+                                       C.c_void_p, C.POINTER(C.c_void_p)]
+        l.fxp_stage_destroy.argtypes = [C.c_void_p]
+        l.fxp_stage_workspace_bytes.restype = C.c_size_t
+        l.fxp_stage_workspace_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32]
+        l.fxp_stage_forward.argtypes = [C.c_void_p, C.POINTER(KvPool), C.POINTER(Batch), C.c_void_p, C.c_void_p,
+                                        C.c_void_p, C.c_size_t, C.c_void_p]
+        l.fxp_stage_forward_debug.argtypes = [C.c_void_p, C.POINTER(KvPool), C.POINTER(Batch), C.c_void_p, C.c_void_p,
+                                              C.c_void_p, C.c_size_t, C.c_void_p, C.c_int64, C.c_void_p]
+        l.fxp_kv_repartition.argtypes = [C.POINTER(StageDesc), C.POINTER(KvView), C.c_int32, C.POINTER(KvView),
+                                         C.c_int32, C.c_void_p, C.c_int32, C.c_void_p]
+        l.fxp_kv_packed_bytes.restype = C.c_size_t
+        l.fxp_kv_packed_bytes.argtypes = [C.POINTER(StageDesc), C.c_int32, C.c_int32, C.c_void_p, C.c_int32]
+        l.fxp_kv_pack.argtypes = [C.POINTER(StageDesc), C.POINTER(KvView), C.c_int32, C.c_int32, C.c_void_p,
+                                  C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
+        l.fxp_kv_unpack.argtypes = [C.POINTER(StageDesc), C.c_void_p, C.c_size_t, C.POINTER(KvView), C.c_int32,
+                                    C.c_int32, C.c_void_p, C.c_int32, C.c_void_p]
+        _lib = l
+    return _lib
+
+
+def _check(rc: int) -> None:
+    if rc != FXP_OK:
+        raise FxpError(rc, lib().fxp_last_error().decode())
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def make_desc(shape, layer_begin: int, layer_end: int) -> StageDesc:
+    """``shape`` is any object with hidden / n_q_heads / n_kv_heads / head_dim / ffn /
+    rms_eps / rope_base / kv_block_size attributes."""
+    return StageDesc(layer_begin, layer_end, shape.hidden, shape.n_q_heads, shape.n_kv_heads,
+                     shape.head_dim, shape.ffn, shape.rms_eps, shape.rope_base, shape.kv_block_size)
+
+
+@dataclass
+class KVCache:
+    """A stage's paged cache: ``pool`` is a bf16/int16 CUDA tensor of logical shape
+    [layers][blocks][2][Hkv][16][D]; ``block_table`` int32 CUDA [num_seqs][max_blocks]."""
+    pool: torch.Tensor
+    layer_begin: int
+    layer_end: int
+    block_table: torch.Tensor
+
+    def c_pool(self) -> KvPool:
+        assert self.pool.is_cuda and self.pool.is_contiguous() and self.pool.element_size() == 2
+        assert self.pool.shape[0] == self.layer_end - self.layer_begin
+        return KvPool(self.pool.data_ptr(), self.pool.shape[1], self.layer_begin, self.layer_end)
+
+    def c_view(self, keep: list) -> KvView:
+        assert self.block_table.is_cuda and self.block_table.dtype == torch.int32 and self.block_table.is_contiguous()
+        p = self.c_pool(); keep.append(p)
+        return KvView(C.pointer(p), self.block_table.data_ptr(), self.block_table.shape[1])
+
+
+class Stage:
+    """fxp_stage_create / fxp_stage_forward / fxp_stage_destroy."""
+
+    def __init__(self, shape, layer_begin: int, layer_end: int, layers: Sequence[Dict[str, torch.Tensor]]):
+        self.shape = shape
+        self.desc = make_desc(shape, layer_begin, layer_end)
+        n = layer_end - layer_begin
+        if len(layers) != n:
+            raise ValueError("one weight dict per layer")
+        arr = (LayerWeights * n)()
+        for k, lw in enumerate(layers):
+            for name in LAYER_TENSORS:
+                t = lw[name]
+                assert t.is_cuda and t.is_contiguous() and t.element_size() == 2, name
+                setattr(arr[k], name, t.data_ptr())
+        nbytes = lib().fxp_stage_weight_arena_bytes(C.byref(self.desc))
+        if nbytes == 0:
+            raise FxpError(FXP_EINVAL, lib().fxp_last_error().decode())
+        self.arena = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        handle = C.c_void_p()
+        _check(lib().fxp_stage_create(C.byref(self.desc), arr, self.arena.data_ptr(), nbytes, _stream(), C.byref(handle)))
+        self.handle = handle
+        self._ws: Optional[torch.Tensor] = None
+
+    def close(self) -> None:
+        if getattr(self, "handle", None):
+            lib().fxp_stage_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def workspace_bytes(self, max_tokens: int, max_seqs: int, max_blocks_per_seq: int) -> int:
+        return lib().fxp_stage_workspace_bytes(self.handle, max_tokens, max_seqs, max_blocks_per_seq)
+
+    def _workspace(self, nbytes: int) -> torch.Tensor:
+        if self._ws is None or self._ws.numel() < nbytes:
+            self._ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        return self._ws
+
+    def forward(self, cache: KVCache, cu_seqlens_q: torch.Tensor, ctx_lens: torch.Tensor, hidden_in: torch.Tensor,
+                max_q_len: int, hidden_out: Optional[torch.Tensor] = None,
+                probs: Optional[torch.Tensor] = None) -> torch.Tensor:
+        """One step.  ``hidden_in`` bf16 CUDA [T,H]; ``cu_seqlens_q`` int32 CUDA [B+1]; ``ctx_lens`` int32 CUDA [B].
+        ``probs`` (float32 CUDA [layers][T][Hq][stride]) switches to the debug entry point."""
+        T = hidden_in.shape[0]
+        B = ctx_lens.shape[0]
+        assert hidden_in.is_cuda and hidden_in.is_contiguous() and hidden_in.element_size() == 2
+        assert cu_seqlens_q.dtype == torch.int32 and ctx_lens.dtype == torch.int32
+        if hidden_out is None:
+            hidden_out = torch.empty_like(hidden_in)
+        pool = cache.c_pool()
+        batch = Batch(B, T, max_q_len, cache.block_table.shape[1], cu_seqlens_q.data_ptr(), ctx_lens.data_ptr(),
+                      cache.block_table.data_ptr())
+        nbytes = self.workspace_bytes(T, B, cache.block_table.shape[1])
+        ws = self._workspace(nbytes)
+        if probs is None:
+            _check(lib().fxp_stage_forward(self.handle, C.byref(pool), C.byref(batch), hidden_in.data_ptr(),
+                                           hidden_out.data_ptr(), ws.data_ptr(), ws.numel(), _stream()))
+        else:
+            assert probs.dtype == torch.float32 and probs.is_contiguous()
+            _check(lib().fxp_stage_forward_debug(self.handle, C.byref(pool), C.byref(batch), hidden_in.data_ptr(),
+                                                 hidden_out.data_ptr(), ws.data_ptr(), ws.numel(), probs.data_ptr(),
+                                                 probs.shape[-1], _stream()))
+        return hidden_out
+
+
+def kv_repartition(shape, src: Sequence[KVCache], dst: Sequence[KVCache], ctx_lens: torch.Tensor) -> None:
+    keep: list = []
+    desc = make_desc(shape, 0, 1)
+    s = (KvView * len(src))(*[v.c_view(keep) for v in src])
+    d = (KvView * len(dst))(*[v.c_view(keep) for v in dst])
+    assert ctx_lens.is_cuda and ctx_lens.dtype == torch.int32
+    _check(lib().fxp_kv_repartition(C.byref(desc), s, len(src), d, len(dst), ctx_lens.data_ptr(), ctx_lens.shape[0], _stream()))
+
+
+def kv_packed_bytes(shape, layer_begin: int, layer_end: int, ctx_lens_host) -> int:
+    import numpy as np
+    cl = np.ascontiguousarray(ctx_lens_host, dtype=np.int32)
+    desc = make_desc(shape, 0, 1)
+    return lib().fxp_kv_packed_bytes(C.byref(desc), layer_begin, layer_end, cl.ctypes.data, cl.shape[0])
+
+
+def kv_pack(shape, src: KVCache, layer_begin: int, layer_end: int, ctx_lens: torch.Tensor, packed: torch.Tensor) -> None:
+    keep: list = []
+    desc = make_desc(shape, 0, 1)
+    v = src.c_view(keep)
+    _check(lib().fxp_kv_pack(C.byref(desc), C.byref(v), layer_begin, layer_end, ctx_lens.data_ptr(), ctx_lens.shape[0],
+                             packed.data_ptr(), packed.numel() * packed.element_size(), _stream()))
+
+
+def kv_unpack(shape, packed: torch.Tensor, dst: KVCache, layer_begin: int, layer_end: int, ctx_lens: torch.Tensor) -> None:
+    keep: list = []
+    desc = make_desc(shape, 0, 1)
+    v = dst.c_view(keep)
+    _check(lib().fxp_kv_unpack(C.byref(desc), packed.data_ptr(), packed.numel() * packed.element_size(), C.byref(v),
+                               layer_begin, layer_end, ctx_lens.data_ptr(), ctx_lens.shape[0], _stream()))

@@ -1,0 +1,227 @@
+// Chunked-prefill attention over the paged cache: every new token of a sequence
+// attends causally to the cached prefix plus the new tokens up to itself (all of
+// which rope_kvwrite has already stored in the cache), flash-style with an
+// online softmax so no score matrix is materialised.
+//
+// This is a dense contraction, so both products run on the matrix cores
+// (v_mfma_f32_16x16x32_bf16), arranged so that no register shuffling is needed
+// between them:
+//   S^T[kv][q] = K[kv][:] . Q[q][:]      row operand K, column operand Q;
+//                                         the accumulator leaves each lane with
+//                                         4 consecutive kv of ONE query column;
+//   softmax over kv per query column: 4 in-lane values + 2 cross-lane steps;
+//   O^T[dim][q] += V^T[dim][kv] . P^T[kv][q]
+//                                         P^T in accumulator layout is already
+//                                         the column operand of the next MFMA
+//                                         (k slots 8c..8c+7 of lane group c are
+//                                         kv 4c..4c+3 of two 16-key sub-tiles);
+//                                         V^T comes from LDS, where the 64-key
+//                                         tile of V was stored transposed.
+// A workgroup is 4 waves x 16 query rows of one (sequence, query head); the
+// 64-key K and V tiles are staged once in LDS and shared by the 4 waves.
+// Probabilities enter the second product rounded to bf16; everything else is
+// float.  Rows of V past the sequence end are zeroed while staging so that a
+// zero probability never meets an uninitialised (possibly NaN) value.
+#include "kernels.h"
+#include "common.hip.h"
+#include <math.h>
+
+namespace fxp {
+
+constexpr int kPfThreads = 256;
+constexpr int kPfQPerWave = 16;
+constexpr int kPfQTile = 64;        // query rows per workgroup
+constexpr int kPfKvTile = 64;       // keys per LDS tile (4 cache blocks)
+
+template <int D, bool DEBUG>
+__global__ __launch_bounds__(kPfThreads) void attn_prefill_kernel(PrefillAttnArgs a)
+{
+    constexpr int KS = D / 32;                    // k-steps of the QK product
+    constexpr int DT = D / 16;                    // 16-dim tiles of the output
+    constexpr int kKPitch = D * 2 + 16;           // bytes per K row in LDS (conflict-free 16-byte reads)
+    constexpr int kVPitch = (kPfKvTile + 4) * 2;  // bytes per V^T row in LDS (8-byte aligned)
+    __shared__ __attribute__((aligned(16))) char s_k[kPfKvTile * kKPitch];
+    __shared__ __attribute__((aligned(16))) char s_vt[D * kVPitch];
+
+    const int qt = blockIdx.x, h = blockIdx.y, seq = blockIdx.z;
+    const int t0 = a.cu_seqlens_q[seq];
+    const int q_len = a.cu_seqlens_q[seq + 1] - t0;
+    if (qt * kPfQTile >= q_len) return;
+    const int ctx = a.ctx_lens[seq];
+    const int n_keys = ctx + q_len;
+    const int hk = h / (a.n_q_heads / a.n_kv_heads);
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int col = lane & 15, c = lane >> 4;
+
+    const int j0 = qt * kPfQTile + wave * kPfQPerWave;        // first query row of this wave
+    const int jq = j0 + col;                                   // this lane's query column
+    const int q_pos = ctx + jq;
+    const bool q_ok = jq < q_len;
+    const int wave_last_pos = ctx + min(j0 + kPfQPerWave - 1, q_len - 1);
+    const int wg_last_pos = ctx + min(qt * kPfQTile + kPfQTile - 1, q_len - 1);
+    const int n_tiles = wg_last_pos / kPfKvTile + 1;
+
+    // Q as column operand: lane holds Q[jq][32*ks + 8*c .. +7]
+    u32x4 qreg[KS];
+    {
+        const uint16_t *qp = a.q + ((int64_t)(t0 + min(jq, q_len - 1)) * a.n_q_heads + h) * D + c * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) qreg[ks] = ld16(qp + ks * 32);
+    }
+    f32x4_t o[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) o[dt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    float m_run = -INFINITY, l_run = 0.f;
+
+    const int64_t head_elems = (int64_t)kBlockTokens * D;
+    const int64_t unit_elems = 2 * (int64_t)a.n_kv_heads * head_elems;
+    const uint16_t *layer_base = a.pool + (int64_t)a.layer_local * a.num_blocks * unit_elems;
+    const int32_t *table = a.block_table + (int64_t)seq * a.max_blocks_per_seq;
+    constexpr int kChunksPerRow = D / 8;
+    constexpr int kChunksPerThread = kPfKvTile * kChunksPerRow / kPfThreads;
+
+    for (int tile = 0; tile < n_tiles; ++tile) {
+        const int kv0 = tile * kPfKvTile;
+        // ---- stage K (row-major, padded) and V (transposed) of keys kv0 .. kv0+63
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < kChunksPerThread; ++i) {
+            const int qd = i * kPfThreads + tid;
+            const int r = qd / kChunksPerRow, dc = qd % kChunksPerRow;
+            const int kv = kv0 + r;
+            u32x4 kvec = {0u, 0u, 0u, 0u}, vvec = {0u, 0u, 0u, 0u};
+            if (kv < n_keys) {
+                const int32_t phys = table[kv / kBlockTokens];
+                const uint16_t *kp = layer_base + (int64_t)phys * unit_elems + (int64_t)hk * head_elems
+                                     + (int64_t)(kv % kBlockTokens) * D + dc * 8;
+                kvec = ld16(kp);
+                vvec = ld16(kp + (int64_t)a.n_kv_heads * head_elems);
+            }
+            *reinterpret_cast<u32x4 *>(s_k + r * kKPitch + dc * 16) = kvec;
+            uint16_t *vt = reinterpret_cast<uint16_t *>(s_vt);
+            const int d0 = dc * 8;
+            const uint32_t w[4] = {vvec.x, vvec.y, vvec.z, vvec.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                vt[(d0 + 2 * e) * (kVPitch / 2) + r] = (uint16_t)(w[e] & 0xffffu);
+                vt[(d0 + 2 * e + 1) * (kVPitch / 2) + r] = (uint16_t)(w[e] >> 16);
+            }
+        }
+        __syncthreads();
+        if (kv0 > wave_last_pos) continue;          // whole tile is in this wave's future (wave-uniform)
+
+        // ---- S^T = K . Q^T for the 4 sub-tiles of 16 keys
+        float s[4][4];
+#pragma unroll
+        for (int st = 0; st < 4; ++st) {
+            f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const u32x4 kop = *reinterpret_cast<const u32x4 *>(s_k + (st * 16 + col) * kKPitch + ks * 64 + c * 16);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kop),
+                                                              __builtin_bit_cast(bf16x8_t, qreg[ks]), acc, 0, 0, 0);
+            }
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int kv = kv0 + st * 16 + 4 * c + v;
+                const float sv = acc[v] * a.scale_log2e;
+                s[st][v] = (kv <= q_pos) ? sv : -INFINITY;
+                if constexpr (DEBUG) {
+                    if (q_ok && kv <= q_pos)
+                        a.dbg_scores[((int64_t)(t0 + jq) * a.n_q_heads + h) * a.dbg_stride + kv] = sv;
+                }
+            }
+        }
+        // ---- online softmax per query column (lanes col, col+16, col+32, col+48)
+        float mx = m_run;
+#pragma unroll
+        for (int st = 0; st < 4; ++st)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) mx = fmaxf(mx, s[st][v]);
+        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float ms = (mx == -INFINITY) ? 0.f : mx;
+        const float alpha = __builtin_amdgcn_exp2f(m_run - ms);
+        m_run = mx;
+        float psum = 0.f;
+        u32x4 pop[2];                                 // P^T column operands for sub-tile pairs (0,1) and (2,3)
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            float p[8];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                p[v] = __builtin_amdgcn_exp2f(s[2 * u][v] - ms);
+                p[4 + v] = __builtin_amdgcn_exp2f(s[2 * u + 1][v] - ms);
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) psum += p[e];
+            pop[u] = u32x4{pack_bf16x2(p[0], p[1]), pack_bf16x2(p[2], p[3]), pack_bf16x2(p[4], p[5]), pack_bf16x2(p[6], p[7])};
+        }
+        psum += __shfl_xor(psum, 16, 64);
+        psum += __shfl_xor(psum, 32, 64);
+        l_run = l_run * alpha + psum;
+        // ---- O^T = O^T * alpha + V^T . P^T
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+            o[dt] *= alpha;
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                // row operand: dim 16*dt + col; k slots 8c..8c+3 = keys 32u+4c.., 8c+4.. = keys 32u+16+4c..
+                const char *vrow = s_vt + (dt * 16 + col) * kVPitch + (32 * u + 4 * c) * 2;
+                const u32x2 lo = *reinterpret_cast<const u32x2 *>(vrow);
+                const u32x2 hi = *reinterpret_cast<const u32x2 *>(vrow + 32);
+                const u32x4 vop = {lo.x, lo.y, hi.x, hi.y};
+                o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, vop),
+                                                                __builtin_bit_cast(bf16x8_t, pop[u]), o[dt], 0, 0, 0);
+            }
+        }
+    }
+
+    if (!q_ok) return;
+    const float inv = 1.f / l_run;
+    uint16_t *op = a.out + ((int64_t)(t0 + jq) * a.n_q_heads + h) * D + 4 * c;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+        const u32x2 w = {pack_bf16x2(o[dt][0] * inv, o[dt][1] * inv), pack_bf16x2(o[dt][2] * inv, o[dt][3] * inv)};
+        *reinterpret_cast<u32x2 *>(op + dt * 16) = w;
+    }
+    if constexpr (DEBUG) {
+        if (c == 0) {
+            float *ml = a.dbg_ml + ((int64_t)(t0 + jq) * a.n_q_heads + h) * 3;
+            ml[0] = m_run; ml[1] = l_run; ml[2] = __int_as_float(q_pos + 1);
+        }
+    }
+}
+
+// debug only: scores (log2 domain) -> probabilities, one workgroup per (token, head)
+__global__ void attn_probs_normalize_kernel(float *scores, const float *ml, int64_t stride)
+{
+    const int64_t row = blockIdx.x;
+    const float m = ml[row * 3], l = ml[row * 3 + 1];
+    const int n = __float_as_int(ml[row * 3 + 2]);
+    for (int r = threadIdx.x; r < n; r += blockDim.x)
+        scores[row * stride + r] = __builtin_amdgcn_exp2f(scores[row * stride + r] - m) / l;
+}
+
+template <int D>
+static hipError_t launch_d(const PrefillAttnArgs &a, hipStream_t stream)
+{
+    dim3 grid((a.max_q_len + kPfQTile - 1) / kPfQTile, a.n_q_heads, a.num_seqs);
+    if (a.dbg_scores) {
+        hipLaunchKernelGGL((attn_prefill_kernel<D, true>), grid, dim3(kPfThreads), 0, stream, a);
+        hipLaunchKernelGGL(attn_probs_normalize_kernel, dim3(a.num_tokens * a.n_q_heads), dim3(64), 0, stream,
+                           a.dbg_scores, a.dbg_ml, a.dbg_stride);
+    } else {
+        hipLaunchKernelGGL((attn_prefill_kernel<D, false>), grid, dim3(kPfThreads), 0, stream, a);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_attn_prefill(const PrefillAttnArgs &a, hipStream_t stream)
+{
+    if (a.head_dim == 128) return launch_d<128>(a, stream);
+    if (a.head_dim == 64) return launch_d<64>(a, stream);
+    return hipErrorInvalidValue;
+}
+
+}  // namespace fxp

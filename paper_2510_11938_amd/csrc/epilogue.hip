@@ -1,0 +1,221 @@
+// Row-wise kernels around the projections.  All are HBM/latency bound on tiny
+// rows, so each is one pass, 16-byte vectors, one workgroup per token row, and
+// each also performs the fixed-order reduction of the split-K partial sums when
+// it follows a skinny projection (so no separate reduce launch exists):
+//   rmsnorm            n = x * rsqrt(mean(x^2) + eps) * g
+//   qkv_rope_kvwrite   rotary embedding of q and k at the token's position,
+//                      q -> bf16 buffer, rotated k and raw v -> paged cache
+//   resid_norm         h = x + proj ; optionally n = rmsnorm(h) for the next block
+//   swiglu             a = silu(gate) * up
+// Sums are float; every value that leaves a kernel is rounded once to bf16.
+#include "kernels.h"
+#include "common.hip.h"
+
+namespace fxp {
+
+constexpr int kRowThreads = 256;
+
+__device__ __forceinline__ float block_sum(float v, float *red)
+{
+    v = wave_sum(v);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    __syncthreads();
+    if (lane == 0) red[wave] = v;
+    __syncthreads();
+    float t = 0.f;
+#pragma unroll
+    for (int w = 0; w < kRowThreads / 64; ++w) t += red[w];
+    return t;
+}
+
+__device__ __forceinline__ void unpack8(const u32x4 v, float (&f)[8])
+{
+    f[0] = bf16_lo(v.x); f[1] = bf16_hi(v.x); f[2] = bf16_lo(v.y); f[3] = bf16_hi(v.y);
+    f[4] = bf16_lo(v.z); f[5] = bf16_hi(v.z); f[6] = bf16_lo(v.w); f[7] = bf16_hi(v.w);
+}
+__device__ __forceinline__ u32x4 pack8(const float (&f)[8])
+{
+    return u32x4{pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]), pack_bf16x2(f[6], f[7])};
+}
+// sum over the S split-K slices of 8 consecutive columns of row t, in slice order
+__device__ __forceinline__ void partial8(const float *P, int S, int64_t slice_stride, int64_t off, float (&f)[8])
+{
+#pragma unroll
+    for (int e = 0; e < 8; ++e) f[e] = 0.f;
+    for (int s = 0; s < S; ++s) {
+        const f32x4_t a = *reinterpret_cast<const f32x4_t *>(P + s * slice_stride + off);
+        const f32x4_t b = *reinterpret_cast<const f32x4_t *>(P + s * slice_stride + off + 4);
+        f[0] += a[0]; f[1] += a[1]; f[2] += a[2]; f[3] += a[3];
+        f[4] += b[0]; f[5] += b[1]; f[6] += b[2]; f[7] += b[3];
+    }
+}
+
+// ---------------------------------------------------------------- rmsnorm
+__global__ __launch_bounds__(kRowThreads) void rmsnorm_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ g,
+                                                              uint16_t *__restrict__ out, int H, float eps)
+{
+    __shared__ float red[kRowThreads / 64];
+    const int64_t row = (int64_t)blockIdx.x * H;
+    float ss = 0.f;
+    for (int c = threadIdx.x; c < H / 8; c += kRowThreads) {
+        float f[8];
+        unpack8(ld16(x + row + c * 8), f);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ss += f[e] * f[e];
+    }
+    const float rstd = rsqrtf(block_sum(ss, red) / (float)H + eps);
+    for (int c = threadIdx.x; c < H / 8; c += kRowThreads) {
+        float f[8], gg[8];
+        unpack8(ld16(x + row + c * 8), f);
+        unpack8(ld16(g + c * 8), gg);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) f[e] = f[e] * rstd * gg[e];
+        st16(out + row + c * 8, pack8(f));
+    }
+}
+
+hipError_t launch_rmsnorm(const void *x, const void *g, void *out, int T, int H, float eps, hipStream_t stream)
+{
+    hipLaunchKernelGGL(rmsnorm_kernel, dim3(T), dim3(kRowThreads), 0, stream, static_cast<const uint16_t *>(x),
+                       static_cast<const uint16_t *>(g), static_cast<uint16_t *>(out), H, eps);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- residual (+ norm)
+__global__ __launch_bounds__(kRowThreads) void resid_norm_kernel(ResidNormArgs a)
+{
+    __shared__ float red[kRowThreads / 64];
+    const int t = blockIdx.x;
+    const int64_t row = (int64_t)t * a.H;
+    float ss = 0.f;
+    for (int c = threadIdx.x; c < a.H / 8; c += kRowThreads) {
+        float f[8], p[8];
+        unpack8(ld16(a.x + row + c * 8), f);
+        partial8(a.P, a.S, (int64_t)a.T * a.H, row + c * 8, p);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) f[e] += p[e];
+        const u32x4 hv = pack8(f);
+        st16(a.h + row + c * 8, hv);
+        unpack8(hv, f);                     // the norm sees the rounded hidden state, as the next stage would
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ss += f[e] * f[e];
+    }
+    if (!a.g) return;
+    const float rstd = rsqrtf(block_sum(ss, red) / (float)a.H + a.eps);
+    for (int c = threadIdx.x; c < a.H / 8; c += kRowThreads) {
+        float f[8], gg[8];
+        unpack8(ld16(a.h + row + c * 8), f);    // written by this same thread above
+        unpack8(ld16(a.g + c * 8), gg);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) f[e] = f[e] * rstd * gg[e];
+        st16(a.n + row + c * 8, pack8(f));
+    }
+}
+
+hipError_t launch_resid_norm(const ResidNormArgs &a, hipStream_t stream)
+{
+    hipLaunchKernelGGL(resid_norm_kernel, dim3(a.T), dim3(kRowThreads), 0, stream, a);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- SwiGLU
+// Gate and up rows were interleaved in 16-row tiles when the weights were
+// packed: projection column 32*(f/16) + f%16 is gate row f, +16 is up row f.
+__global__ __launch_bounds__(kRowThreads) void swiglu_kernel(SwigluArgs a)
+{
+    const int t = blockIdx.x;
+    const int64_t prow = (int64_t)t * 2 * a.F;
+    for (int c = threadIdx.x; c < a.F / 8; c += kRowThreads) {
+        const int f0 = c * 8;
+        const int64_t col = 32 * (f0 / 16) + (f0 % 16);
+        float gt[8], up[8];
+        partial8(a.P, a.S, (int64_t)a.T * 2 * a.F, prow + col, gt);
+        partial8(a.P, a.S, (int64_t)a.T * 2 * a.F, prow + col + 16, up);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) gt[e] = gt[e] / (1.f + __expf(-gt[e])) * up[e];
+        st16(a.out + (int64_t)t * a.ld_out + f0, pack8(gt));
+    }
+}
+
+hipError_t launch_swiglu(const SwigluArgs &a, hipStream_t stream)
+{
+    hipLaunchKernelGGL(swiglu_kernel, dim3(a.T), dim3(kRowThreads), 0, stream, a);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- RoPE + cache append
+// One workgroup per token.  Threads 0..D/2-1 first evaluate the rotation angles
+// of the token's position in double (position * base^(-2d/D) reaches thousands of
+// radians; float would lose the low bits before the range reduction).
+template <bool FROM_PARTIAL>
+__global__ __launch_bounds__(kRowThreads) void qkv_rope_kvwrite_kernel(RopeArgs a)
+{
+    __shared__ float cs[128], sn[128];      // D/2 <= 128
+    __shared__ int s_seq, s_pos;
+    const int t = blockIdx.x;
+    const int D = a.head_dim, half = D / 2;
+    if (threadIdx.x == 0) {
+        // sequence that owns token t: cu[seq] <= t < cu[seq+1]
+        int lo = 0, hi = a.num_seqs;
+        while (hi - lo > 1) { const int mid = (lo + hi) >> 1; if (a.cu_seqlens_q[mid] <= t) lo = mid; else hi = mid; }
+        s_seq = lo;
+        s_pos = a.ctx_lens[lo] + (t - a.cu_seqlens_q[lo]);
+    }
+    __syncthreads();
+    const int seq = s_seq, pos = s_pos;
+    if (threadIdx.x < half) {
+        const double ang = (double)pos * pow((double)a.rope_base, -2.0 * (double)threadIdx.x / (double)D);
+        cs[threadIdx.x] = (float)cos(ang);
+        sn[threadIdx.x] = (float)sin(ang);
+    }
+    __syncthreads();
+
+    const int Nq = a.n_q_heads * D, Nkv = a.n_kv_heads * D, Nall = Nq + 2 * Nkv;
+    const int64_t src_row = (int64_t)t * Nall;
+    const int32_t phys = a.block_table[(int64_t)seq * a.max_blocks_per_seq + pos / kBlockTokens];
+    const int slot = pos % kBlockTokens;
+    // cache row of (kv, head): ((((layer*num_blocks + phys)*2 + kv)*Hkv + head)*16 + slot)*D
+    const int64_t blk = ((int64_t)a.layer_local * a.num_blocks + phys) * 2;
+
+    auto fetch8 = [&](int64_t col, float (&f)[8]) {
+        if constexpr (FROM_PARTIAL) partial8(a.P, a.S, (int64_t)a.T * Nall, src_row + col, f);
+        else unpack8(ld16(a.qkv + src_row + col), f);
+    };
+
+    // rotated heads: q heads then k heads, 8 rotation pairs per thread-step
+    const int chunks_per_head = half / 8;
+    const int n_rot = (a.n_q_heads + a.n_kv_heads) * chunks_per_head;
+    for (int c = threadIdx.x; c < n_rot; c += kRowThreads) {
+        const int head = c / chunks_per_head, d0 = (c % chunks_per_head) * 8;
+        float lo[8], hi[8], rl[8], rh[8];
+        fetch8((int64_t)head * D + d0, lo);
+        fetch8((int64_t)head * D + d0 + half, hi);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float co = cs[d0 + e], si = sn[d0 + e];
+            rl[e] = lo[e] * co - hi[e] * si;
+            rh[e] = hi[e] * co + lo[e] * si;
+        }
+        uint16_t *dst;
+        if (head < a.n_q_heads) dst = a.q_out + (int64_t)t * Nq + (int64_t)head * D;
+        else dst = a.pool + (((blk + 0) * a.n_kv_heads + (head - a.n_q_heads)) * kBlockTokens + slot) * D;
+        st16(dst + d0, pack8(rl));
+        st16(dst + d0 + half, pack8(rh));
+    }
+    // v heads: plain copy into the cache
+    for (int c = threadIdx.x; c < Nkv / 8; c += kRowThreads) {
+        const int head = (c * 8) / D, d0 = (c * 8) % D;
+        float f[8];
+        fetch8((int64_t)Nq + Nkv + c * 8, f);
+        st16(a.pool + (((blk + 1) * a.n_kv_heads + head) * kBlockTokens + slot) * D + d0, pack8(f));
+    }
+}
+
+hipError_t launch_qkv_rope_kvwrite(const RopeArgs &a, hipStream_t stream)
+{
+    if (a.P) hipLaunchKernelGGL(qkv_rope_kvwrite_kernel<true>, dim3(a.T), dim3(kRowThreads), 0, stream, a);
+    else hipLaunchKernelGGL(qkv_rope_kvwrite_kernel<false>, dim3(a.T), dim3(kRowThreads), 0, stream, a);
+    return hipGetLastError();
+}
+
+}  // namespace fxp

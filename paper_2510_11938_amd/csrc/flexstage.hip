@@ -1,0 +1,508 @@
+// C ABI of the library (include/flexstage.h): argument validation, the stage
+// handle, workspace carving and the per-layer launch sequence.  All arithmetic
+// is in the kernels; this file only decides which kernel runs on which buffer.
+#include "../../include/flexstage.h"
+#include "kernels.h"
+
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+#include <new>
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int hip_fail(hipError_t e, const char *what)
+{
+    return fail(FXP_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline int k_steps(int K) { return (K + 63) / 64 * 2; }                   // 32-wide steps, K padded to 64
+inline size_t packed_bytes(int N, int K) { return (size_t)(N / 16) * k_steps(K) * 1024; }
+
+constexpr int kSkinnyMaxTokens = 128;
+
+int check_desc(const fxp_stage_desc *d)
+{
+    if (!d) return fail(FXP_EINVAL, "stage descriptor is null");
+    if (d->layer_begin < 0 || d->layer_end <= d->layer_begin) return fail(FXP_EINVAL, "bad layer range [%d,%d)", d->layer_begin, d->layer_end);
+    if (d->kv_block_size != 16) return fail(FXP_EINVAL, "kv_block_size must be 16 (got %d)", d->kv_block_size);
+    if (d->head_dim != 64 && d->head_dim != 128) return fail(FXP_EINVAL, "head_dim must be 64 or 128 (got %d)", d->head_dim);
+    if (d->n_kv_heads <= 0 || d->n_q_heads <= 0 || d->n_q_heads % d->n_kv_heads)
+        return fail(FXP_EINVAL, "n_q_heads (%d) must be a positive multiple of n_kv_heads (%d)", d->n_q_heads, d->n_kv_heads);
+    if (!fxp::decode_attn_supported(d->head_dim, d->n_q_heads / d->n_kv_heads))
+        return fail(FXP_EINVAL, "query heads per kv head must be 1, 2, 4 or 8 (got %d)", d->n_q_heads / d->n_kv_heads);
+    if (d->hidden <= 0 || d->hidden % 16 || d->ffn <= 0 || d->ffn % 16)
+        return fail(FXP_EINVAL, "hidden (%d) and ffn (%d) must be positive multiples of 16", d->hidden, d->ffn);
+    if (!(d->rms_eps >= 0.f) || !(d->rope_base > 1.f)) return fail(FXP_EINVAL, "bad rms_eps or rope_base");
+    return FXP_OK;
+}
+
+// KV geometry checks shared by the repartition calls (only these fields are read)
+int check_kv_geom(const fxp_stage_desc *d)
+{
+    if (!d) return fail(FXP_EINVAL, "stage descriptor is null");
+    if (d->kv_block_size != 16) return fail(FXP_EINVAL, "kv_block_size must be 16 (got %d)", d->kv_block_size);
+    if (d->n_kv_heads <= 0 || d->head_dim <= 0 || d->head_dim % 8)
+        return fail(FXP_EINVAL, "bad kv geometry: n_kv_heads %d head_dim %d", d->n_kv_heads, d->head_dim);
+    return FXP_OK;
+}
+
+struct LayerRecord {           // offsets into one layer's contiguous record in the arena
+    size_t wqkv, wo, wgu, wd, g_attn, g_ffn, bytes;
+};
+
+LayerRecord layer_record(const fxp_stage_desc &d)
+{
+    LayerRecord r;
+    const int Nqkv = (d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim, Nq = d.n_q_heads * d.head_dim;
+    size_t at = 0;
+    r.wqkv = at; at += align_up(packed_bytes(Nqkv, d.hidden), 256);
+    r.wo = at;   at += align_up(packed_bytes(d.hidden, Nq), 256);
+    r.wgu = at;  at += align_up(packed_bytes(2 * d.ffn, d.hidden), 256);
+    r.wd = at;   at += align_up(packed_bytes(d.hidden, d.ffn), 256);
+    r.g_attn = at; at += align_up((size_t)d.hidden * 2, 256);
+    r.g_ffn = at;  at += align_up((size_t)d.hidden * 2, 256);
+    r.bytes = at;
+    return r;
+}
+
+int device_cus()
+{
+    static int cus = 0;
+    if (!cus) {
+        int dev = 0;
+        hipDeviceProp_t p;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&p, dev) == hipSuccess) cus = p.multiProcessorCount;
+        if (cus <= 0) cus = 256;
+    }
+    return cus;
+}
+
+int env_int(const char *name, int dflt)
+{
+    const char *v = getenv(name);
+    return (v && *v) ? atoi(v) : dflt;
+}
+
+// Split-K factor of a skinny projection: enough workgroups to cover the chip a
+// few times over, at least 8 k-steps per split.  Depends on shapes only.
+int choose_split(int N, int K, int M)
+{
+    const int forced = env_int("FXP_SKINNY_SPLIT", 0);
+    const int ks = k_steps(K);
+    const int wgs_n = (N + fxp::skinny_rows_per_wg(M) - 1) / fxp::skinny_rows_per_wg(M);
+    int s = forced > 0 ? forced : (env_int("FXP_SKINNY_TARGET_WGS", 1024) + wgs_n - 1) / wgs_n;
+    const int max_s = ks / 8 > 0 ? ks / 8 : 1;
+    if (s > max_s) s = max_s;
+    if (s < 1) s = 1;
+    return s;
+}
+
+}  // namespace
+
+struct fxp_stage {
+    fxp_stage_desc d;
+    int n_layers;
+    char *arena;
+    LayerRecord rec;
+};
+
+namespace {
+
+struct Workspace {
+    uint16_t *x[2], *n, *q, *qkv, *o, *h, *a;
+    float *P, *part_acc, *part_ml, *dbg_ml;
+    int max_splits;
+    size_t bytes;
+};
+
+Workspace carve(const fxp_stage_desc &d, int T, int B, int max_blocks, char *base)
+{
+    Workspace w;
+    size_t at = 0;
+    auto take = [&](size_t bytes) { char *p = base ? base + at : nullptr; at += align_up(bytes, 256); return p; };
+    const int H = d.hidden, Nq = d.n_q_heads * d.head_dim, Nall = (d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim, F = d.ffn;
+    const size_t t = (size_t)(T > 0 ? T : 1);
+    w.x[0] = (uint16_t *)take(t * H * 2);
+    w.x[1] = (uint16_t *)take(t * H * 2);
+    w.n = (uint16_t *)take(t * H * 2);
+    w.h = (uint16_t *)take(t * H * 2);
+    w.q = (uint16_t *)take(t * Nq * 2);
+    w.o = (uint16_t *)take(t * Nq * 2);
+    w.a = (uint16_t *)take(t * F * 2);
+    w.qkv = (uint16_t *)take(T > kSkinnyMaxTokens ? t * Nall * 2 : 0);
+    const int Ms = T < kSkinnyMaxTokens ? (T > 0 ? T : 1) : kSkinnyMaxTokens;
+    size_t pmax = 0;
+    const int shapes[4][2] = {{Nall, H}, {H, Nq}, {2 * F, H}, {H, F}};
+    for (auto &s : shapes) {
+        // the split factor depends on the row-tile configuration chosen for M: size for the larger one
+        const int s_lo = choose_split(s[0], s[1], 16), s_hi = choose_split(s[0], s[1], kSkinnyMaxTokens);
+        const size_t b = (size_t)(s_lo > s_hi ? s_lo : s_hi) * Ms * s[0] * 4;
+        if (b > pmax) pmax = b;
+    }
+    w.P = (float *)take(pmax);
+    w.max_splits = (int)(((size_t)max_blocks * 16 + fxp::kDecodeSplitTokens - 1) / fxp::kDecodeSplitTokens);
+    if (w.max_splits < 1) w.max_splits = 1;
+    const size_t rows = (size_t)(B > 0 ? B : 1) * d.n_q_heads * w.max_splits;
+    w.part_acc = (float *)take(rows * d.head_dim * 4);
+    w.part_ml = (float *)take(rows * 2 * 4);
+    w.dbg_ml = (float *)take(t * d.n_q_heads * 3 * 4);
+    w.bytes = at;
+    return w;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *fxp_last_error(void) { return g_err; }
+const char *fxp_version(void) { return "flexstage 0.1 (gfx950)"; }
+
+size_t fxp_stage_weight_arena_bytes(const fxp_stage_desc *desc)
+{
+    if (check_desc(desc) != FXP_OK) return 0;
+    return layer_record(*desc).bytes * (size_t)(desc->layer_end - desc->layer_begin);
+}
+
+int fxp_stage_create(const fxp_stage_desc *desc, const fxp_layer_weights *layers, void *weight_arena,
+                     size_t weight_arena_bytes, void *hip_stream, fxp_stage **out)
+{
+    if (int rc = check_desc(desc)) return rc;
+    if (!layers || !weight_arena || !out) return fail(FXP_EINVAL, "null argument to fxp_stage_create");
+    if ((uintptr_t)weight_arena % 256) return fail(FXP_EINVAL, "weight arena must be 256-byte aligned");
+    const fxp_stage_desc &d = *desc;
+    const int L = d.layer_end - d.layer_begin;
+    const LayerRecord rec = layer_record(d);
+    if (weight_arena_bytes < rec.bytes * (size_t)L)
+        return fail(FXP_ENOSPC, "weight arena too small: %zu < %zu", weight_arena_bytes, rec.bytes * (size_t)L);
+    hipStream_t st = (hipStream_t)hip_stream;
+    const int H = d.hidden, D = d.head_dim, Nq = d.n_q_heads * D, Nkv = d.n_kv_heads * D, F = d.ffn;
+    for (int l = 0; l < L; ++l) {
+        const fxp_layer_weights &w = layers[l];
+        if (!w.g_attn || !w.wq || !w.wk || !w.wv || !w.wo || !w.g_ffn || !w.w_gate || !w.w_up || !w.w_down)
+            return fail(FXP_EINVAL, "layer %d has a null weight pointer", d.layer_begin + l);
+        char *base = (char *)weight_arena + rec.bytes * (size_t)l;
+        hipError_t e;
+        // q | k | v rows concatenated
+        if ((e = fxp::launch_weight_pack(w.wq, Nq, H, base + rec.wqkv, k_steps(H), 0, 1, st))) return hip_fail(e, "pack wq");
+        if ((e = fxp::launch_weight_pack(w.wk, Nkv, H, base + rec.wqkv, k_steps(H), Nq / 16, 1, st))) return hip_fail(e, "pack wk");
+        if ((e = fxp::launch_weight_pack(w.wv, Nkv, H, base + rec.wqkv, k_steps(H), (Nq + Nkv) / 16, 1, st))) return hip_fail(e, "pack wv");
+        if ((e = fxp::launch_weight_pack(w.wo, H, Nq, base + rec.wo, k_steps(Nq), 0, 1, st))) return hip_fail(e, "pack wo");
+        // gate and up rows interleaved in 16-row tiles
+        if ((e = fxp::launch_weight_pack(w.w_gate, F, H, base + rec.wgu, k_steps(H), 0, 2, st))) return hip_fail(e, "pack w_gate");
+        if ((e = fxp::launch_weight_pack(w.w_up, F, H, base + rec.wgu, k_steps(H), 1, 2, st))) return hip_fail(e, "pack w_up");
+        if ((e = fxp::launch_weight_pack(w.w_down, H, F, base + rec.wd, k_steps(F), 0, 1, st))) return hip_fail(e, "pack w_down");
+        if ((e = hipMemcpyAsync(base + rec.g_attn, w.g_attn, (size_t)H * 2, hipMemcpyDeviceToDevice, st))) return hip_fail(e, "copy g_attn");
+        if ((e = hipMemcpyAsync(base + rec.g_ffn, w.g_ffn, (size_t)H * 2, hipMemcpyDeviceToDevice, st))) return hip_fail(e, "copy g_ffn");
+    }
+    fxp_stage *s = new (std::nothrow) fxp_stage;
+    if (!s) return fail(FXP_ENOSPC, "out of host memory");
+    s->d = d; s->n_layers = L; s->arena = (char *)weight_arena; s->rec = rec;
+    *out = s;
+    return FXP_OK;
+}
+
+int fxp_stage_destroy(fxp_stage *stage)
+{
+    delete stage;
+    return FXP_OK;
+}
+
+size_t fxp_stage_workspace_bytes(const fxp_stage *stage, int32_t max_tokens, int32_t max_seqs, int32_t max_blocks_per_seq)
+{
+    if (!stage || max_tokens < 0 || max_seqs < 0 || max_blocks_per_seq < 0) { fail(FXP_EINVAL, "bad argument to fxp_stage_workspace_bytes"); return 0; }
+    return carve(stage->d, max_tokens, max_seqs, max_blocks_per_seq, nullptr).bytes;
+}
+
+static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_batch *batch, const void *hidden_in,
+                        void *hidden_out, void *workspace, size_t workspace_bytes, float *probs, int64_t probs_stride,
+                        void *hip_stream)
+{
+    if (!stage || !pool || !batch) return fail(FXP_EINVAL, "null argument to fxp_stage_forward");
+    const fxp_stage_desc &d = stage->d;
+    const int T = batch->num_tokens, B = batch->num_seqs;
+    if (T < 0 || B < 0) return fail(FXP_EINVAL, "negative batch size");
+    if (T == 0 || B == 0) return FXP_OK;
+    if (!hidden_in || !hidden_out || !workspace) return fail(FXP_EINVAL, "null buffer passed to fxp_stage_forward");
+    if (!batch->cu_seqlens_q || !batch->ctx_lens || !batch->block_table) return fail(FXP_EINVAL, "null batch table");
+    if (!pool->base || pool->num_blocks <= 0) return fail(FXP_EINVAL, "empty kv pool");
+    if (pool->layer_begin != d.layer_begin || pool->layer_end != d.layer_end)
+        return fail(FXP_EINVAL, "pool holds layers [%d,%d) but the stage is [%d,%d)", pool->layer_begin, pool->layer_end, d.layer_begin, d.layer_end);
+    if (batch->max_q_len < 1 || batch->max_q_len > T) return fail(FXP_EINVAL, "max_q_len %d out of range for %d tokens", batch->max_q_len, T);
+    if (batch->max_blocks_per_seq < 1) return fail(FXP_EINVAL, "max_blocks_per_seq must be positive");
+    if ((uintptr_t)workspace % 256) return fail(FXP_EINVAL, "workspace must be 256-byte aligned");
+    if (probs && probs_stride < 1) return fail(FXP_EINVAL, "probs_stride must be positive");
+    Workspace w = carve(d, T, B, batch->max_blocks_per_seq, (char *)workspace);
+    if (workspace_bytes < w.bytes) return fail(FXP_ENOSPC, "workspace too small: %zu < %zu", workspace_bytes, w.bytes);
+
+    hipStream_t st = (hipStream_t)hip_stream;
+    const int H = d.hidden, D = d.head_dim, Nq = d.n_q_heads * D, Nall = (d.n_q_heads + 2 * d.n_kv_heads) * D, F = d.ffn;
+    const bool skinny = T <= kSkinnyMaxTokens;
+    const bool decode = batch->max_q_len == 1 && T == B;
+    const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
+    hipError_t e;
+
+    auto project_skinny = [&](const char *wbase, const uint16_t *X, int N, int K, int ldx, int *S_out) -> hipError_t {
+        fxp::SkinnyArgs a;
+        a.W = (const uint16_t *)wbase; a.X = X; a.P = w.P;
+        a.M = T; a.N = N; a.K = K; a.KS = k_steps(K); a.NT = N / 16; a.ldx = ldx; a.S = choose_split(N, K, T);
+        *S_out = a.S;
+        return fxp::launch_gemm_skinny(a, st);
+    };
+    auto project_tiled = [&](const char *wbase, const uint16_t *X, int N, int K, int ldx, uint16_t *C, int ldc,
+                             const uint16_t *R, int epi) -> hipError_t {
+        fxp::TiledArgs a;
+        a.W = (const uint16_t *)wbase; a.X = X; a.R = R; a.C = C;
+        a.M = T; a.K = K; a.KS = k_steps(K); a.NT = N / 16; a.ldx = ldx; a.ldc = ldc; a.epilogue = epi;
+        return fxp::launch_gemm_tiled(a, st);
+    };
+
+    const uint16_t *x_cur = (const uint16_t *)hidden_in;
+    for (int ll = 0; ll < stage->n_layers; ++ll) {
+        const char *rec = stage->arena + stage->rec.bytes * (size_t)ll;
+        const uint16_t *g_attn = (const uint16_t *)(rec + stage->rec.g_attn), *g_ffn = (const uint16_t *)(rec + stage->rec.g_ffn);
+        const bool last = ll + 1 == stage->n_layers;
+        uint16_t *x_next = last ? (uint16_t *)hidden_out : w.x[ll & 1];
+        float *dbg = probs ? probs + (int64_t)ll * T * d.n_q_heads * probs_stride : nullptr;
+        int S = 1;
+
+        // attention norm (layers after the first get it from the previous layer's fused epilogue on the skinny path)
+        if (!skinny || ll == 0)
+            if ((e = fxp::launch_rmsnorm(x_cur, g_attn, w.n, T, H, d.rms_eps, st))) return hip_fail(e, "rmsnorm");
+
+        // q|k|v projection, rotary embedding, cache append
+        fxp::RopeArgs ra;
+        ra.P = nullptr; ra.qkv = nullptr; ra.S = 1;
+        if (skinny) {
+            if ((e = project_skinny(rec + stage->rec.wqkv, w.n, Nall, H, H, &S))) return hip_fail(e, "qkv projection");
+            ra.P = w.P; ra.S = S;
+        } else {
+            if ((e = project_tiled(rec + stage->rec.wqkv, w.n, Nall, H, H, w.qkv, Nall, nullptr, fxp::kEpiStore))) return hip_fail(e, "qkv projection");
+            ra.qkv = w.qkv;
+        }
+        ra.q_out = w.q; ra.pool = (uint16_t *)pool->base;
+        ra.cu_seqlens_q = batch->cu_seqlens_q; ra.ctx_lens = batch->ctx_lens; ra.block_table = batch->block_table;
+        ra.num_blocks = pool->num_blocks; ra.T = T; ra.num_seqs = B; ra.max_blocks_per_seq = batch->max_blocks_per_seq;
+        ra.layer_local = ll; ra.n_q_heads = d.n_q_heads; ra.n_kv_heads = d.n_kv_heads; ra.head_dim = D; ra.rope_base = d.rope_base;
+        if ((e = fxp::launch_qkv_rope_kvwrite(ra, st))) return hip_fail(e, "rope + kv append");
+
+        // attention
+        if (decode) {
+            fxp::DecodeAttnArgs aa;
+            aa.q = w.q; aa.pool = (const uint16_t *)pool->base; aa.ctx_lens = batch->ctx_lens; aa.block_table = batch->block_table;
+            aa.part_acc = w.part_acc; aa.part_ml = w.part_ml; aa.out = w.o; aa.dbg_scores = dbg; aa.dbg_stride = probs_stride;
+            aa.num_blocks = pool->num_blocks; aa.num_seqs = B; aa.max_blocks_per_seq = batch->max_blocks_per_seq;
+            aa.max_splits = w.max_splits; aa.layer_local = ll; aa.n_q_heads = d.n_q_heads; aa.n_kv_heads = d.n_kv_heads;
+            aa.head_dim = D; aa.scale_log2e = scale_log2e;
+            if ((e = fxp::launch_attn_decode(aa, st))) return hip_fail(e, "decode attention");
+        } else {
+            fxp::PrefillAttnArgs pa;
+            pa.q = w.q; pa.pool = (const uint16_t *)pool->base; pa.cu_seqlens_q = batch->cu_seqlens_q; pa.ctx_lens = batch->ctx_lens;
+            pa.block_table = batch->block_table; pa.out = w.o; pa.dbg_scores = dbg; pa.dbg_ml = w.dbg_ml; pa.dbg_stride = probs_stride;
+            pa.num_blocks = pool->num_blocks; pa.num_seqs = B; pa.num_tokens = T; pa.max_q_len = batch->max_q_len;
+            pa.max_blocks_per_seq = batch->max_blocks_per_seq; pa.layer_local = ll; pa.n_q_heads = d.n_q_heads;
+            pa.n_kv_heads = d.n_kv_heads; pa.head_dim = D; pa.scale_log2e = scale_log2e;
+            if ((e = fxp::launch_attn_prefill(pa, st))) return hip_fail(e, "prefill attention");
+        }
+
+        if (skinny) {
+            // output projection + residual, fused with the feed-forward norm
+            if ((e = project_skinny(rec + stage->rec.wo, w.o, H, Nq, Nq, &S))) return hip_fail(e, "output projection");
+            fxp::ResidNormArgs rn;
+            rn.x = x_cur; rn.P = w.P; rn.h = w.h; rn.g = g_ffn; rn.n = w.n; rn.T = T; rn.H = H; rn.S = S; rn.eps = d.rms_eps;
+            if ((e = fxp::launch_resid_norm(rn, st))) return hip_fail(e, "residual + norm");
+            // gate|up projection + SwiGLU
+            if ((e = project_skinny(rec + stage->rec.wgu, w.n, 2 * F, H, H, &S))) return hip_fail(e, "gate/up projection");
+            fxp::SwigluArgs sg;
+            sg.P = w.P; sg.out = w.a; sg.T = T; sg.F = F; sg.S = S; sg.ld_out = F;
+            if ((e = fxp::launch_swiglu(sg, st))) return hip_fail(e, "swiglu");
+            // down projection + residual, fused with the next layer's attention norm
+            if ((e = project_skinny(rec + stage->rec.wd, w.a, H, F, F, &S))) return hip_fail(e, "down projection");
+            rn.x = w.h; rn.P = w.P; rn.h = x_next; rn.S = S;
+            rn.g = last ? nullptr : (const uint16_t *)(rec + stage->rec.bytes + stage->rec.g_attn);
+            rn.n = w.n;
+            if ((e = fxp::launch_resid_norm(rn, st))) return hip_fail(e, "residual + norm");
+        } else {
+            if ((e = project_tiled(rec + stage->rec.wo, w.o, H, Nq, Nq, w.h, H, x_cur, fxp::kEpiResidual))) return hip_fail(e, "output projection");
+            if ((e = fxp::launch_rmsnorm(w.h, g_ffn, w.n, T, H, d.rms_eps, st))) return hip_fail(e, "rmsnorm");
+            if ((e = project_tiled(rec + stage->rec.wgu, w.n, 2 * F, H, H, w.a, F, nullptr, fxp::kEpiSwiglu))) return hip_fail(e, "gate/up projection");
+            if ((e = project_tiled(rec + stage->rec.wd, w.a, H, F, F, x_next, H, w.h, fxp::kEpiResidual))) return hip_fail(e, "down projection");
+        }
+        x_cur = x_next;
+    }
+    return FXP_OK;
+}
+
+int fxp_stage_forward(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_batch *batch, const void *hidden_in,
+                      void *hidden_out, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return forward_impl(stage, pool, batch, hidden_in, hidden_out, workspace, workspace_bytes, nullptr, 0, hip_stream);
+}
+
+int fxp_stage_forward_debug(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_batch *batch, const void *hidden_in,
+                            void *hidden_out, void *workspace, size_t workspace_bytes, float *probs,
+                            int64_t probs_stride, void *hip_stream)
+{
+    if (!probs) return fail(FXP_EINVAL, "probs is null");
+    return forward_impl(stage, pool, batch, hidden_in, hidden_out, workspace, workspace_bytes, probs, probs_stride, hip_stream);
+}
+
+// ------------------------------------------------------------------ KV repartition
+
+static int check_view(const fxp_kv_view *v, const char *what, int idx)
+{
+    if (!v->pool || !v->pool->base || !v->block_table) return fail(FXP_EINVAL, "%s view %d has a null pointer", what, idx);
+    if (v->pool->num_blocks <= 0 || v->max_blocks_per_seq <= 0) return fail(FXP_EINVAL, "%s view %d is empty", what, idx);
+    if (v->pool->layer_begin < 0 || v->pool->layer_end <= v->pool->layer_begin) return fail(FXP_EINVAL, "%s view %d has a bad layer range", what, idx);
+    return FXP_OK;
+}
+
+static int check_tiling(const fxp_kv_view *v, int n, const char *what)
+{
+    for (int i = 0; i < n; ++i) if (int rc = check_view(&v[i], what, i)) return rc;
+    for (int i = 1; i < n; ++i)
+        if (v[i].pool->layer_begin != v[i - 1].pool->layer_end)
+            return fail(FXP_EINVAL, "%s views do not tile a layer range (view %d starts at %d, previous ends at %d)", what, i,
+                        v[i].pool->layer_begin, v[i - 1].pool->layer_end);
+    return FXP_OK;
+}
+
+static fxp::KvMoveSide pool_side(const fxp_kv_view &v)
+{
+    fxp::KvMoveSide s;
+    s.base = (char *)v.pool->base; s.table = v.block_table; s.num_blocks = v.pool->num_blocks; s.limit_bytes = 0;
+    s.layer_base = v.pool->layer_begin; s.n_layers = v.pool->layer_end - v.pool->layer_begin; s.max_blocks_per_seq = v.max_blocks_per_seq;
+    return s;
+}
+
+static fxp::KvMoveSide packed_side(const void *buf, size_t bytes, int lb, int le)
+{
+    fxp::KvMoveSide s;
+    s.base = (char *)buf; s.table = nullptr; s.num_blocks = 0; s.limit_bytes = (int64_t)bytes;
+    s.layer_base = lb; s.n_layers = le - lb; s.max_blocks_per_seq = 0;
+    return s;
+}
+
+static int move_grid(const fxp::KvMoveArgs &a, int max_blocks_per_seq)
+{
+    const int64_t chunks = (a.unit_bytes + 16383) / 16384;
+    int64_t items = 0;
+    for (int j = 0; j < a.n_jobs; ++j)
+        items += (int64_t)a.num_seqs * max_blocks_per_seq * (a.jobs[j].layer_end - a.jobs[j].layer_begin) * chunks;
+    int64_t grid = (int64_t)device_cus() * env_int("FXP_MOVE_WGS_PER_CU", 8);
+    if (grid > items) grid = items;
+    return (int)(grid < 1 ? 1 : grid);
+}
+
+static int launch_moves(fxp::KvMoveArgs &a, int max_blocks_per_seq, hipStream_t st)
+{
+    if (a.n_jobs == 0) return FXP_OK;
+    hipError_t e = fxp::launch_kv_move(a, move_grid(a, max_blocks_per_seq), st);
+    if (e != hipSuccess) return hip_fail(e, "kv move");
+    return FXP_OK;
+}
+
+int fxp_kv_repartition(const fxp_stage_desc *desc, const fxp_kv_view *src, int32_t n_src, const fxp_kv_view *dst,
+                       int32_t n_dst, const int32_t *ctx_lens, int32_t num_seqs, void *hip_stream)
+{
+    if (int rc = check_kv_geom(desc)) return rc;
+    if (!src || !dst || n_src <= 0 || n_dst <= 0) return fail(FXP_EINVAL, "empty view list");
+    if (num_seqs < 0 || num_seqs > 16383) return fail(FXP_EINVAL, "num_seqs %d out of range [0,16383]", num_seqs);
+    if (int rc = check_tiling(src, n_src, "source")) return rc;
+    if (int rc = check_tiling(dst, n_dst, "destination")) return rc;
+    if (src[0].pool->layer_begin != dst[0].pool->layer_begin || src[n_src - 1].pool->layer_end != dst[n_dst - 1].pool->layer_end)
+        return fail(FXP_EINVAL, "source layers [%d,%d) and destination layers [%d,%d) differ", src[0].pool->layer_begin,
+                    src[n_src - 1].pool->layer_end, dst[0].pool->layer_begin, dst[n_dst - 1].pool->layer_end);
+    const int64_t unit = 2ll * desc->n_kv_heads * 16 * desc->head_dim * 2;
+    for (int s = 0; s < n_src; ++s)
+        for (int t = 0; t < n_dst; ++t) {
+            const char *sb = (const char *)src[s].pool->base, *db = (const char *)dst[t].pool->base;
+            const int64_t sbytes = unit * src[s].pool->num_blocks * (src[s].pool->layer_end - src[s].pool->layer_begin);
+            const int64_t dbytes = unit * dst[t].pool->num_blocks * (dst[t].pool->layer_end - dst[t].pool->layer_begin);
+            if (sb < db + dbytes && db < sb + sbytes) return fail(FXP_EINVAL, "source pool %d overlaps destination pool %d", s, t);
+        }
+    if (num_seqs == 0) return FXP_OK;
+    if (!ctx_lens) return fail(FXP_EINVAL, "ctx_lens is null");
+
+    fxp::KvMoveArgs a;
+    a.ctx_lens = ctx_lens; a.unit_bytes = unit; a.num_seqs = num_seqs; a.head_dim = desc->head_dim; a.n_jobs = 0;
+    int max_blocks = 0;
+    for (int t = 0; t < n_dst; ++t)
+        for (int s = 0; s < n_src; ++s) {
+            const int lb = src[s].pool->layer_begin > dst[t].pool->layer_begin ? src[s].pool->layer_begin : dst[t].pool->layer_begin;
+            const int le = src[s].pool->layer_end < dst[t].pool->layer_end ? src[s].pool->layer_end : dst[t].pool->layer_end;
+            if (lb >= le) continue;
+            if (a.n_jobs == fxp::kMaxMoveJobs) {
+                if (int rc = launch_moves(a, max_blocks, (hipStream_t)hip_stream)) return rc;
+                a.n_jobs = 0; max_blocks = 0;
+            }
+            fxp::KvMoveJob &j = a.jobs[a.n_jobs++];
+            j.src = pool_side(src[s]); j.dst = pool_side(dst[t]); j.layer_begin = lb; j.layer_end = le;
+            const int mb = src[s].max_blocks_per_seq < dst[t].max_blocks_per_seq ? src[s].max_blocks_per_seq : dst[t].max_blocks_per_seq;
+            if (mb > max_blocks) max_blocks = mb;
+        }
+    return launch_moves(a, max_blocks, (hipStream_t)hip_stream);
+}
+
+size_t fxp_kv_packed_bytes(const fxp_stage_desc *desc, int32_t layer_begin, int32_t layer_end,
+                           const int32_t *ctx_lens_host, int32_t num_seqs)
+{
+    if (check_kv_geom(desc) != FXP_OK) return 0;
+    if (layer_begin < 0 || layer_end <= layer_begin || num_seqs < 0 || (num_seqs > 0 && !ctx_lens_host)) {
+        fail(FXP_EINVAL, "bad argument to fxp_kv_packed_bytes");
+        return 0;
+    }
+    size_t blocks = 0;
+    for (int i = 0; i < num_seqs; ++i) blocks += (size_t)((ctx_lens_host[i] + 15) / 16);
+    return blocks * (size_t)(layer_end - layer_begin) * 2 * desc->n_kv_heads * 16 * desc->head_dim * 2;
+}
+
+static int pack_or_unpack(const fxp_stage_desc *desc, const fxp_kv_view *view, int lb, int le, const int32_t *ctx_lens,
+                          int num_seqs, void *packed, size_t packed_bytes, bool to_packed, void *hip_stream)
+{
+    if (int rc = check_kv_geom(desc)) return rc;
+    if (!view) return fail(FXP_EINVAL, "view is null");
+    if (int rc = check_view(view, to_packed ? "source" : "destination", 0)) return rc;
+    if (lb < view->pool->layer_begin || le > view->pool->layer_end || lb >= le)
+        return fail(FXP_EINVAL, "layers [%d,%d) are not inside the pool's [%d,%d)", lb, le, view->pool->layer_begin, view->pool->layer_end);
+    if (num_seqs < 0 || num_seqs > 16383) return fail(FXP_EINVAL, "num_seqs %d out of range [0,16383]", num_seqs);
+    if (num_seqs == 0) return FXP_OK;
+    if (!ctx_lens || !packed) return fail(FXP_EINVAL, "null buffer");
+    const int64_t unit = 2ll * desc->n_kv_heads * 16 * desc->head_dim * 2;
+    if (packed_bytes < (size_t)unit * (size_t)(le - lb)) return fail(FXP_ENOSPC, "packed buffer smaller than one block per layer");
+    fxp::KvMoveArgs a;
+    a.ctx_lens = ctx_lens; a.unit_bytes = unit; a.num_seqs = num_seqs; a.head_dim = desc->head_dim; a.n_jobs = 1;
+    fxp::KvMoveJob &j = a.jobs[0];
+    j.layer_begin = lb; j.layer_end = le;
+    if (to_packed) { j.src = pool_side(*view); j.dst = packed_side(packed, packed_bytes, lb, le); }
+    else           { j.src = packed_side(packed, packed_bytes, lb, le); j.dst = pool_side(*view); }
+    return launch_moves(a, view->max_blocks_per_seq, (hipStream_t)hip_stream);
+}
+
+int fxp_kv_pack(const fxp_stage_desc *desc, const fxp_kv_view *src, int32_t layer_begin, int32_t layer_end,
+                const int32_t *ctx_lens, int32_t num_seqs, void *packed, size_t packed_bytes, void *hip_stream)
+{
+    return pack_or_unpack(desc, src, layer_begin, layer_end, ctx_lens, num_seqs, packed, packed_bytes, true, hip_stream);
+}
+
+int fxp_kv_unpack(const fxp_stage_desc *desc, const void *packed, size_t packed_bytes, const fxp_kv_view *dst,
+                  int32_t layer_begin, int32_t layer_end, const int32_t *ctx_lens, int32_t num_seqs, void *hip_stream)
+{
+    return pack_or_unpack(desc, dst, layer_begin, layer_end, ctx_lens, num_seqs, const_cast<void *>(packed), packed_bytes, false, hip_stream);
+}
+
+}  // extern "C"

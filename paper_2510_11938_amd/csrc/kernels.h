@@ -1,0 +1,130 @@
+// Host-side declarations of the kernel launchers (one translation unit per
+// kernel family).  Internal to the library; the public ABI is include/flexstage.h.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace fxp {
+
+// ---------------------------------------------------------------- KV mover
+constexpr int kMaxMoveJobs = 8;
+
+// One end of a move.  table != nullptr: a paged pool addressed through a block
+// table; table == nullptr: the contiguous packed buffer.
+struct KvMoveSide {
+    char *base;
+    const int32_t *table;        // [num_seqs][max_blocks_per_seq] or nullptr
+    int64_t num_blocks;          // pool: physical blocks per layer
+    int64_t limit_bytes;         // packed: size of the buffer (0 = unchecked)
+    int32_t layer_base;          // model layer stored at index 0
+    int32_t n_layers;            // packed: layers in the buffer
+    int32_t max_blocks_per_seq;
+};
+struct KvMoveJob {
+    KvMoveSide src, dst;
+    int32_t layer_begin, layer_end;   // model layers this job moves
+};
+struct KvMoveArgs {
+    KvMoveJob jobs[kMaxMoveJobs];
+    const int32_t *ctx_lens;     // device [num_seqs]
+    int64_t unit_bytes;          // bytes of one (layer, block): 2 * Hkv * 16 * D * 2
+    int32_t n_jobs, num_seqs, head_dim;
+};
+hipError_t launch_kv_move(const KvMoveArgs &args, int grid, hipStream_t stream);
+
+// ---------------------------------------------------------------- weights
+// W[N][K] row-major bf16 -> packed[n_tile][k_step][lane][8] (k zero-padded to k_steps*32).
+hipError_t launch_weight_pack(const void *src, int N, int K, void *dst, int k_steps,
+                              int tile_offset, int tile_stride, hipStream_t stream);
+
+// ---------------------------------------------------------------- projections
+struct SkinnyArgs {
+    const uint16_t *W;     // packed weights
+    const uint16_t *X;     // token rows [M][ldx] bf16
+    float *P;              // partial sums [S][M][N]
+    int M, N, K, KS, NT, ldx, S;   // KS = padded K / 32, NT = N / 16
+};
+hipError_t launch_gemm_skinny(const SkinnyArgs &a, hipStream_t stream);
+int skinny_rows_per_wg(int M);
+
+enum { kEpiStore = 0, kEpiResidual = 1, kEpiSwiglu = 2 };
+struct TiledArgs {
+    const uint16_t *W;     // packed weights
+    const uint16_t *X;     // token rows [M][ldx] bf16
+    const uint16_t *R;     // residual [M][ldc] (kEpiResidual), may alias C
+    uint16_t *C;           // output [M][ldc] bf16
+    int M, K, KS, NT, ldx, ldc, epilogue;
+};
+hipError_t launch_gemm_tiled(const TiledArgs &a, hipStream_t stream);
+
+// ---------------------------------------------------------------- row-wise kernels
+hipError_t launch_rmsnorm(const void *x, const void *g, void *out, int T, int H, float eps, hipStream_t stream);
+
+struct ResidNormArgs {
+    const uint16_t *x;     // residual input [T][H]
+    const float *P;        // projection partial sums [S][T][H]
+    uint16_t *h;           // x + proj, bf16 [T][H] (may alias x)
+    const uint16_t *g;     // gain of the following norm, or nullptr
+    uint16_t *n;           // normed output [T][H] (when g)
+    int T, H, S;
+    float eps;
+};
+hipError_t launch_resid_norm(const ResidNormArgs &a, hipStream_t stream);
+
+struct SwigluArgs {
+    const float *P;        // gate|up partial sums [S][T][2F], rows interleaved in 16-tiles
+    uint16_t *out;         // [T][ld_out] bf16
+    int T, F, S, ld_out;
+};
+hipError_t launch_swiglu(const SwigluArgs &a, hipStream_t stream);
+
+struct RopeArgs {
+    const float *P;        // q|k|v partial sums [S][T][Nall], or nullptr
+    const uint16_t *qkv;   // q|k|v bf16 [T][Nall] (when P == nullptr)
+    uint16_t *q_out;       // rotated q [T][Hq*D] bf16
+    uint16_t *pool;        // stage KV pool
+    const int32_t *cu_seqlens_q, *ctx_lens, *block_table;
+    int64_t num_blocks;
+    int T, S, num_seqs, max_blocks_per_seq, layer_local;
+    int n_q_heads, n_kv_heads, head_dim;
+    float rope_base;
+};
+hipError_t launch_qkv_rope_kvwrite(const RopeArgs &a, hipStream_t stream);
+
+// ---------------------------------------------------------------- attention
+constexpr int kDecodeSplitTokens = 512;   // keys per workgroup of the decode kernel
+
+struct DecodeAttnArgs {
+    const uint16_t *q;     // [num_seqs][Hq][D] bf16 (rotated)
+    const uint16_t *pool;
+    const int32_t *ctx_lens, *block_table;
+    float *part_acc;       // [num_seqs][Hq][max_splits][D]
+    float *part_ml;        // [num_seqs][Hq][max_splits][2]
+    uint16_t *out;         // [num_seqs][Hq*D] bf16
+    float *dbg_scores;     // optional [num_seqs][Hq][dbg_stride]
+    int64_t dbg_stride;
+    int64_t num_blocks;
+    int num_seqs, max_blocks_per_seq, max_splits, layer_local;
+    int n_q_heads, n_kv_heads, head_dim;
+    float scale_log2e;     // log2(e) / sqrt(D)
+};
+bool decode_attn_supported(int head_dim, int group);
+hipError_t launch_attn_decode(const DecodeAttnArgs &a, hipStream_t stream);
+
+struct PrefillAttnArgs {
+    const uint16_t *q;     // [T][Hq][D] bf16 (rotated)
+    const uint16_t *pool;
+    const int32_t *cu_seqlens_q, *ctx_lens, *block_table;
+    uint16_t *out;         // [T][Hq*D] bf16
+    float *dbg_scores;     // optional [T][Hq][dbg_stride]
+    float *dbg_ml;         // optional [T][Hq][3]
+    int64_t dbg_stride;
+    int64_t num_blocks;
+    int num_seqs, num_tokens, max_q_len, max_blocks_per_seq, layer_local;
+    int n_q_heads, n_kv_heads, head_dim;
+    float scale_log2e;
+};
+hipError_t launch_attn_prefill(const PrefillAttnArgs &a, hipStream_t stream);
+
+}  // namespace fxp
