@@ -1,0 +1,205 @@
+#!/usr/bin/env python3
+"""Benchmark of the stage-forward / KV-repartition hot path on one MI355X.
+
+One step = one decode pass of the whole stage (Llama-2-7B-shaped, 4 layers,
+batch 32, contexts uniform in [512,4096], permuted block table) followed, as a
+separately timed leg, by the KV repartition of that stage's cache (4 layers ->
+2 + 2 into fresh permuted tables).  Inputs are synthetic, seeded, and resident
+in HBM before the timed region starts.
+
+Prints one JSON line: decode tokens/s as `value`, the repartition rate, the
+roofline of the dominant kernel (paged decode attention, HBM bound) measured
+with HIP events around each launch, and the CPU oracle timed on a bounded sample
+of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def read_traffic(path: str, kernel: str):
+    """HBM bytes per launch measured with rocprofv3 counters, if a summary was committed."""
+    try:
+        for line in open(path):
+            if line.startswith(f"traffic_bytes_per_launch[{kernel}]:"):
+                return float(line.split(":", 1)[1].split()[0])
+    except OSError:
+        pass
+    return None
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="C2", help="synthetic workload id (C2 is the headline configuration)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-seqs", type=int, default=4)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from concurrent.futures import ThreadPoolExecutor
+    from paper_2510_11938_amd import binding, synth
+
+    wl = synth.WORKLOADS[args.workload]
+    if wl.kind != "decode":
+        print("bench.py: the benchmark step is a decode step; pick a decode workload", file=sys.stderr)
+        return 2
+    ms, L, B = wl.shape, wl.n_layers, wl.num_seqs
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    def to_dev(bits):
+        return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(dev).view(torch.bfloat16)
+
+    # ---- inputs (seeded, synthetic) -------------------------------------------------
+    t_setup = time.time()
+    ctx = synth.draw_lengths(wl.length_dist, B, wl.seed)
+    table, nblk = synth.block_table(ctx + 1, 16, wl.seed)
+    w_bits = [synth.layer_weights(ms, wl.seed, l) for l in range(L)]
+    w_dev = [{k: to_dev(v) for k, v in lw.items()} for lw in w_bits]
+    stage = binding.Stage(ms, 0, L, w_dev)
+    torch.cuda.synchronize()
+    del w_dev                                            # the stage keeps its own re-tiled copy
+    pool_host = np.zeros((L, nblk, 2, ms.n_kv_heads, 16, ms.head_dim), dtype=np.uint16)
+
+    def fill(job):
+        i, l = job
+        synth.fill_pool_rows(pool_host, l, table[i], synth.cache_rows(ms, wl.seed, i, l, int(ctx[i])), 16)
+
+    with ThreadPoolExecutor(max_workers=16) as ex:
+        list(ex.map(fill, [(i, l) for i in range(B) for l in range(L)]))
+    cache = binding.KVCache(torch.from_numpy(pool_host.view(np.int16)).to(dev), 0, L,
+                            torch.from_numpy(table).to(dev))
+    hidden_bits = synth.hidden_states(B, ms.hidden, wl.seed)
+    x = to_dev(hidden_bits)
+    y = torch.empty_like(x)
+    cu = torch.arange(B + 1, dtype=torch.int32, device=dev)
+    cl = torch.from_numpy(ctx).to(dev)
+    setup_s = time.time() - t_setup
+
+    def step():
+        stage.forward(cache, cu, cl, x, 1, hidden_out=y)
+
+    # ---- decode: W warm-up steps, then exactly K timed steps -------------------------
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    tokens_per_s = B / (ms_per_step * 1e-3)
+
+    # ---- per-kernel durations: the same K steps again with an event pair around each launch
+    binding.profile_enable(True)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    prof = binding.profile_read()
+    binding.profile_enable(False)
+
+    n_keys = int((ctx.astype(np.int64) + 1).sum())
+    kv_bytes_per_token = 2 * ms.n_kv_heads * ms.head_dim * 2
+    attn_bytes = n_keys * kv_bytes_per_token                         # per launch = per layer
+    weight_bytes_layer = 2 * (ms.params_per_layer - 2 * ms.hidden)   # the four projections of one layer
+    kernels = {}
+    for name, rec in prof.items():
+        kernels[name] = {"avg_us": rec["ms"] * 1e3 / rec["launches"], "launches_per_step": rec["launches"] / args.steps}
+    attn_us = kernels["attn_decode"]["avg_us"]
+    attn_gbps = attn_bytes / (attn_us * 1e-6) / 1e9
+    skinny_us_layer = kernels["gemm_skinny"]["avg_us"] * 4
+    kernels["attn_decode"]["GBps"] = attn_gbps
+    kernels["gemm_skinny"]["weight_stream_GBps"] = weight_bytes_layer / (skinny_us_layer * 1e-6) / 1e9
+    ideal_ms = (L * weight_bytes_layer + L * attn_bytes) / (HBM_PEAK_GBPS * 1e9) * 1e3
+
+    # ---- KV repartition: the stage's cache re-split 4 -> 2 + 2 into fresh tables -------
+    half = L // 2
+    dst = []
+    for s, (a, b) in enumerate([(0, half), (half, L)]):
+        t, n = synth.block_table(ctx + 1, 16, wl.seed, salt=1 + s)
+        dst.append(binding.KVCache(torch.zeros((b - a, n, 2, ms.n_kv_heads, 16, ms.head_dim), dtype=torch.int16, device=dev),
+                                   a, b, torch.from_numpy(t).to(dev)))
+    moved_blocks = int(((ctx.astype(np.int64) + 15) // 16).sum())
+    move_bytes = 2 * moved_blocks * L * ms.block_elems * 2             # read + write
+    for _ in range(3):
+        binding.kv_repartition(ms, [cache], dst, cl)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = max(5, min(20, args.steps))
+    ev0.record()
+    for _ in range(reps):
+        binding.kv_repartition(ms, [cache], dst, cl)
+    ev1.record()
+    torch.cuda.synchronize()
+    move_ms = ev0.elapsed_time(ev1) / reps
+    move_gbps = move_bytes / (move_ms * 1e-3) / 1e9
+
+    out = {
+        "metric": "stage decode tokens/s (7B shape, 4 layers, B=32); KV repartition GB/s vs HBM",
+        "value": tokens_per_s, "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {ms.hidden}-hidden {ms.n_q_heads}/{ms.n_kv_heads}x{ms.head_dim} heads, ffn {ms.ffn}, "
+                               f"{L} layers, decode batch {B}, contexts {wl.length_dist}, kv block 16, permuted block table",
+                   "seed": wl.seed, "tokens_in_cache": int(ctx.sum())},
+        "hbm_ideal_ms_per_step": ideal_ms, "frac_of_hbm_ideal": ideal_ms / ms_per_step,
+        "kv_repartition": {"GBps": move_gbps, "ms": move_ms, "bytes_read_plus_written": move_bytes,
+                           "frac_of_hbm_peak": move_gbps / HBM_PEAK_GBPS, "split": f"[0,{L}) -> [0,{half}) + [{half},{L})"},
+        "roofline": {"kernel": "attn_decode_kernel", "bound": "hbm", "achieved": attn_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": attn_gbps / HBM_PEAK_GBPS,
+                     "traffic": read_traffic(os.path.join(ROOT, "profiles", "attn_decode_c2_pmc.txt"), "attn_decode_kernel"),
+                     "algorithmic_bytes_per_launch": attn_bytes, "avg_launch_us": attn_us},
+        "kernels": kernels,
+        "setup_s": setup_s,
+    }
+
+    # ---- the oracle on the host cores, on a bounded sample of the same workload ------
+    if not args.no_cpu_baseline:
+        import oracle
+        osh = oracle.Shape(ms.hidden, ms.n_q_heads, ms.n_kv_heads, ms.head_dim, ms.ffn, 16, ms.rms_eps, ms.rope_base)
+        wf = [{k: oracle.bf16_bits_to_f32(v) for k, v in lw.items()} for lw in w_bits]
+        sample = list(range(min(args.cpu_sample_seqs, B)))
+        nb = [(int(ctx[i]) + 16) // 16 for i in sample]
+        sub_table = np.full((len(sample), max(nb)), -1, dtype=np.int32)
+        blocks, at = [], 0
+        for r, i in enumerate(sample):
+            sub_table[r, : nb[r]] = np.arange(at, at + nb[r]); at += nb[r]
+            blocks.append(table[i, : nb[r]])
+        sub_pool = oracle.bf16_bits_to_f32(pool_host[:, np.concatenate(blocks)])
+        xs = oracle.bf16_bits_to_f32(hidden_bits[sample]).astype(np.float64)
+        t0 = time.perf_counter()
+        ref = oracle.stage_forward(osh, wf, sub_pool, np.arange(len(sample) + 1), ctx[sample], sub_table, xs)
+        cpu_s = time.perf_counter() - t0
+        got = synth.bf16_bits_to_f32(y[sample].view(torch.int16).cpu().numpy().view(np.uint16)).astype(np.float64)
+        rms = np.sqrt((ref ** 2).mean(axis=1, keepdims=True))
+        out["cpu_baseline"] = {"value": len(sample) / cpu_s, "unit": "tokens/s", "cores": oracle.num_threads(),
+                               "kind": "oracle",
+                               "sample": f"one decode step of the same stage for sequences {sample} of the batch "
+                                         f"(contexts {[int(ctx[i]) for i in sample]}), {cpu_s:.2f} s",
+                               "gpu_vs_oracle_rel_l2": float(np.sqrt(((got - ref) ** 2).sum(axis=1) / (ref ** 2).sum(axis=1)).max()),
+                               "gpu_vs_oracle_max_elem": float((np.abs(got - ref) / np.maximum(np.abs(ref), rms)).max())}
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

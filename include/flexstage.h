@@ -160,10 +160,12 @@ int    fxp_kv_repartition(const fxp_stage_desc *desc,
  * [layer_begin, layer_end) of ONE source view into a contiguous DEVICE buffer
  *   [sequence][layer - layer_begin][logical block][2: K,V][kv_head][slot][head_dim]
  * (invalid slots zero); unpack scatters such a buffer into ONE destination
- * view through its own table.  fxp_kv_packed_bytes takes the lengths from HOST
- * memory; pack/unpack return FXP_ENOSPC when packed_bytes is smaller than
- * max_total_blocks * (layers) * block bytes, where max_total_blocks is the
- * caller's bound on sum_i ceil(ctx_lens[i]/16) implied by packed_bytes. */
+ * view through its own table.  fxp_kv_packed_bytes computes the buffer size
+ * from lengths in HOST memory.  pack/unpack read the lengths on the device and
+ * cannot know the total on the host: `packed_bytes` is the size of the buffer
+ * the caller really has, and a (layer, block) unit that would not lie wholly
+ * inside it is skipped, so neither call ever touches memory past the buffer;
+ * FXP_ENOSPC is returned only when not even one block per layer fits. */
 size_t fxp_kv_packed_bytes(const fxp_stage_desc *desc, int32_t layer_begin, int32_t layer_end,
                            const int32_t *ctx_lens_host, int32_t num_seqs);
 int    fxp_kv_pack(const fxp_stage_desc *desc, const fxp_kv_view *src,
@@ -173,6 +175,22 @@ int    fxp_kv_pack(const fxp_stage_desc *desc, const fxp_kv_view *src,
 int    fxp_kv_unpack(const fxp_stage_desc *desc, const void *packed, size_t packed_bytes,
                      const fxp_kv_view *dst, int32_t layer_begin, int32_t layer_end,
                      const int32_t *ctx_lens, int32_t num_seqs, void *hip_stream);
+
+/* ---- per-kernel timing for benchmarks ---------------------------------------
+ * While enabled, every kernel launch the library makes is bracketed by a pair
+ * of HIP events recorded on the caller's stream (up to 8192 launches; later
+ * ones are not timed).  fxp_profile_enable(on) also clears what was recorded.
+ * fxp_profile_read waits for the recorded events and returns the summed
+ * duration and the launch count of one kernel class; classes are numbered
+ * 0 .. fxp_profile_num_classes()-1 and named by fxp_profile_class_name.
+ * Not thread-safe; the events perturb the stream slightly, so whole-step
+ * throughput is measured with profiling off. */
+int         fxp_profile_enable(int on);
+int         fxp_profile_num_classes(void);
+const char *fxp_profile_class_name(int kernel_class);
+int         fxp_profile_read(int kernel_class, double *total_ms, int64_t *launches);
+/* One recorded launch, in launch order; FXP_EINVAL once index is past the last record. */
+int         fxp_profile_read_launch(int index, int *kernel_class, double *ms);
 
 const char *fxp_last_error(void);
 const char *fxp_version(void);

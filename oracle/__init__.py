@@ -87,6 +87,10 @@ class Shape:
         return 2 * self.n_kv_heads * self.kv_block_size * self.head_dim
 
 
+def num_threads() -> int:
+    return int(lib().orc_num_threads())
+
+
 def _f64(a) -> np.ndarray:
     return np.ascontiguousarray(a, dtype=np.float64)
 

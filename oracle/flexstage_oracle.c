@@ -45,6 +45,19 @@
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* threads the parallel loops will use (for reporting the timed baseline) */
+int orc_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
 
 typedef struct {
     int32_t hidden, n_q_heads, n_kv_heads, head_dim, ffn, kv_block_size;

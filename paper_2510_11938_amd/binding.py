@@ -15,7 +15,8 @@ from typing import Dict, List, Optional, Sequence
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libflexstage.so")
+# FXP_LIBRARY may point at another build of the same library (kernel tuning experiments)
+LIB_PATH = os.environ.get("FXP_LIBRARY") or os.path.join(_HERE, "libflexstage.so")
 
 FXP_OK, FXP_EINVAL, FXP_ENOSPC, FXP_EHIP = 0, -1, -2, -3
 
@@ -23,6 +24,7 @@ EXPORTS = (
     "fxp_stage_weight_arena_bytes", "fxp_stage_create", "fxp_stage_destroy",
     "fxp_stage_workspace_bytes", "fxp_stage_forward", "fxp_stage_forward_debug",
     "fxp_kv_repartition", "fxp_kv_packed_bytes", "fxp_kv_pack", "fxp_kv_unpack",
+    "fxp_profile_enable", "fxp_profile_num_classes", "fxp_profile_class_name", "fxp_profile_read", "fxp_profile_read_launch",
     "fxp_last_error", "fxp_version",
 )
 
@@ -100,8 +102,37 @@ def lib() -> C.CDLL:
                                   C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
         l.fxp_kv_unpack.argtypes = [C.POINTER(StageDesc), C.c_void_p, C.c_size_t, C.POINTER(KvView), C.c_int32,
                                     C.c_int32, C.c_void_p, C.c_int32, C.c_void_p]
+        l.fxp_profile_class_name.restype = C.c_char_p
+        l.fxp_profile_class_name.argtypes = [C.c_int]
+        l.fxp_profile_read.argtypes = [C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+        l.fxp_profile_read_launch.argtypes = [C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_double)]
         _lib = l
     return _lib
+
+
+def profile_enable(on: bool) -> None:
+    _check(lib().fxp_profile_enable(1 if on else 0))
+
+
+def profile_launches() -> List[tuple]:
+    """[(kernel class name, ms)] of every recorded launch, in launch order."""
+    out, i = [], 0
+    cls, ms = C.c_int(), C.c_double()
+    while lib().fxp_profile_read_launch(i, C.byref(cls), C.byref(ms)) == FXP_OK:
+        out.append((lib().fxp_profile_class_name(cls.value).decode(), ms.value))
+        i += 1
+    return out
+
+
+def profile_read() -> Dict[str, Dict[str, float]]:
+    """{kernel class name: {"ms": summed duration, "launches": count}} for the launches recorded so far."""
+    out = {}
+    for k in range(lib().fxp_profile_num_classes()):
+        ms, n = C.c_double(), C.c_int64()
+        _check(lib().fxp_profile_read(k, C.byref(ms), C.byref(n)))
+        if n.value:
+            out[lib().fxp_profile_class_name(k).decode()] = {"ms": ms.value, "launches": n.value}
+    return out
 
 
 def _check(rc: int) -> None:

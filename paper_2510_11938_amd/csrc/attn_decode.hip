@@ -3,20 +3,26 @@
 //
 // Bound by streaming the cache from HBM (every cached K and V byte is read
 // exactly once per step, also with grouped query heads: the G query heads of a
-// KV head are handled by the same lanes).  Layout of the work:
-//   grid  = (context splits, kv heads, sequences); a split is 512 tokens, so
-//           long and short contexts give equal-sized workgroups;
-//   wave  : takes every 4th 16-token block of the split.  A block's K (and V)
-//           for one head is one contiguous 16*D*2-byte run; a wave load
-//           instruction covers 1 KiB of it: D/8 lanes per token row, 16 bytes
-//           (8 dims) per lane.  The q.k dot product is 8 FMAs per lane plus a
-//           log2(D/8)-step butterfly inside the row's lanes.
-//   softmax: each group of D/8 lanes keeps its own running (max, sum, acc[8])
-//           over the tokens it sees -- no cross-lane traffic in the loop; groups,
-//           waves (through LDS) and splits (second kernel) are merged afterwards,
-//           always in the same fixed order, so results are bit-reproducible.
-//   Two register buffers hold the next block's K and V while the current one is
-//   consumed.  Everything after the bf16 loads is float.
+// KV head are handled by the same lanes).  Contexts in a batch are ragged, so
+// the work is not cut per sequence but as one line:
+//   unit   = one 16-token cache block of one (sequence, kv head); all units of
+//            the batch are numbered (sequence, kv head, block);
+//   worker = one wavefront; worker w owns the units [w*U/W, (w+1)*U/W), so every
+//            worker streams the same number of blocks (+-1) whatever the length
+//            mix, and the whole grid starts and ends together.  The cut depends
+//            on the lengths only, never on the physical placement of blocks;
+//   piece  = the part of one (sequence, kv head) inside a worker's range; the
+//            worker leaves one partial softmax state (max, sum, acc[D]) per piece
+//            and a second kernel merges the pieces of each head in worker order.
+// Inside a worker a block's K (and V) for one head is one contiguous 16*D*2-byte
+// run; a wave load instruction covers 1 KiB of it: D/8 lanes per token row, 16
+// bytes (8 dims) per lane.  The q.k dot product is 8 FMAs per lane plus a
+// log2(D/8)-step butterfly inside the row's lanes.  Each group of D/8 lanes keeps
+// its own running (max, sum, acc[8]) over the token rows it sees, so the block
+// loop has no other cross-lane traffic; the groups are merged once per piece in a
+// fixed order.  Two register buffers hold the next block while the current one is
+// consumed.  Everything after the bf16 loads is float; results are
+// bit-reproducible.
 #include "kernels.h"
 #include "common.hip.h"
 #include <math.h>
@@ -41,203 +47,263 @@ __device__ __forceinline__ void merge_state(float &m, float &l, float (&acc)[NV]
     m = mn;
 }
 
+// first unit of worker w when U units are cut into W ranges
+__device__ __forceinline__ int64_t worker_begin(int64_t w, int64_t U, int64_t W) { return w * U / W; }
+// worker that owns unit u
+__device__ __forceinline__ int64_t worker_of(int64_t u, int64_t U, int64_t W) { return ((u + 1) * W + U - 1) / U - 1; }
+
+// exclusive scan of the per-sequence block counts ceil((ctx+1)/16) into prefix[0..n]
+__device__ __forceinline__ void scan_blocks(const int32_t *ctx_lens, int n, int32_t *prefix, int32_t *part)
+{
+    const int tid = threadIdx.x, nt = blockDim.x;
+    const int per = (n + nt - 1) / nt;
+    const int lo = min(tid * per, n), hi = min(lo + per, n);
+    int32_t local = 0;
+    for (int i = lo; i < hi; ++i) local += (ctx_lens[i] + 1 + kBlockTokens - 1) / kBlockTokens;
+    part[tid] = local;
+    __syncthreads();
+    if (tid == 0) {
+        int32_t run = 0;
+        for (int t = 0; t < nt; ++t) { const int32_t v = part[t]; part[t] = run; run += v; }
+        prefix[n] = run;
+    }
+    __syncthreads();
+    int32_t run = part[tid];
+    for (int i = lo; i < hi; ++i) { prefix[i] = run; run += (ctx_lens[i] + 1 + kBlockTokens - 1) / kBlockTokens; }
+    __syncthreads();
+}
+
 template <int D, int G, bool DEBUG>
 __global__ __launch_bounds__(kDecThreads) void attn_decode_kernel(DecodeAttnArgs a)
 {
-    constexpr int LPT = D / 8;             // lanes per token row
-    constexpr int TPI = 64 / LPT;          // token rows per wave load instruction
+    constexpr int LPT = D / 8;               // lanes per token row
+    constexpr int TPI = 64 / LPT;            // token rows per wave load instruction
     constexpr int IPB = kBlockTokens / TPI;  // load instructions per block (K or V)
-    constexpr int kBlocksPerSplit = kDecodeSplitTokens / kBlockTokens;
 
-    const int split = blockIdx.x, hk = blockIdx.y, seq = blockIdx.z;
-    const int n_keys = a.ctx_lens[seq] + 1;                  // cached tokens + the one appended this step
-    const int tok0 = split * kDecodeSplitTokens;
-    if (tok0 >= n_keys) return;
-    const int nblk = (min(n_keys, tok0 + kDecodeSplitTokens) - tok0 + kBlockTokens - 1) / kBlockTokens;
+    extern __shared__ int32_t s_prefix[];    // [num_seqs + 1] blocks (per head) before each sequence
+    __shared__ int32_t s_part[kDecThreads];
+    scan_blocks(a.ctx_lens, a.num_seqs, s_prefix, s_part);
 
-    __shared__ int32_t s_phys[kBlocksPerSplit];
-    __shared__ float s_merge[kDecWaves][G][D + 2];
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    if (tid < nblk) s_phys[tid] = a.block_table[(int64_t)seq * a.max_blocks_per_seq + tok0 / kBlockTokens + tid];
-    __syncthreads();
+    const int lane = threadIdx.x & 63;
+    const int Hkv = a.n_kv_heads;
+    const int64_t U = (int64_t)s_prefix[a.num_seqs] * Hkv;
+    const int64_t W = min((int64_t)gridDim.x * kDecWaves, U);       // never more workers than units: no empty ranges
+    const int64_t wk = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * kDecWaves + (threadIdx.x >> 6)));
+    if (wk >= W) return;
+    int64_t u = worker_begin(wk, U, W);
+    const int64_t u_end = worker_begin(wk + 1, U, W);
+    if (u >= u_end) return;
 
     const int dc = lane % LPT, ti = lane / LPT;
-    // query, pre-scaled by log2(e)/sqrt(D) so that probabilities are exp2(s - m)
-    float q[G][8];
-    const int tq = seq;                                       // decode: token index == sequence index
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-        const u32x4 v = ld16(a.q + ((int64_t)tq * a.n_q_heads + hk * G + g) * D + dc * 8);
-        q[g][0] = bf16_lo(v.x) * a.scale_log2e; q[g][1] = bf16_hi(v.x) * a.scale_log2e;
-        q[g][2] = bf16_lo(v.y) * a.scale_log2e; q[g][3] = bf16_hi(v.y) * a.scale_log2e;
-        q[g][4] = bf16_lo(v.z) * a.scale_log2e; q[g][5] = bf16_hi(v.z) * a.scale_log2e;
-        q[g][6] = bf16_lo(v.w) * a.scale_log2e; q[g][7] = bf16_hi(v.w) * a.scale_log2e;
-    }
-    float m[G], l[G], acc[G][8];
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-        m[g] = -INFINITY; l[g] = 0.f;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc[g][e] = 0.f;
+    const int64_t head_bytes = (int64_t)kBlockTokens * D * 2;
+    const int64_t unit_bytes = 2 * (int64_t)Hkv * head_bytes;
+    const char *layer_base = reinterpret_cast<const char *>(a.pool) + (int64_t)a.layer_local * a.num_blocks * unit_bytes;
+
+    // sequence that owns unit u: prefix[seq]*Hkv <= u < prefix[seq+1]*Hkv
+    int seq;
+    {
+        int lo = 0, hi = a.num_seqs;
+        while (hi - lo > 1) { const int mid = (lo + hi) >> 1; if ((int64_t)s_prefix[mid] * Hkv <= u) lo = mid; else hi = mid; }
+        seq = lo;
     }
 
-    const int64_t head_bytes = (int64_t)kBlockTokens * D * 2;
-    const int64_t unit_bytes = 2 * (int64_t)a.n_kv_heads * head_bytes;
-    const char *layer_base = reinterpret_cast<const char *>(a.pool) + (int64_t)a.layer_local * a.num_blocks * unit_bytes;
-    auto load_block = [&](int b, u32x4(&k)[IPB], u32x4(&v)[IPB]) {
-        const char *kp = layer_base + (int64_t)s_phys[b] * unit_bytes + (int64_t)hk * head_bytes + lane * 16;
-        const char *vp = kp + (int64_t)a.n_kv_heads * head_bytes;
-#pragma unroll
-        for (int i = 0; i < IPB; ++i) {
-            k[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(kp + i * 1024));
-            v[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(vp + i * 1024));
-        }
-    };
-    auto consume = [&](int b, const u32x4(&k)[IPB], const u32x4(&v)[IPB]) {
-        const int tbase = tok0 + b * kBlockTokens;
+    while (u < u_end) {
+        while ((int64_t)s_prefix[seq + 1] * Hkv <= u) ++seq;
+        const int nb_seq = s_prefix[seq + 1] - s_prefix[seq];
+        const int64_t r = u - (int64_t)s_prefix[seq] * Hkv;
+        const int hk = (int)(r / nb_seq), blk0 = (int)(r % nb_seq);
+        const int nblk = (int)min((int64_t)(nb_seq - blk0), u_end - u);  // blocks of this piece
+        const int n_keys = a.ctx_lens[seq] + 1;                          // cached tokens + the one appended this step
+        const int32_t *trow = a.block_table + (int64_t)seq * a.max_blocks_per_seq + blk0;
+
+        // query, pre-scaled by log2(e)/sqrt(D) so that probabilities are exp2(s - m)
+        float q[G][8];
 #pragma unroll
         for (int g = 0; g < G; ++g) {
-            float s[IPB];
+            const u32x4 v = ld16(a.q + ((int64_t)seq * a.n_q_heads + hk * G + g) * D + dc * 8);
+            q[g][0] = bf16_lo(v.x) * a.scale_log2e; q[g][1] = bf16_hi(v.x) * a.scale_log2e;
+            q[g][2] = bf16_lo(v.y) * a.scale_log2e; q[g][3] = bf16_hi(v.y) * a.scale_log2e;
+            q[g][4] = bf16_lo(v.z) * a.scale_log2e; q[g][5] = bf16_hi(v.z) * a.scale_log2e;
+            q[g][6] = bf16_lo(v.w) * a.scale_log2e; q[g][7] = bf16_hi(v.w) * a.scale_log2e;
+        }
+        float m[G], l[G], acc[G][8];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            m[g] = -INFINITY; l[g] = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[g][e] = 0.f;
+        }
+
+        auto load_block = [&](int b, u32x4(&k)[IPB], u32x4(&v)[IPB]) {
+            const int32_t phys = trow[b];
+            const char *kp = layer_base + (int64_t)phys * unit_bytes + (int64_t)hk * head_bytes + lane * 16;
+            const char *vp = kp + (int64_t)Hkv * head_bytes;
 #pragma unroll
             for (int i = 0; i < IPB; ++i) {
-                float d = q[g][0] * bf16_lo(k[i].x);
-                d = fmaf(q[g][1], bf16_hi(k[i].x), d);
-                d = fmaf(q[g][2], bf16_lo(k[i].y), d);
-                d = fmaf(q[g][3], bf16_hi(k[i].y), d);
-                d = fmaf(q[g][4], bf16_lo(k[i].z), d);
-                d = fmaf(q[g][5], bf16_hi(k[i].z), d);
-                d = fmaf(q[g][6], bf16_lo(k[i].w), d);
-                d = fmaf(q[g][7], bf16_hi(k[i].w), d);
+                k[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(kp + i * 1024));
+                v[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(vp + i * 1024));
+            }
+        };
+        auto consume = [&](int b, const u32x4(&k)[IPB], u32x4(&v)[IPB]) {
+            const int tbase = (blk0 + b) * kBlockTokens;
+            if (tbase + kBlockTokens > n_keys) {
+                // last block of the sequence: rows past the end may hold anything (also NaN
+                // patterns); zero them so that a zero probability meets a zero value
 #pragma unroll
-                for (int o = LPT / 2; o > 0; o >>= 1) d += __shfl_xor(d, o, 64);
-                const int tok = tbase + i * TPI + ti;
-                s[i] = tok < n_keys ? d : -INFINITY;
-                if constexpr (DEBUG) {
-                    if (dc == 0 && tok < n_keys)
-                        a.dbg_scores[((int64_t)tq * a.n_q_heads + hk * G + g) * a.dbg_stride + tok] = d;
+                for (int i = 0; i < IPB; ++i)
+                    if (tbase + i * TPI + ti >= n_keys) v[i] = u32x4{0u, 0u, 0u, 0u};
+            }
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                float s[IPB];
+#pragma unroll
+                for (int i = 0; i < IPB; ++i) {
+                    float d = q[g][0] * bf16_lo(k[i].x);
+                    d = fmaf(q[g][1], bf16_hi(k[i].x), d);
+                    d = fmaf(q[g][2], bf16_lo(k[i].y), d);
+                    d = fmaf(q[g][3], bf16_hi(k[i].y), d);
+                    d = fmaf(q[g][4], bf16_lo(k[i].z), d);
+                    d = fmaf(q[g][5], bf16_hi(k[i].z), d);
+                    d = fmaf(q[g][6], bf16_lo(k[i].w), d);
+                    d = fmaf(q[g][7], bf16_hi(k[i].w), d);
+#pragma unroll
+                    for (int o = LPT / 2; o > 0; o >>= 1) d += __shfl_xor(d, o, 64);
+                    const int tok = tbase + i * TPI + ti;
+                    s[i] = tok < n_keys ? d : -INFINITY;
+                    if constexpr (DEBUG) {
+                        if (dc == 0 && tok < n_keys)
+                            a.dbg_scores[((int64_t)seq * a.n_q_heads + hk * G + g) * a.dbg_stride + tok] = d;
+                    }
+                }
+                float mn = m[g];
+#pragma unroll
+                for (int i = 0; i < IPB; ++i) mn = fmaxf(mn, s[i]);
+                const float ms = (mn == -INFINITY) ? 0.f : mn;
+                const float alpha = fast_exp2(m[g] - ms);
+                m[g] = mn;
+                float p[IPB], psum = 0.f;
+#pragma unroll
+                for (int i = 0; i < IPB; ++i) { p[i] = fast_exp2(s[i] - ms); psum += p[i]; }
+                l[g] = l[g] * alpha + psum;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[g][e] *= alpha;
+#pragma unroll
+                for (int i = 0; i < IPB; ++i) {
+                    acc[g][0] = fmaf(p[i], bf16_lo(v[i].x), acc[g][0]);
+                    acc[g][1] = fmaf(p[i], bf16_hi(v[i].x), acc[g][1]);
+                    acc[g][2] = fmaf(p[i], bf16_lo(v[i].y), acc[g][2]);
+                    acc[g][3] = fmaf(p[i], bf16_hi(v[i].y), acc[g][3]);
+                    acc[g][4] = fmaf(p[i], bf16_lo(v[i].z), acc[g][4]);
+                    acc[g][5] = fmaf(p[i], bf16_hi(v[i].z), acc[g][5]);
+                    acc[g][6] = fmaf(p[i], bf16_lo(v[i].w), acc[g][6]);
+                    acc[g][7] = fmaf(p[i], bf16_hi(v[i].w), acc[g][7]);
                 }
             }
-            float mn = m[g];
-#pragma unroll
-            for (int i = 0; i < IPB; ++i) mn = fmaxf(mn, s[i]);
-            const float ms = (mn == -INFINITY) ? 0.f : mn;
-            const float alpha = fast_exp2(m[g] - ms);
-            m[g] = mn;
-            float p[IPB], psum = 0.f;
-#pragma unroll
-            for (int i = 0; i < IPB; ++i) { p[i] = fast_exp2(s[i] - ms); psum += p[i]; }
-            l[g] = l[g] * alpha + psum;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) acc[g][e] *= alpha;
-#pragma unroll
-            for (int i = 0; i < IPB; ++i) {
-                acc[g][0] = fmaf(p[i], bf16_lo(v[i].x), acc[g][0]);
-                acc[g][1] = fmaf(p[i], bf16_hi(v[i].x), acc[g][1]);
-                acc[g][2] = fmaf(p[i], bf16_lo(v[i].y), acc[g][2]);
-                acc[g][3] = fmaf(p[i], bf16_hi(v[i].y), acc[g][3]);
-                acc[g][4] = fmaf(p[i], bf16_lo(v[i].z), acc[g][4]);
-                acc[g][5] = fmaf(p[i], bf16_hi(v[i].z), acc[g][5]);
-                acc[g][6] = fmaf(p[i], bf16_lo(v[i].w), acc[g][6]);
-                acc[g][7] = fmaf(p[i], bf16_hi(v[i].w), acc[g][7]);
+        };
+
+        {
+            u32x4 k0[IPB], v0[IPB], k1[IPB], v1[IPB];
+            load_block(0, k0, v0);
+            for (int b = 0; b < nblk; b += 2) {
+                if (b + 1 < nblk) load_block(b + 1, k1, v1);
+                consume(b, k0, v0);
+                if (b + 2 < nblk) load_block(b + 2, k0, v0);
+                if (b + 1 < nblk) consume(b + 1, k1, v1);
             }
         }
-    };
 
-    {
-        u32x4 k0[IPB], v0[IPB], k1[IPB], v1[IPB];
-        int b = wave;
-        if (b < nblk) load_block(b, k0, v0);
-        for (; b < nblk; b += 2 * kDecWaves) {
-            const int b1 = b + kDecWaves, b2 = b + 2 * kDecWaves;
-            if (b1 < nblk) load_block(b1, k1, v1);
-            consume(b, k0, v0);
-            if (b2 < nblk) load_block(b2, k0, v0);
-            if (b1 < nblk) consume(b1, k1, v1);
+        // merge the TPI lane groups (butterfly, lower group always the first operand) and store the piece
+        const int64_t pair = (int64_t)seq * Hkv + hk;
+        const int64_t slot = wk + pair;                  // unique: consecutive pieces differ in worker or in pair
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+#pragma unroll
+            for (int o = LPT; o < 64; o <<= 1) {
+                float m2 = __shfl_xor(m[g], o, 64), l2 = __shfl_xor(l[g], o, 64), acc2[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc2[e] = __shfl_xor(acc[g][e], o, 64);
+                if ((lane & o) == 0) merge_state<8>(m[g], l[g], acc[g], m2, l2, acc2);
+                else {
+                    float mm = m2, ll = l2;
+                    merge_state<8>(mm, ll, acc2, m[g], l[g], acc[g]);
+                    m[g] = mm; l[g] = ll;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) acc[g][e] = acc2[e];
+                }
+            }
+            if (ti == 0) {
+                float *pa = a.part_acc + (slot * G + g) * D + dc * 8;
+                *reinterpret_cast<f32x4_t *>(pa) = f32x4_t{acc[g][0], acc[g][1], acc[g][2], acc[g][3]};
+                *reinterpret_cast<f32x4_t *>(pa + 4) = f32x4_t{acc[g][4], acc[g][5], acc[g][6], acc[g][7]};
+                if (dc == 0) { a.part_ml[(slot * G + g) * 2] = m[g]; a.part_ml[(slot * G + g) * 2 + 1] = l[g]; }
+            }
         }
-    }
-
-    // merge the TPI lane groups of the wave (butterfly: every lane ends with the wave's state)
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-#pragma unroll
-        for (int o = LPT; o < 64; o <<= 1) {
-            float m2 = __shfl_xor(m[g], o, 64), l2 = __shfl_xor(l[g], o, 64), acc2[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) acc2[e] = __shfl_xor(acc[g][e], o, 64);
-            // fixed order: the lower lane group is always the first operand
-            if ((lane & o) == 0) merge_state<8>(m[g], l[g], acc[g], m2, l2, acc2);
-            else { float mm = m2, ll = l2; merge_state<8>(mm, ll, acc2, m[g], l[g], acc[g]);
-                   m[g] = mm; l[g] = ll;
-#pragma unroll
-                   for (int e = 0; e < 8; ++e) acc[g][e] = acc2[e]; }
-        }
-        if (ti == 0) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) s_merge[wave][g][dc * 8 + e] = acc[g][e];
-            if (dc == 0) { s_merge[wave][g][D] = m[g]; s_merge[wave][g][D + 1] = l[g]; }
-        }
-    }
-    __syncthreads();
-    // merge the waves in wave order; thread d of the first D threads owns output dim d
-    const int n_splits = a.max_splits;
-    for (int idx = tid; idx < G * D; idx += kDecThreads) {
-        const int g = idx / D, d = idx % D;
-        float mm = -INFINITY;
-#pragma unroll
-        for (int w = 0; w < kDecWaves; ++w) mm = fmaxf(mm, s_merge[w][g][D]);
-        const float ms = (mm == -INFINITY) ? 0.f : mm;
-        float ll = 0.f, av = 0.f;
-#pragma unroll
-        for (int w = 0; w < kDecWaves; ++w) {
-            const float sc = fast_exp2(s_merge[w][g][D] - ms);
-            ll += s_merge[w][g][D + 1] * sc;
-            av += s_merge[w][g][d] * sc;
-        }
-        const int64_t row = ((int64_t)tq * a.n_q_heads + hk * G + g) * n_splits + split;
-        a.part_acc[row * D + d] = av;
-        if (d == 0) { a.part_ml[row * 2] = mm; a.part_ml[row * 2 + 1] = ll; }
+        u += nblk;
     }
 }
 
-// Merge the context splits of each (token, query head) in split order and
-// normalise: o = sum_s acc_s 2^(m_s - m) / sum_s l_s 2^(m_s - m).
+// Merge the pieces of each (sequence, query head) in worker order and normalise:
+// o = sum_p acc_p 2^(m_p - m) / sum_p l_p 2^(m_p - m).  One workgroup per (sequence, kv head).
 template <bool DEBUG>
 __global__ void attn_decode_combine_kernel(DecodeAttnArgs a)
 {
-    const int row = blockIdx.x;                      // token * Hq + head
-    const int seq = row / a.n_q_heads;
-    const int D = a.head_dim;
-    const int n_keys = a.ctx_lens[seq] + 1;
-    const int ns = (n_keys + kDecodeSplitTokens - 1) / kDecodeSplitTokens;
-    const float *ml = a.part_ml + (int64_t)row * a.max_splits * 2;
-    float mm = -INFINITY;
-    for (int s = 0; s < ns; ++s) mm = fmaxf(mm, ml[s * 2]);
-    float ll = 0.f;
-    for (int s = 0; s < ns; ++s) ll += ml[s * 2 + 1] * fast_exp2(ml[s * 2] - mm);
-    for (int d = threadIdx.x; d < D; d += blockDim.x) {
-        float av = 0.f;
-        for (int s = 0; s < ns; ++s)
-            av += a.part_acc[((int64_t)row * a.max_splits + s) * D + d] * fast_exp2(ml[s * 2] - mm);
-        a.out[(int64_t)row * D + d] = f32_to_bf16(av / ll);
+    __shared__ int32_t s_red[4];
+    const int seq = blockIdx.x / a.n_kv_heads, hk = blockIdx.x % a.n_kv_heads;
+    const int D = a.head_dim, G = a.n_q_heads / a.n_kv_heads, Hkv = a.n_kv_heads;
+    // blocks before this sequence and in total (per head)
+    int32_t before = 0, total = 0;
+    for (int i = threadIdx.x; i < a.num_seqs; i += blockDim.x) {
+        const int32_t nb = (a.ctx_lens[i] + 1 + kBlockTokens - 1) / kBlockTokens;
+        total += nb;
+        if (i < seq) before += nb;
     }
-    if constexpr (DEBUG) {
-        // turn the stored scaled scores (log2 domain) into probabilities
-        float *pr = a.dbg_scores + (int64_t)row * a.dbg_stride;
-        for (int r = threadIdx.x; r < n_keys; r += blockDim.x) pr[r] = fast_exp2(pr[r] - mm) / ll;
+    for (int o = 32; o > 0; o >>= 1) { before += __shfl_xor(before, o, 64); total += __shfl_xor(total, o, 64); }
+    if ((threadIdx.x & 63) == 0) { s_red[(threadIdx.x >> 6) * 2] = before; s_red[(threadIdx.x >> 6) * 2 + 1] = total; }
+    __syncthreads();
+    before = s_red[0]; total = s_red[1];
+    if (blockDim.x > 64) { before += s_red[2]; total += s_red[3]; }
+    const int n_keys = a.ctx_lens[seq] + 1;
+    const int nb = (n_keys + kBlockTokens - 1) / kBlockTokens;
+    const int64_t U = (int64_t)total * Hkv, W = min((int64_t)a.n_workers, U);
+    const int64_t u0 = (int64_t)before * Hkv + (int64_t)hk * nb;
+    const int64_t w_first = worker_of(u0, U, W), w_last = worker_of(u0 + nb - 1, U, W);
+    const int64_t pair = (int64_t)seq * Hkv + hk;
+    for (int g = 0; g < G; ++g) {
+        float mm = -INFINITY;
+        for (int64_t w = w_first; w <= w_last; ++w) mm = fmaxf(mm, a.part_ml[((w + pair) * G + g) * 2]);
+        float ll = 0.f;
+        for (int64_t w = w_first; w <= w_last; ++w)
+            ll += a.part_ml[((w + pair) * G + g) * 2 + 1] * fast_exp2(a.part_ml[((w + pair) * G + g) * 2] - mm);
+        const int64_t row = (int64_t)seq * a.n_q_heads + hk * G + g;
+        for (int d = threadIdx.x; d < D; d += blockDim.x) {
+            float av = 0.f;
+            for (int64_t w = w_first; w <= w_last; ++w)
+                av += a.part_acc[((w + pair) * G + g) * D + d] * fast_exp2(a.part_ml[((w + pair) * G + g) * 2] - mm);
+            a.out[row * D + d] = f32_to_bf16(av / ll);
+        }
+        if constexpr (DEBUG) {
+            // turn the stored scaled scores (log2 domain) into probabilities
+            float *pr = a.dbg_scores + row * a.dbg_stride;
+            for (int r = threadIdx.x; r < n_keys; r += blockDim.x) pr[r] = fast_exp2(pr[r] - mm) / ll;
+        }
     }
 }
 
 template <int D, int G>
 static hipError_t launch_dg(const DecodeAttnArgs &a, hipStream_t stream)
 {
-    dim3 grid(a.max_splits, a.n_kv_heads, a.num_seqs);
-    if (a.dbg_scores) hipLaunchKernelGGL((attn_decode_kernel<D, G, true>), grid, dim3(kDecThreads), 0, stream, a);
-    else hipLaunchKernelGGL((attn_decode_kernel<D, G, false>), grid, dim3(kDecThreads), 0, stream, a);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    dim3 cgrid(a.num_seqs * a.n_q_heads);
-    if (a.dbg_scores) hipLaunchKernelGGL(attn_decode_combine_kernel<true>, cgrid, dim3(D), 0, stream, a);
-    else hipLaunchKernelGGL(attn_decode_combine_kernel<false>, cgrid, dim3(D), 0, stream, a);
+    const dim3 grid(a.n_workers / kDecWaves);
+    const size_t lds = (size_t)(a.num_seqs + 1) * sizeof(int32_t);
+    if (a.dbg_scores) hipLaunchKernelGGL((attn_decode_kernel<D, G, true>), grid, dim3(kDecThreads), lds, stream, a);
+    else hipLaunchKernelGGL((attn_decode_kernel<D, G, false>), grid, dim3(kDecThreads), lds, stream, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_attn_decode_combine(const DecodeAttnArgs &a, hipStream_t stream)
+{
+    const dim3 cgrid(a.num_seqs * a.n_kv_heads);
+    if (a.dbg_scores) hipLaunchKernelGGL(attn_decode_combine_kernel<true>, cgrid, dim3(a.head_dim), 0, stream, a);
+    else hipLaunchKernelGGL(attn_decode_combine_kernel<false>, cgrid, dim3(a.head_dim), 0, stream, a);
     return hipGetLastError();
 }
 

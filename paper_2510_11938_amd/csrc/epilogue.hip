@@ -124,54 +124,73 @@ hipError_t launch_resid_norm(const ResidNormArgs &a, hipStream_t stream)
 __global__ __launch_bounds__(kRowThreads) void swiglu_kernel(SwigluArgs a)
 {
     const int t = blockIdx.x;
+    const int c = blockIdx.y * kRowThreads + threadIdx.x;       // 8-wide output chunk of row t
+    if (c >= a.F / 8) return;
     const int64_t prow = (int64_t)t * 2 * a.F;
-    for (int c = threadIdx.x; c < a.F / 8; c += kRowThreads) {
-        const int f0 = c * 8;
-        const int64_t col = 32 * (f0 / 16) + (f0 % 16);
-        float gt[8], up[8];
-        partial8(a.P, a.S, (int64_t)a.T * 2 * a.F, prow + col, gt);
-        partial8(a.P, a.S, (int64_t)a.T * 2 * a.F, prow + col + 16, up);
+    const int f0 = c * 8;
+    const int64_t col = 32 * (f0 / 16) + (f0 % 16);
+    float gt[8], up[8];
+    partial8(a.P, a.S, (int64_t)a.T * 2 * a.F, prow + col, gt);
+    partial8(a.P, a.S, (int64_t)a.T * 2 * a.F, prow + col + 16, up);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) gt[e] = gt[e] / (1.f + __expf(-gt[e])) * up[e];
-        st16(a.out + (int64_t)t * a.ld_out + f0, pack8(gt));
-    }
+    for (int e = 0; e < 8; ++e) gt[e] = gt[e] / (1.f + __expf(-gt[e])) * up[e];
+    st16(a.out + (int64_t)t * a.ld_out + f0, pack8(gt));
 }
 
 hipError_t launch_swiglu(const SwigluArgs &a, hipStream_t stream)
 {
-    hipLaunchKernelGGL(swiglu_kernel, dim3(a.T), dim3(kRowThreads), 0, stream, a);
+    const dim3 grid(a.T, (a.F / 8 + kRowThreads - 1) / kRowThreads);
+    hipLaunchKernelGGL(swiglu_kernel, grid, dim3(kRowThreads), 0, stream, a);
     return hipGetLastError();
 }
 
 // ---------------------------------------------------------------- RoPE + cache append
-// One workgroup per token.  Threads 0..D/2-1 first evaluate the rotation angles
-// of the token's position in double (position * base^(-2d/D) reaches thousands of
-// radians; float would lose the low bits before the range reduction).
-template <bool FROM_PARTIAL>
-__global__ __launch_bounds__(kRowThreads) void qkv_rope_kvwrite_kernel(RopeArgs a)
+// Rotation table of one step: for every token its sequence, its absolute
+// position and cos/sin of position * base^(-2d/D), d < D/2.  The angle is
+// evaluated in double (it reaches thousands of radians; float would lose the low
+// bits before the range reduction).  Positions are the same for every layer of
+// the stage, so this runs once per forward call.
+__global__ void rope_table_kernel(RopeTableArgs a)
 {
-    __shared__ float cs[128], sn[128];      // D/2 <= 128
     __shared__ int s_seq, s_pos;
-    const int t = blockIdx.x;
-    const int D = a.head_dim, half = D / 2;
+    const int t = blockIdx.x, half = a.head_dim / 2;
     if (threadIdx.x == 0) {
         // sequence that owns token t: cu[seq] <= t < cu[seq+1]
         int lo = 0, hi = a.num_seqs;
         while (hi - lo > 1) { const int mid = (lo + hi) >> 1; if (a.cu_seqlens_q[mid] <= t) lo = mid; else hi = mid; }
         s_seq = lo;
         s_pos = a.ctx_lens[lo] + (t - a.cu_seqlens_q[lo]);
+        a.tok_seq[t] = s_seq;
+        a.tok_pos[t] = s_pos;
     }
     __syncthreads();
-    const int seq = s_seq, pos = s_pos;
-    if (threadIdx.x < half) {
-        const double ang = (double)pos * pow((double)a.rope_base, -2.0 * (double)threadIdx.x / (double)D);
-        cs[threadIdx.x] = (float)cos(ang);
-        sn[threadIdx.x] = (float)sin(ang);
+    if ((int)threadIdx.x < half) {
+        const double ang = (double)s_pos * pow((double)a.rope_base, -2.0 * (double)threadIdx.x / (double)a.head_dim);
+        a.cs[(int64_t)t * half + threadIdx.x] = (float)cos(ang);
+        a.sn[(int64_t)t * half + threadIdx.x] = (float)sin(ang);
     }
-    __syncthreads();
+}
 
+hipError_t launch_rope_table(const RopeTableArgs &a, hipStream_t stream)
+{
+    hipLaunchKernelGGL(rope_table_kernel, dim3(a.T), dim3(128), 0, stream, a);
+    return hipGetLastError();
+}
+
+// grid (token, column part): each thread rotates 8 pairs of one q or k head, or
+// copies 8 values of a v head; rotated k and v go straight into the token's cache slot.
+template <bool FROM_PARTIAL>
+__global__ __launch_bounds__(kRowThreads) void qkv_rope_kvwrite_kernel(RopeArgs a)
+{
+    const int t = blockIdx.x;
+    const int D = a.head_dim, half = D / 2;
     const int Nq = a.n_q_heads * D, Nkv = a.n_kv_heads * D, Nall = Nq + 2 * Nkv;
+    const int chunks_per_head = half / 8;
+    const int n_rot = (a.n_q_heads + a.n_kv_heads) * chunks_per_head, n_v = Nkv / 8;
+    const int c = blockIdx.y * kRowThreads + threadIdx.x;
+    if (c >= n_rot + n_v) return;
     const int64_t src_row = (int64_t)t * Nall;
+    const int seq = a.tok_seq[t], pos = a.tok_pos[t];
     const int32_t phys = a.block_table[(int64_t)seq * a.max_blocks_per_seq + pos / kBlockTokens];
     const int slot = pos % kBlockTokens;
     // cache row of (kv, head): ((((layer*num_blocks + phys)*2 + kv)*Hkv + head)*16 + slot)*D
@@ -182,17 +201,15 @@ __global__ __launch_bounds__(kRowThreads) void qkv_rope_kvwrite_kernel(RopeArgs 
         else unpack8(ld16(a.qkv + src_row + col), f);
     };
 
-    // rotated heads: q heads then k heads, 8 rotation pairs per thread-step
-    const int chunks_per_head = half / 8;
-    const int n_rot = (a.n_q_heads + a.n_kv_heads) * chunks_per_head;
-    for (int c = threadIdx.x; c < n_rot; c += kRowThreads) {
+    if (c < n_rot) {
         const int head = c / chunks_per_head, d0 = (c % chunks_per_head) * 8;
         float lo[8], hi[8], rl[8], rh[8];
         fetch8((int64_t)head * D + d0, lo);
         fetch8((int64_t)head * D + d0 + half, hi);
+        const float *cs = a.cs + (int64_t)t * half + d0, *sn = a.sn + (int64_t)t * half + d0;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            const float co = cs[d0 + e], si = sn[d0 + e];
+            const float co = cs[e], si = sn[e];
             rl[e] = lo[e] * co - hi[e] * si;
             rh[e] = hi[e] * co + lo[e] * si;
         }
@@ -201,20 +218,21 @@ __global__ __launch_bounds__(kRowThreads) void qkv_rope_kvwrite_kernel(RopeArgs 
         else dst = a.pool + (((blk + 0) * a.n_kv_heads + (head - a.n_q_heads)) * kBlockTokens + slot) * D;
         st16(dst + d0, pack8(rl));
         st16(dst + d0 + half, pack8(rh));
-    }
-    // v heads: plain copy into the cache
-    for (int c = threadIdx.x; c < Nkv / 8; c += kRowThreads) {
-        const int head = (c * 8) / D, d0 = (c * 8) % D;
+    } else {
+        const int cv = c - n_rot;
+        const int head = (cv * 8) / D, d0 = (cv * 8) % D;
         float f[8];
-        fetch8((int64_t)Nq + Nkv + c * 8, f);
+        fetch8((int64_t)Nq + Nkv + cv * 8, f);
         st16(a.pool + (((blk + 1) * a.n_kv_heads + head) * kBlockTokens + slot) * D + d0, pack8(f));
     }
 }
 
 hipError_t launch_qkv_rope_kvwrite(const RopeArgs &a, hipStream_t stream)
 {
-    if (a.P) hipLaunchKernelGGL(qkv_rope_kvwrite_kernel<true>, dim3(a.T), dim3(kRowThreads), 0, stream, a);
-    else hipLaunchKernelGGL(qkv_rope_kvwrite_kernel<false>, dim3(a.T), dim3(kRowThreads), 0, stream, a);
+    const int chunks = (a.n_q_heads + a.n_kv_heads) * (a.head_dim / 16) + a.n_kv_heads * a.head_dim / 8;
+    const dim3 grid(a.T, (chunks + kRowThreads - 1) / kRowThreads);
+    if (a.P) hipLaunchKernelGGL(qkv_rope_kvwrite_kernel<true>, grid, dim3(kRowThreads), 0, stream, a);
+    else hipLaunchKernelGGL(qkv_rope_kvwrite_kernel<false>, grid, dim3(kRowThreads), 0, stream, a);
     return hipGetLastError();
 }
 

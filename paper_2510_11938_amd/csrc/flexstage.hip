@@ -98,19 +98,61 @@ int env_int(const char *name, int dflt)
     return (v && *v) ? atoi(v) : dflt;
 }
 
-// Split-K factor of a skinny projection: enough workgroups to cover the chip a
-// few times over, at least 8 k-steps per split.  Depends on shapes only.
-int choose_split(int N, int K, int M)
+// Launch shape of a skinny projection: R weight tiles per wavefront (workgroup =
+// 4 wavefronts = 64*R rows) and the split-K factor S.  Enough workgroups to put
+// several wavefronts on every CU, but as few splits as that allows: every split
+// adds a float slice of partial sums that the epilogue has to read back.
+// Depends on shapes only, so results do not depend on anything else.
+struct SkinnyCfg { int R, S; };
+SkinnyCfg skinny_cfg(int N, int K, int M)
 {
-    const int forced = env_int("FXP_SKINNY_SPLIT", 0);
+    static const int forced_s = env_int("FXP_SKINNY_SPLIT", 0), forced_r = env_int("FXP_SKINNY_R", 0);
+    static const int target = env_int("FXP_SKINNY_TARGET_WGS", 512);
     const int ks = k_steps(K);
-    const int wgs_n = (N + fxp::skinny_rows_per_wg(M) - 1) / fxp::skinny_rows_per_wg(M);
-    int s = forced > 0 ? forced : (env_int("FXP_SKINNY_TARGET_WGS", 1024) + wgs_n - 1) / wgs_n;
+    SkinnyCfg c;
+    c.R = forced_r ? forced_r : (M > 64 ? 2 : (N >= 8192 ? 2 : 1));
+    const int wgs_n = (N + 64 * c.R - 1) / (64 * c.R);
+    int s = forced_s ? forced_s : (target + wgs_n - 1) / wgs_n;
     const int max_s = ks / 8 > 0 ? ks / 8 : 1;
     if (s > max_s) s = max_s;
+    if (s > 8 && !forced_s) s = 8;
     if (s < 1) s = 1;
-    return s;
+    c.S = s;
+    return c;
 }
+int choose_split(int N, int K, int M) { return skinny_cfg(N, K, M).S; }
+
+// ---- optional per-kernel timing (fxp_profile_*): HIP events recorded on the caller's stream
+enum KernelClass { kKcRmsnorm, kKcSkinny, kKcTiled, kKcRope, kKcAttnDecode, kKcAttnCombine, kKcAttnPrefill,
+                   kKcResidNorm, kKcSwiglu, kKcKvMove, kKcRopeTable, kKcCount };
+const char *const kKernelClassNames[kKcCount] = {"rmsnorm", "gemm_skinny", "gemm_tiled", "rope_kvwrite", "attn_decode",
+                                                 "attn_decode_combine", "attn_prefill", "resid_norm", "swiglu", "kv_move",
+                                                 "rope_table"};
+struct Profiler {
+    static constexpr int kMaxPairs = 8192;
+    bool on = false;
+    int used = 0, created = 0;
+    hipEvent_t ev[kMaxPairs][2];
+    int cls[kMaxPairs];
+} g_prof;
+
+struct KernelTimer {     // records an event pair around the launches made during its lifetime
+    int slot = -1;
+    hipStream_t st;
+    KernelTimer(int kc, hipStream_t stream) : st(stream)
+    {
+        if (!g_prof.on || g_prof.used >= Profiler::kMaxPairs) return;
+        if (g_prof.used >= g_prof.created) {
+            if (hipEventCreate(&g_prof.ev[g_prof.created][0]) != hipSuccess) return;
+            if (hipEventCreate(&g_prof.ev[g_prof.created][1]) != hipSuccess) return;
+            ++g_prof.created;
+        }
+        slot = g_prof.used++;
+        g_prof.cls[slot] = kc;
+        (void)hipEventRecord(g_prof.ev[slot][0], st);
+    }
+    ~KernelTimer() { if (slot >= 0) (void)hipEventRecord(g_prof.ev[slot][1], st); }
+};
 
 }  // namespace
 
@@ -125,8 +167,9 @@ namespace {
 
 struct Workspace {
     uint16_t *x[2], *n, *q, *qkv, *o, *h, *a;
-    float *P, *part_acc, *part_ml, *dbg_ml;
-    int max_splits;
+    float *P, *part_acc, *part_ml, *dbg_ml, *rope_cs, *rope_sn;
+    int32_t *tok_seq, *tok_pos;
+    int n_workers;
     size_t bytes;
 };
 
@@ -155,12 +198,16 @@ Workspace carve(const fxp_stage_desc &d, int T, int B, int max_blocks, char *bas
         if (b > pmax) pmax = b;
     }
     w.P = (float *)take(pmax);
-    w.max_splits = (int)(((size_t)max_blocks * 16 + fxp::kDecodeSplitTokens - 1) / fxp::kDecodeSplitTokens);
-    if (w.max_splits < 1) w.max_splits = 1;
-    const size_t rows = (size_t)(B > 0 ? B : 1) * d.n_q_heads * w.max_splits;
+    (void)max_blocks;
+    w.n_workers = device_cus() * env_int("FXP_DECODE_WORKERS_PER_CU", fxp::kDecodeWorkersPerCu) / 4 * 4;
+    const size_t rows = ((size_t)w.n_workers + (size_t)(B > 0 ? B : 1) * d.n_kv_heads) * (d.n_q_heads / d.n_kv_heads);
     w.part_acc = (float *)take(rows * d.head_dim * 4);
     w.part_ml = (float *)take(rows * 2 * 4);
     w.dbg_ml = (float *)take(t * d.n_q_heads * 3 * 4);
+    w.rope_cs = (float *)take(t * (d.head_dim / 2) * 4);
+    w.rope_sn = (float *)take(t * (d.head_dim / 2) * 4);
+    w.tok_seq = (int32_t *)take(t * 4);
+    w.tok_pos = (int32_t *)take(t * 4);
     w.bytes = at;
     return w;
 }
@@ -171,6 +218,49 @@ extern "C" {
 
 const char *fxp_last_error(void) { return g_err; }
 const char *fxp_version(void) { return "flexstage 0.1 (gfx950)"; }
+
+int fxp_profile_enable(int on)
+{
+    g_prof.on = on != 0;
+    g_prof.used = 0;
+    return FXP_OK;
+}
+
+int fxp_profile_num_classes(void) { return kKcCount; }
+
+const char *fxp_profile_class_name(int kernel_class)
+{
+    return (kernel_class >= 0 && kernel_class < kKcCount) ? kKernelClassNames[kernel_class] : nullptr;
+}
+
+int fxp_profile_read_launch(int index, int *kernel_class, double *ms)
+{
+    if (index < 0 || index >= g_prof.used || !kernel_class || !ms) return fail(FXP_EINVAL, "launch index %d out of range [0,%d)", index, g_prof.used);
+    hipError_t e = hipEventSynchronize(g_prof.ev[index][1]);
+    if (e != hipSuccess) return hip_fail(e, "hipEventSynchronize");
+    float t = 0.f;
+    if ((e = hipEventElapsedTime(&t, g_prof.ev[index][0], g_prof.ev[index][1])) != hipSuccess) return hip_fail(e, "hipEventElapsedTime");
+    *kernel_class = g_prof.cls[index];
+    *ms = t;
+    return FXP_OK;
+}
+
+int fxp_profile_read(int kernel_class, double *total_ms, int64_t *launches)
+{
+    if (kernel_class < 0 || kernel_class >= kKcCount || !total_ms || !launches) return fail(FXP_EINVAL, "bad argument to fxp_profile_read");
+    double sum = 0.0;
+    int64_t n = 0;
+    for (int i = 0; i < g_prof.used; ++i) {
+        if (g_prof.cls[i] != kernel_class) continue;
+        hipError_t e = hipEventSynchronize(g_prof.ev[i][1]);
+        if (e != hipSuccess) return hip_fail(e, "hipEventSynchronize");
+        float ms = 0.f;
+        if ((e = hipEventElapsedTime(&ms, g_prof.ev[i][0], g_prof.ev[i][1])) != hipSuccess) return hip_fail(e, "hipEventElapsedTime");
+        sum += ms; ++n;
+    }
+    *total_ms = sum; *launches = n;
+    return FXP_OK;
+}
 
 size_t fxp_stage_weight_arena_bytes(const fxp_stage_desc *desc)
 {
@@ -259,8 +349,9 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
     auto project_skinny = [&](const char *wbase, const uint16_t *X, int N, int K, int ldx, int *S_out) -> hipError_t {
         fxp::SkinnyArgs a;
         a.W = (const uint16_t *)wbase; a.X = X; a.P = w.P;
-        a.M = T; a.N = N; a.K = K; a.KS = k_steps(K); a.NT = N / 16; a.ldx = ldx; a.S = choose_split(N, K, T);
+        a.M = T; a.N = N; a.K = K; a.KS = k_steps(K); a.NT = N / 16; a.ldx = ldx; a.S = skinny_cfg(N, K, T).S; a.R = skinny_cfg(N, K, T).R;
         *S_out = a.S;
+        KernelTimer kt(kKcSkinny, st);
         return fxp::launch_gemm_skinny(a, st);
     };
     auto project_tiled = [&](const char *wbase, const uint16_t *X, int N, int K, int ldx, uint16_t *C, int ldc,
@@ -268,9 +359,17 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
         fxp::TiledArgs a;
         a.W = (const uint16_t *)wbase; a.X = X; a.R = R; a.C = C;
         a.M = T; a.K = K; a.KS = k_steps(K); a.NT = N / 16; a.ldx = ldx; a.ldc = ldc; a.epilogue = epi;
+        KernelTimer kt(kKcTiled, st);
         return fxp::launch_gemm_tiled(a, st);
     };
 
+    {   // token -> (sequence, position) and the rotation table: the same for every layer
+        fxp::RopeTableArgs rt;
+        rt.cu_seqlens_q = batch->cu_seqlens_q; rt.ctx_lens = batch->ctx_lens; rt.tok_seq = w.tok_seq; rt.tok_pos = w.tok_pos;
+        rt.cs = w.rope_cs; rt.sn = w.rope_sn; rt.T = T; rt.num_seqs = B; rt.head_dim = D; rt.rope_base = d.rope_base;
+        KernelTimer kt(kKcRopeTable, st);
+        if ((e = fxp::launch_rope_table(rt, st))) return hip_fail(e, "rope table");
+    }
     const uint16_t *x_cur = (const uint16_t *)hidden_in;
     for (int ll = 0; ll < stage->n_layers; ++ll) {
         const char *rec = stage->arena + stage->rec.bytes * (size_t)ll;
@@ -281,8 +380,10 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
         int S = 1;
 
         // attention norm (layers after the first get it from the previous layer's fused epilogue on the skinny path)
-        if (!skinny || ll == 0)
+        if (!skinny || ll == 0) {
+            KernelTimer kt(kKcRmsnorm, st);
             if ((e = fxp::launch_rmsnorm(x_cur, g_attn, w.n, T, H, d.rms_eps, st))) return hip_fail(e, "rmsnorm");
+        }
 
         // q|k|v projection, rotary embedding, cache append
         fxp::RopeArgs ra;
@@ -295,10 +396,13 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
             ra.qkv = w.qkv;
         }
         ra.q_out = w.q; ra.pool = (uint16_t *)pool->base;
-        ra.cu_seqlens_q = batch->cu_seqlens_q; ra.ctx_lens = batch->ctx_lens; ra.block_table = batch->block_table;
-        ra.num_blocks = pool->num_blocks; ra.T = T; ra.num_seqs = B; ra.max_blocks_per_seq = batch->max_blocks_per_seq;
-        ra.layer_local = ll; ra.n_q_heads = d.n_q_heads; ra.n_kv_heads = d.n_kv_heads; ra.head_dim = D; ra.rope_base = d.rope_base;
-        if ((e = fxp::launch_qkv_rope_kvwrite(ra, st))) return hip_fail(e, "rope + kv append");
+        ra.tok_seq = w.tok_seq; ra.tok_pos = w.tok_pos; ra.cs = w.rope_cs; ra.sn = w.rope_sn; ra.block_table = batch->block_table;
+        ra.num_blocks = pool->num_blocks; ra.T = T; ra.max_blocks_per_seq = batch->max_blocks_per_seq;
+        ra.layer_local = ll; ra.n_q_heads = d.n_q_heads; ra.n_kv_heads = d.n_kv_heads; ra.head_dim = D;
+        {
+            KernelTimer kt(kKcRope, st);
+            if ((e = fxp::launch_qkv_rope_kvwrite(ra, st))) return hip_fail(e, "rope + kv append");
+        }
 
         // attention
         if (decode) {
@@ -306,9 +410,16 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
             aa.q = w.q; aa.pool = (const uint16_t *)pool->base; aa.ctx_lens = batch->ctx_lens; aa.block_table = batch->block_table;
             aa.part_acc = w.part_acc; aa.part_ml = w.part_ml; aa.out = w.o; aa.dbg_scores = dbg; aa.dbg_stride = probs_stride;
             aa.num_blocks = pool->num_blocks; aa.num_seqs = B; aa.max_blocks_per_seq = batch->max_blocks_per_seq;
-            aa.max_splits = w.max_splits; aa.layer_local = ll; aa.n_q_heads = d.n_q_heads; aa.n_kv_heads = d.n_kv_heads;
+            aa.n_workers = w.n_workers; aa.layer_local = ll; aa.n_q_heads = d.n_q_heads; aa.n_kv_heads = d.n_kv_heads;
             aa.head_dim = D; aa.scale_log2e = scale_log2e;
-            if ((e = fxp::launch_attn_decode(aa, st))) return hip_fail(e, "decode attention");
+            {
+                KernelTimer kt(kKcAttnDecode, st);
+                if ((e = fxp::launch_attn_decode(aa, st))) return hip_fail(e, "decode attention");
+            }
+            {
+                KernelTimer kt(kKcAttnCombine, st);
+                if ((e = fxp::launch_attn_decode_combine(aa, st))) return hip_fail(e, "decode attention combine");
+            }
         } else {
             fxp::PrefillAttnArgs pa;
             pa.q = w.q; pa.pool = (const uint16_t *)pool->base; pa.cu_seqlens_q = batch->cu_seqlens_q; pa.ctx_lens = batch->ctx_lens;
@@ -316,6 +427,7 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
             pa.num_blocks = pool->num_blocks; pa.num_seqs = B; pa.num_tokens = T; pa.max_q_len = batch->max_q_len;
             pa.max_blocks_per_seq = batch->max_blocks_per_seq; pa.layer_local = ll; pa.n_q_heads = d.n_q_heads;
             pa.n_kv_heads = d.n_kv_heads; pa.head_dim = D; pa.scale_log2e = scale_log2e;
+            KernelTimer kt(kKcAttnPrefill, st);
             if ((e = fxp::launch_attn_prefill(pa, st))) return hip_fail(e, "prefill attention");
         }
 
@@ -324,21 +436,33 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
             if ((e = project_skinny(rec + stage->rec.wo, w.o, H, Nq, Nq, &S))) return hip_fail(e, "output projection");
             fxp::ResidNormArgs rn;
             rn.x = x_cur; rn.P = w.P; rn.h = w.h; rn.g = g_ffn; rn.n = w.n; rn.T = T; rn.H = H; rn.S = S; rn.eps = d.rms_eps;
-            if ((e = fxp::launch_resid_norm(rn, st))) return hip_fail(e, "residual + norm");
+            {
+                KernelTimer kt(kKcResidNorm, st);
+                if ((e = fxp::launch_resid_norm(rn, st))) return hip_fail(e, "residual + norm");
+            }
             // gate|up projection + SwiGLU
             if ((e = project_skinny(rec + stage->rec.wgu, w.n, 2 * F, H, H, &S))) return hip_fail(e, "gate/up projection");
             fxp::SwigluArgs sg;
             sg.P = w.P; sg.out = w.a; sg.T = T; sg.F = F; sg.S = S; sg.ld_out = F;
-            if ((e = fxp::launch_swiglu(sg, st))) return hip_fail(e, "swiglu");
+            {
+                KernelTimer kt(kKcSwiglu, st);
+                if ((e = fxp::launch_swiglu(sg, st))) return hip_fail(e, "swiglu");
+            }
             // down projection + residual, fused with the next layer's attention norm
             if ((e = project_skinny(rec + stage->rec.wd, w.a, H, F, F, &S))) return hip_fail(e, "down projection");
             rn.x = w.h; rn.P = w.P; rn.h = x_next; rn.S = S;
             rn.g = last ? nullptr : (const uint16_t *)(rec + stage->rec.bytes + stage->rec.g_attn);
             rn.n = w.n;
-            if ((e = fxp::launch_resid_norm(rn, st))) return hip_fail(e, "residual + norm");
+            {
+                KernelTimer kt(kKcResidNorm, st);
+                if ((e = fxp::launch_resid_norm(rn, st))) return hip_fail(e, "residual + norm");
+            }
         } else {
             if ((e = project_tiled(rec + stage->rec.wo, w.o, H, Nq, Nq, w.h, H, x_cur, fxp::kEpiResidual))) return hip_fail(e, "output projection");
-            if ((e = fxp::launch_rmsnorm(w.h, g_ffn, w.n, T, H, d.rms_eps, st))) return hip_fail(e, "rmsnorm");
+            {
+                KernelTimer kt(kKcRmsnorm, st);
+                if ((e = fxp::launch_rmsnorm(w.h, g_ffn, w.n, T, H, d.rms_eps, st))) return hip_fail(e, "rmsnorm");
+            }
             if ((e = project_tiled(rec + stage->rec.wgu, w.n, 2 * F, H, H, w.a, F, nullptr, fxp::kEpiSwiglu))) return hip_fail(e, "gate/up projection");
             if ((e = project_tiled(rec + stage->rec.wd, w.a, H, F, F, x_next, H, w.h, fxp::kEpiResidual))) return hip_fail(e, "down projection");
         }
@@ -411,6 +535,7 @@ static int move_grid(const fxp::KvMoveArgs &a, int max_blocks_per_seq)
 static int launch_moves(fxp::KvMoveArgs &a, int max_blocks_per_seq, hipStream_t st)
 {
     if (a.n_jobs == 0) return FXP_OK;
+    KernelTimer kt(kKcKvMove, st);
     hipError_t e = fxp::launch_kv_move(a, move_grid(a, max_blocks_per_seq), st);
     if (e != hipSuccess) return hip_fail(e, "kv move");
     return FXP_OK;

@@ -115,19 +115,24 @@ static hipError_t launch_cfg(const SkinnyArgs &a, hipStream_t stream)
     return hipGetLastError();
 }
 
-int skinny_rows_per_wg(int M)
+template <int MT, int U>
+static hipError_t launch_r(const SkinnyArgs &a, hipStream_t stream)
 {
-    const int mt = (M + 15) / 16;
-    return (mt <= 4 ? 4 : 2) * 4 * 16;
+    switch (a.R) {
+    case 1: return launch_cfg<MT, 1, U>(a, stream);
+    case 2: return launch_cfg<MT, 2, U>(a, stream);
+    case 4: return launch_cfg<MT, 4, (MT == 8 ? 1 : U)>(a, stream);
+    default: return hipErrorInvalidValue;
+    }
 }
 
 hipError_t launch_gemm_skinny(const SkinnyArgs &a, hipStream_t stream)
 {
     const int mt = (a.M + 15) / 16;
-    if (mt <= 1) return launch_cfg<1, 4, 4>(a, stream);
-    if (mt <= 2) return launch_cfg<2, 4, 4>(a, stream);
-    if (mt <= 4) return launch_cfg<4, 4, 2>(a, stream);
-    if (mt <= 8) return launch_cfg<8, 2, 2>(a, stream);
+    if (mt <= 1) return launch_r<1, 4>(a, stream);
+    if (mt <= 2) return launch_r<2, 4>(a, stream);
+    if (mt <= 4) return launch_r<4, 2>(a, stream);
+    if (mt <= 8) return launch_r<8, 2>(a, stream);
     return hipErrorInvalidValue;
 }
 

@@ -44,9 +44,9 @@ struct SkinnyArgs {
     const uint16_t *X;     // token rows [M][ldx] bf16
     float *P;              // partial sums [S][M][N]
     int M, N, K, KS, NT, ldx, S;   // KS = padded K / 32, NT = N / 16
+    int R;                         // 16-row weight tiles per wavefront: 1, 2 or 4
 };
 hipError_t launch_gemm_skinny(const SkinnyArgs &a, hipStream_t stream);
-int skinny_rows_per_wg(int M);
 
 enum { kEpiStore = 0, kEpiResidual = 1, kEpiSwiglu = 2 };
 struct TiledArgs {
@@ -79,38 +79,49 @@ struct SwigluArgs {
 };
 hipError_t launch_swiglu(const SwigluArgs &a, hipStream_t stream);
 
+struct RopeTableArgs {
+    const int32_t *cu_seqlens_q, *ctx_lens;
+    int32_t *tok_seq, *tok_pos;   // [T]
+    float *cs, *sn;               // [T][D/2]
+    int T, num_seqs, head_dim;
+    float rope_base;
+};
+hipError_t launch_rope_table(const RopeTableArgs &a, hipStream_t stream);
+
 struct RopeArgs {
     const float *P;        // q|k|v partial sums [S][T][Nall], or nullptr
     const uint16_t *qkv;   // q|k|v bf16 [T][Nall] (when P == nullptr)
     uint16_t *q_out;       // rotated q [T][Hq*D] bf16
     uint16_t *pool;        // stage KV pool
-    const int32_t *cu_seqlens_q, *ctx_lens, *block_table;
+    const int32_t *tok_seq, *tok_pos;   // from the rope table
+    const float *cs, *sn;
+    const int32_t *block_table;
     int64_t num_blocks;
-    int T, S, num_seqs, max_blocks_per_seq, layer_local;
+    int T, S, max_blocks_per_seq, layer_local;
     int n_q_heads, n_kv_heads, head_dim;
-    float rope_base;
 };
 hipError_t launch_qkv_rope_kvwrite(const RopeArgs &a, hipStream_t stream);
 
 // ---------------------------------------------------------------- attention
-constexpr int kDecodeSplitTokens = 512;   // keys per workgroup of the decode kernel
+constexpr int kDecodeWorkersPerCu = 8;    // wavefronts of the decode kernel per compute unit
 
 struct DecodeAttnArgs {
     const uint16_t *q;     // [num_seqs][Hq][D] bf16 (rotated)
     const uint16_t *pool;
     const int32_t *ctx_lens, *block_table;
-    float *part_acc;       // [num_seqs][Hq][max_splits][D]
-    float *part_ml;        // [num_seqs][Hq][max_splits][2]
+    float *part_acc;       // [n_workers + num_seqs*Hkv][G][D]   one row group per piece
+    float *part_ml;        // [n_workers + num_seqs*Hkv][G][2]
     uint16_t *out;         // [num_seqs][Hq*D] bf16
     float *dbg_scores;     // optional [num_seqs][Hq][dbg_stride]
     int64_t dbg_stride;
     int64_t num_blocks;
-    int num_seqs, max_blocks_per_seq, max_splits, layer_local;
+    int num_seqs, max_blocks_per_seq, n_workers, layer_local;   // n_workers: multiple of 4
     int n_q_heads, n_kv_heads, head_dim;
     float scale_log2e;     // log2(e) / sqrt(D)
 };
 bool decode_attn_supported(int head_dim, int group);
-hipError_t launch_attn_decode(const DecodeAttnArgs &a, hipStream_t stream);
+hipError_t launch_attn_decode(const DecodeAttnArgs &a, hipStream_t stream);          // per-split partial results
+hipError_t launch_attn_decode_combine(const DecodeAttnArgs &a, hipStream_t stream);  // merge of the splits
 
 struct PrefillAttnArgs {
     const uint16_t *q;     // [T][Hq][D] bf16 (rotated)
