@@ -107,17 +107,17 @@ struct SkinnyCfg { int R, S; };
 SkinnyCfg skinny_cfg(int N, int K, int M)
 {
     static const int forced_s = env_int("FXP_SKINNY_SPLIT", 0), forced_r = env_int("FXP_SKINNY_R", 0);
-    static const int target = env_int("FXP_SKINNY_TARGET_WGS", 512);
+    static const int max_wgs = env_int("FXP_SKINNY_MAX_WGS", 320);
     const int ks = k_steps(K);
     SkinnyCfg c;
-    c.R = forced_r ? forced_r : (M > 64 ? 2 : (N >= 8192 ? 2 : 1));
+    // Measured on MI355X: about one workgroup (4 wavefronts, 8-16 KiB of weights in flight each)
+    // per CU streams fastest; more, thinner workgroups lose bandwidth, as do uneven k ranges,
+    // hence power-of-two splits.
+    c.R = forced_r ? forced_r : ((N >= 16384 && M <= 64) ? 4 : 2);
     const int wgs_n = (N + 64 * c.R - 1) / (64 * c.R);
-    int s = forced_s ? forced_s : (target + wgs_n - 1) / wgs_n;
-    const int max_s = ks / 8 > 0 ? ks / 8 : 1;
-    if (s > max_s) s = max_s;
-    if (s > 8 && !forced_s) s = 8;
-    if (s < 1) s = 1;
-    c.S = s;
+    int s = 1;
+    while (s * 2 <= 8 && s * 2 <= ks / 8 && wgs_n * s * 2 <= max_wgs) s *= 2;
+    c.S = forced_s ? forced_s : s;
     return c;
 }
 int choose_split(int N, int K, int M) { return skinny_cfg(N, K, M).S; }
@@ -349,7 +349,7 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
     auto project_skinny = [&](const char *wbase, const uint16_t *X, int N, int K, int ldx, int *S_out) -> hipError_t {
         fxp::SkinnyArgs a;
         a.W = (const uint16_t *)wbase; a.X = X; a.P = w.P;
-        a.M = T; a.N = N; a.K = K; a.KS = k_steps(K); a.NT = N / 16; a.ldx = ldx; a.S = skinny_cfg(N, K, T).S; a.R = skinny_cfg(N, K, T).R;
+        a.M = T; a.N = N; a.K = K; a.KS = k_steps(K); a.NT = N / 16; a.ldx = ldx; a.S = skinny_cfg(N, K, T).S; a.R = skinny_cfg(N, K, T).R; a.U = env_int("FXP_SKINNY_U", 4);
         *S_out = a.S;
         KernelTimer kt(kKcSkinny, st);
         return fxp::launch_gemm_skinny(a, st);

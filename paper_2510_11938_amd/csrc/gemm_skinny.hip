@@ -8,8 +8,10 @@
 //     goes from HBM straight into the registers that feed
 //     v_mfma_f32_16x16x32_bf16 -- no LDS, every weight byte is read once;
 //   - each wavefront owns R 16-row tiles of W and a contiguous range of k; the
-//     token rows X (<= 128 x K bf16, L2 resident) are the column operand and are
-//     re-used across the R tiles;
+//     token rows X (<= 128 x K bf16, L2 resident) are the column operand, staged
+//     once per workgroup through LDS in operand order (the 4 wavefronts of a
+//     workgroup share the k range) and re-used across the R tiles: fetching them
+//     per wavefront cost as much L2 bandwidth as the weights themselves;
 //   - two register buffers of U k-steps each keep 2*U*R KiB of weights in flight
 //     per wavefront while the other buffer is consumed;
 //   - split-K across workgroups fills all 256 CUs; partial sums go to a float
@@ -23,27 +25,39 @@ namespace fxp {
 template <int MT, int R, int U>
 __global__ __launch_bounds__(256) void gemm_skinny_kernel(SkinnyArgs a)
 {
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    constexpr int kXChunks = U * MT * 64;            // 16-byte chunks of one staged group of token rows
+    constexpr int kXPerThread = (kXChunks + 255) / 256;
+    __shared__ u32x4 s_x[2][kXChunks];
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int nt0 = (blockIdx.x * 4 + wave) * R;
-    if (nt0 >= a.NT) return;
     const int s = blockIdx.y;
     const int ks_begin = (int)((int64_t)a.KS * s / a.S);
     const int ks_end = (int)((int64_t)a.KS * (s + 1) / a.S);
+    const int ng = (ks_end - ks_begin + U - 1) / U;  // groups of U k-steps, the last one may be partial
 
     const u32x4 *wp[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-        const int nt = min(nt0 + r, a.NT - 1);
+        const int nt = min(nt0 + r, a.NT - 1);        // tiles past the end are clamped and never stored
         wp[r] = reinterpret_cast<const u32x4 *>(a.W) + (int64_t)nt * a.KS * 64 + lane;
     }
-    const int mrow = lane & 15, kc = (lane >> 4) * 8;
-    const uint16_t *xp[MT];
-    bool mvalid[MT];
+
+    // Staging of the token rows: chunk q of a group is the 16 bytes that lane q%64 feeds to the
+    // MFMA as column operand of (k-step q/64/MT, row tile q/64%MT): row = tile*16 + lane%16,
+    // k = step*32 + 8*(lane/16).  Written to LDS in that order, each operand is one linear,
+    // conflict-free 1 KiB read, and every token value is fetched from L2 once per workgroup
+    // instead of once per wavefront.
+    const uint16_t *xsrc[kXPerThread];
+    int xstep[kXPerThread], xkc[kXPerThread];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        const int m = mt * 16 + mrow;
-        mvalid[mt] = m < a.M;
-        xp[mt] = a.X + (int64_t)min(m, a.M - 1) * a.ldx + kc;
+    for (int i = 0; i < kXPerThread; ++i) {
+        const int q = min(i * 256 + tid, kXChunks - 1);
+        const int lane_op = q & 63, t2 = q >> 6;
+        const int mt = t2 % MT;
+        xstep[i] = t2 / MT;
+        xkc[i] = (lane_op >> 4) * 8;
+        xsrc[i] = a.X + (int64_t)min(mt * 16 + (lane_op & 15), a.M - 1) * a.ldx + xkc[i];   // rows past M: clamped, never stored
     }
 
     f32x4_t acc[R][MT];
@@ -52,48 +66,74 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(SkinnyArgs a)
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) acc[r][mt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-    auto load = [&](u32x4(&w)[U][R], u32x4(&x)[U][MT], int ks0) {
+    // Everything below is branch-free inside the loop body (indices clamped, invalid k-steps
+    // get a zero token operand): a load under a branch makes the compiler's wait-count
+    // insertion assume the worst path and drain the prefetch queue before every MFMA group.
+    auto load_w = [&](u32x4(&w)[U][R], int g) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int ks = min(ks0 + u, ks_end - 1);
+            const int ksc = min(ks_begin + g * U + u, ks_end - 1);
 #pragma unroll
-            for (int r = 0; r < R; ++r) w[u][r] = __builtin_nontemporal_load(wp[r] + (int64_t)ks * 64);
-            const bool kok = ks * 32 + kc + 8 <= a.K;
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                x[u][mt] = u32x4{0u, 0u, 0u, 0u};
-                if (mvalid[mt] && kok) x[u][mt] = ld16(xp[mt] + ks * 32);
-            }
+            for (int r = 0; r < R; ++r) w[u][r] = __builtin_nontemporal_load(wp[r] + (int64_t)ksc * 64);
         }
     };
-    auto mma = [&](u32x4(&w)[U][R], u32x4(&x)[U][MT], int ks0) {
+    auto load_x = [&](u32x4(&x)[kXPerThread], int g) {
+#pragma unroll
+        for (int i = 0; i < kXPerThread; ++i) {
+            const int ks = ks_begin + g * U + xstep[i];
+            const int ksc = min(ks, ks_end - 1);
+            const bool valid = ks < ks_end && ksc * 32 + xkc[i] + 8 <= a.K;
+            const u32x4 v = ld16(xsrc[i] + (valid ? ksc * 32 : 0));
+            x[i] = valid ? v : u32x4{0u, 0u, 0u, 0u};
+        }
+    };
+    auto store_x = [&](const u32x4(&x)[kXPerThread], int buf) {
+#pragma unroll
+        for (int i = 0; i < kXPerThread; ++i)
+            if (kXChunks % 256 == 0 || i * 256 + tid < kXChunks) s_x[buf][i * 256 + tid] = x[i];
+    };
+    auto mma = [&](const u32x4(&w)[U][R], int buf) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            if (ks0 + u < ks_end) {
+            u32x4 xop[MT];
 #pragma unroll
-                for (int r = 0; r < R; ++r)
+            for (int mt = 0; mt < MT; ++mt) xop[mt] = s_x[buf][(u * MT + mt) * 64 + lane];
 #pragma unroll
-                    for (int mt = 0; mt < MT; ++mt)
-                        acc[r][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                            __builtin_bit_cast(bf16x8_t, w[u][r]), __builtin_bit_cast(bf16x8_t, x[u][mt]),
-                            acc[r][mt], 0, 0, 0);
-            }
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+                    acc[r][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                        __builtin_bit_cast(bf16x8_t, w[u][r]), __builtin_bit_cast(bf16x8_t, xop[mt]),
+                        acc[r][mt], 0, 0, 0);
         }
     };
 
-    if (ks_begin < ks_end) {
-        u32x4 w0[U][R], x0[U][MT], w1[U][R], x1[U][MT];
-        load(w0, x0, ks_begin);
-        for (int ks = ks_begin; ks < ks_end; ks += 2 * U) {
-            if (ks + U < ks_end) load(w1, x1, ks + U);
-            mma(w0, x0, ks);
-            if (ks + 2 * U < ks_end) load(w0, x0, ks + 2 * U);
-            if (ks + U < ks_end) mma(w1, x1, ks + U);
+    if (ng > 0) {
+        u32x4 w0[U][R], w1[U][R], xg[kXPerThread];
+        load_x(xg, 0);
+        load_w(w0, 0);
+        store_x(xg, 0);
+        load_x(xg, 1);
+        __syncthreads();
+        for (int g = 0; g < ng; g += 2) {
+            // even group: weights of g in w0, token rows of g in s_x[0], rows of g+1 in xg
+            load_w(w1, g + 1);
+            mma(w0, 0);
+            store_x(xg, 1);
+            load_x(xg, g + 2);
+            __syncthreads();
+            if (g + 1 >= ng) break;
+            load_w(w0, g + 2);
+            mma(w1, 1);
+            store_x(xg, 0);
+            load_x(xg, g + 3);
+            __syncthreads();
         }
     }
 
     // accumulator layout of the 16x16 MFMA: lane l, element v holds D[row 4*(l/16)+v][col l%16]
     // with rows = weight rows n and columns = token rows m: four consecutive n per lane.
+    const int mrow = lane & 15;
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         if (nt0 + r >= a.NT) continue;
@@ -118,9 +158,10 @@ static hipError_t launch_cfg(const SkinnyArgs &a, hipStream_t stream)
 template <int MT, int U>
 static hipError_t launch_r(const SkinnyArgs &a, hipStream_t stream)
 {
+    const bool deep = a.U >= 2 * U && MT <= 2;       // deeper prefetch only where the registers allow it
     switch (a.R) {
-    case 1: return launch_cfg<MT, 1, U>(a, stream);
-    case 2: return launch_cfg<MT, 2, U>(a, stream);
+    case 1: return deep ? launch_cfg<MT, 1, (MT <= 2 ? 2 * U : U)>(a, stream) : launch_cfg<MT, 1, U>(a, stream);
+    case 2: return deep ? launch_cfg<MT, 2, (MT <= 2 ? 2 * U : U)>(a, stream) : launch_cfg<MT, 2, U>(a, stream);
     case 4: return launch_cfg<MT, 4, (MT == 8 ? 1 : U)>(a, stream);
     default: return hipErrorInvalidValue;
     }

@@ -45,6 +45,7 @@ struct SkinnyArgs {
     float *P;              // partial sums [S][M][N]
     int M, N, K, KS, NT, ldx, S;   // KS = padded K / 32, NT = N / 16
     int R;                         // 16-row weight tiles per wavefront: 1, 2 or 4
+    int U;                         // k-steps per prefetch group: 4 or 8 (8 only for R <= 2, M <= 32)
 };
 hipError_t launch_gemm_skinny(const SkinnyArgs &a, hipStream_t stream);
 
