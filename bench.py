@@ -40,11 +40,78 @@ def read_traffic(path: str, kernel: str):
     return None
 
 
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 peak
+
+
+def bench_prefill(args, wl) -> int:
+    """Secondary mode (--workload C3): one step = the chunked-prefill forward of the whole ragged
+    batch (prompts log-uniform in [256,2048], empty cache).  Reports prefill tokens/s and the MFMA
+    roofline of the tiled projection kernel."""
+    import torch
+    from paper_2510_11938_amd import binding, synth
+    ms, L, B = wl.shape, wl.n_layers, wl.num_seqs
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    def to_dev(bits):
+        return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(dev).view(torch.bfloat16)
+
+    lens = synth.draw_lengths(wl.length_dist, B, wl.seed)
+    T = int(lens.sum())
+    table, nblk = synth.block_table(lens, 16, wl.seed)
+    w_dev = [{k: to_dev(v) for k, v in synth.layer_weights(ms, wl.seed, l).items()} for l in range(L)]
+    stage = binding.Stage(ms, 0, L, w_dev)
+    torch.cuda.synchronize()
+    del w_dev
+    cache = binding.KVCache(torch.zeros((L, nblk, 2, ms.n_kv_heads, 16, ms.head_dim), dtype=torch.int16, device=dev), 0, L,
+                            torch.from_numpy(table).to(dev))
+    x = to_dev(synth.hidden_states(T, ms.hidden, wl.seed))
+    y = torch.empty_like(x)
+    cu = torch.from_numpy(synth.cu_seqlens(lens)).to(dev)
+    cl = torch.zeros(B, dtype=torch.int32, device=dev)
+    mq = int(lens.max())
+
+    def step():
+        stage.forward(cache, cu, cl, x, mq, hidden_out=y)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    binding.profile_enable(True)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    prof = binding.profile_read()
+    binding.profile_enable(False)
+    kernels = {k: {"avg_us": v["ms"] * 1e3 / v["launches"], "launches_per_step": v["launches"] / args.steps} for k, v in prof.items()}
+    flops_layer = 2 * T * (ms.params_per_layer - 2 * ms.hidden)          # the four projections of one layer
+    gemm_ms_layer = kernels["gemm_tiled"]["avg_us"] * 4 / 1e3
+    tflops = flops_layer / (gemm_ms_layer * 1e-3) / 1e12
+    out = {
+        "metric": "stage prefill tokens/s (7B shape, 4 layers, 16 ragged prompts)", "value": T / (ms_per_step * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {ms.hidden}-hidden {ms.n_q_heads}/{ms.n_kv_heads}x{ms.head_dim} heads, ffn {ms.ffn}, {L} layers, "
+                               f"{B} prompts {wl.length_dist}, {T} tokens, kv block 16", "seed": wl.seed},
+        "roofline": {"kernel": "gemm_tiled_kernel", "bound": "mfma", "achieved": tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                     "algorithmic_flops_per_layer": flops_layer, "avg_launch_us": kernels["gemm_tiled"]["avg_us"]},
+        "kernels": kernels,
+    }
+    print(json.dumps(out))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=None, help="timed steps (default 50 for decode, 5 for prefill)")
+    ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="C2", help="synthetic workload id (C2 is the headline configuration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-seqs", type=int, default=0, help="sequences the oracle is timed on (0 = the whole batch)")
@@ -58,9 +125,12 @@ def main() -> int:
     from paper_2510_11938_amd import binding, synth
 
     wl = synth.WORKLOADS[args.workload]
-    if wl.kind != "decode":
-        print("bench.py: the benchmark step is a decode step; pick a decode workload", file=sys.stderr)
-        return 2
+    if args.steps is None:
+        args.steps = 50 if wl.kind == "decode" else 5
+    if args.warmup is None:
+        args.warmup = 10 if wl.kind == "decode" else 2
+    if wl.kind == "prefill":
+        return bench_prefill(args, wl)
     ms, L, B = wl.shape, wl.n_layers, wl.num_seqs
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)

@@ -1,16 +1,25 @@
 // Large-M projection for prefill-sized batches:  C[m][n] = sum_k X[m][k] * W[n][k]
 // (+ fused epilogue).  MFMA-bound: v_mfma_f32_16x16x32_bf16, float accumulators.
 //
-// Workgroup tile: 256 weight rows x 128 token rows, k in steps of 64.
+// Workgroup tile: 256 weight rows x 128 token rows, k in steps of 32 (one MFMA k-step).
 //   - 4 waves stacked along n: each owns 64 weight rows (4 row tiles) and all
 //     128 token rows (8 column tiles) -> 32 accumulator tiles, 128 registers;
 //   - the weight operand is never shared between waves, and W is stored in
-//     MFMA operand order (weight_pack.hip), so it streams HBM/L2 -> registers
-//     directly, 1 KiB contiguous per load, one k-step ahead;
-//   - the token-row operand is shared by the 4 waves: it is staged through LDS
-//     (double buffered, rows padded to 144 bytes so the 16-byte operand reads
-//     of 16 consecutive rows hit distinct banks), next tile fetched to registers
-//     while the current one is multiplied.
+//     MFMA operand order (weight_pack.hip), so it streams L2 -> registers
+//     directly, 1 KiB contiguous per load, through a 3-deep register ring
+//     (loads issued two k-steps before use);
+//   - the token-row operand is shared by the 4 waves: it goes global -> registers
+//     -> LDS in stages of 64 k (two k-steps), fetched one stage ahead with full
+//     128-byte lines per row, and is stored in MFMA operand order with a slot
+//     swizzle so that both the staging writes and the linear-by-lane operand
+//     reads are free of bank conflicts; two LDS buffers, one barrier per stage;
+//   - the 32 MFMAs of a k-step are four inline-assembly blocks that issue the
+//     LDS reads of the next operand pair ahead of the current pair's MFMAs;
+//   - every load is unconditional (clamped index + select): a load under a branch
+//     makes the compiler drain the whole prefetch queue at the next wait.
+// Workgroups are numbered so that the 32 that run together on one XCD (they share
+// an L2) form a 4 x 8 block of tiles and walk k in step: each weight k-slice is
+// fetched into that L2 once per 8 workgroups, each token k-slice once per 4.
 // Epilogues (in registers, each lane holds 4 consecutive n of one token row):
 //   plain bf16 store; + residual; SwiGLU over gate/up row tiles interleaved at
 //   pack time.
@@ -20,37 +29,60 @@
 namespace fxp {
 
 constexpr int kTgThreads = 256;
-constexpr int kTgBM = 128, kTgBN = 256, kTgBK = 64;
+constexpr int kTgBM = 128, kTgBN = 256;
 constexpr int kTgRn = 4, kTgRm = 8;
-constexpr int kTgPitch = kTgBK * 2 + 16;                 // bytes per LDS row
-constexpr int kTgStage = kTgBM * kTgBK / 8 / kTgThreads;  // 16-byte chunks per thread per tile (4)
+constexpr int kTgStages = 2;                               // LDS stages of two k-steps (64 k) each
+constexpr int kTgXChunks = 2 * kTgRm * 64;                 // 16-byte chunks of one stage (16 KiB)
+constexpr int kTgXPerThread = kTgXChunks / kTgThreads;     // 4
 
-template <int EPI>
+template <int EPI, bool K_TAIL>
 __global__ __launch_bounds__(kTgThreads, 2) void gemm_tiled_kernel(TiledArgs a)
 {
-    __shared__ __attribute__((aligned(16))) char s_x[2][kTgBM * kTgPitch];
+    __shared__ u32x4 s_x[kTgStages][kTgXChunks];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int col = lane & 15, c = lane >> 4;
-    const int tiles_n = (a.NT * 16 + kTgBN - 1) / kTgBN;
-    const int tile_n = blockIdx.x % tiles_n, tile_m = blockIdx.x / tiles_n;
+
+    // ---- tile of this workgroup (XCD-aware numbering, see the header comment)
+    const int tiles_n = (a.NT * 16 + kTgBN - 1) / kTgBN, tiles_m = (a.M + kTgBM - 1) / kTgBM;
+    int tile_m, tile_n;
+    {
+        constexpr int kXcds = 8, kBlkN = 4, kBlkM = 8;      // 32 workgroups of one XCD = 4 x 8 tiles
+        const int blocks_n = (tiles_n + kBlkN - 1) / kBlkN;
+        const int id = blockIdx.x;
+        const int xcd = id % kXcds, seq = id / kXcds;          // seq-th workgroup given to this XCD
+        const int super = seq / (kBlkN * kBlkM), within = seq % (kBlkN * kBlkM);
+        const int sb = super * kXcds + xcd;                   // super-block index
+        tile_n = (sb % blocks_n) * kBlkN + within % kBlkN;
+        tile_m = (sb / blocks_n) * kBlkM + within / kBlkN;
+    }
+    if (tile_n >= tiles_n || tile_m >= tiles_m) return;
     const int m0 = tile_m * kTgBM;
     const int nt0 = tile_n * (kTgBN / 16) + wave * kTgRn;     // first 16-row tile of this wave
-    const int KT = a.KS / 2;                                   // 64-wide k tiles (K padded to 64)
+    const int KS = a.KS;
 
     const u32x4 *wp[kTgRn];
 #pragma unroll
     for (int r = 0; r < kTgRn; ++r)
-        wp[r] = reinterpret_cast<const u32x4 *>(a.W) + (int64_t)min(nt0 + r, a.NT - 1) * a.KS * 64 + lane;
+        wp[r] = reinterpret_cast<const u32x4 *>(a.W) + (int64_t)min(nt0 + r, a.NT - 1) * KS * 64 + lane;
 
-    // staging map: chunk q = i*256 + tid -> row q/8, 16-byte chunk q%8 of the 64-wide k tile
-    const uint16_t *xsrc[kTgStage];
-    int xoff[kTgStage], xk[kTgStage];
+    // Staging map.  Global side: chunk q = i*256 + tid is 16 bytes of token row q/8, k-chunk q%8
+    // of the 64-wide stage, so 8 consecutive lanes fetch one full 128-byte line (a wave
+    // instruction that touches 16 rows with 64 bytes each, as the operand order would have it,
+    // costs twice the cache-line requests and was the largest stall of this kernel).
+    // LDS side: the chunk belongs to k-step h = (q%8)/4, column tile mt = row/16, operand lane
+    // (m16 = row%16, c = (q%8)%4).  Inside the 1 KiB operand block it is stored at slot
+    // 16*c + ((m16 + 2*c + 8*h) & 15): a bijection per block, so the linear-by-lane operand
+    // reads stay conflict-free, and the 16 lanes of one LDS write cycle (2 rows x 8 chunks)
+    // hit 16 different 16-byte bank groups.
+    const uint16_t *xsrc[kTgXPerThread];
+    int xdst[kTgXPerThread], xkc[kTgXPerThread];
 #pragma unroll
-    for (int i = 0; i < kTgStage; ++i) {
-        const int q = i * kTgThreads + tid, r = q >> 3, ch = q & 7;
-        xsrc[i] = a.X + (int64_t)min(m0 + r, a.M - 1) * a.ldx + ch * 8;
-        xoff[i] = r * kTgPitch + ch * 16;
-        xk[i] = ch * 8;
+    for (int i = 0; i < kTgXPerThread; ++i) {
+        const int q = i * kTgThreads + tid, row = q >> 3, ch = q & 7;
+        const int h = ch >> 2, cc = ch & 3, mt = row >> 4, m16 = row & 15;
+        xkc[i] = ch * 8;
+        xsrc[i] = a.X + (int64_t)min(m0 + row, a.M - 1) * a.ldx + xkc[i];
+        xdst[i] = (h * kTgRm + mt) * 64 + 16 * cc + ((m16 + 2 * cc + 8 * h) & 15);
     }
 
     f32x4_t acc[kTgRn][kTgRm];
@@ -59,53 +91,117 @@ __global__ __launch_bounds__(kTgThreads, 2) void gemm_tiled_kernel(TiledArgs a)
 #pragma unroll
         for (int mt = 0; mt < kTgRm; ++mt) acc[r][mt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-    u32x4 xreg[kTgStage], wcur[2][kTgRn], wnext[2][kTgRn];
-    auto fetch_x = [&](int kt) {
+    auto fetch_w = [&](u32x4(&w)[kTgRn], int ks) {
+        const int ksc = min(ks, KS - 1);
 #pragma unroll
-        for (int i = 0; i < kTgStage; ++i) {
-            xreg[i] = u32x4{0u, 0u, 0u, 0u};
-            if (kt * kTgBK + xk[i] + 8 <= a.K) xreg[i] = ld16(xsrc[i] + kt * kTgBK);
-        }
+        for (int r = 0; r < kTgRn; ++r) w[r] = wp[r][(int64_t)ksc * 64];
     };
-    auto store_x = [&](int buf) {
+    const int KT = KS / 2;                                    // stages (K is padded to 64)
+    auto fetch_x = [&](u32x4(&x)[kTgXPerThread], int kt) {
+        const int ktc = min(kt, KT - 1);
 #pragma unroll
-        for (int i = 0; i < kTgStage; ++i) *reinterpret_cast<u32x4 *>(s_x[buf] + xoff[i]) = xreg[i];
-    };
-    auto fetch_w = [&](u32x4(&w)[2][kTgRn], int kt) {
-#pragma unroll
-        for (int h = 0; h < 2; ++h)
-#pragma unroll
-            for (int r = 0; r < kTgRn; ++r) w[h][r] = wp[r][(int64_t)(kt * 2 + h) * 64];
-    };
-
-    fetch_x(0);
-    fetch_w(wcur, 0);
-    store_x(0);
-    __syncthreads();
-    for (int kt = 0; kt < KT; ++kt) {
-        const bool more = kt + 1 < KT;
-        if (more) { fetch_x(kt + 1); fetch_w(wnext, kt + 1); }
-        const char *xb = s_x[kt & 1];
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-#pragma unroll
-            for (int mt = 0; mt < kTgRm; ++mt) {
-                const u32x4 xop = *reinterpret_cast<const u32x4 *>(xb + (mt * 16 + col) * kTgPitch + h * 64 + c * 16);
-#pragma unroll
-                for (int r = 0; r < kTgRn; ++r)
-                    acc[r][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                        __builtin_bit_cast(bf16x8_t, wcur[h][r]), __builtin_bit_cast(bf16x8_t, xop), acc[r][mt], 0, 0, 0);
+        for (int i = 0; i < kTgXPerThread; ++i) {
+            if constexpr (K_TAIL) {                         // K not a multiple of 64: zero operand past the end
+                const bool ok = ktc * 64 + xkc[i] + 8 <= a.K;
+                const u32x4 v = ld16(xsrc[i] + (ok ? ktc * 64 : 0));
+                x[i] = ok ? v : u32x4{0u, 0u, 0u, 0u};
+            } else {
+                x[i] = ld16(xsrc[i] + ktc * 64);
             }
         }
-        if (more) {
-            store_x((kt + 1) & 1);
+    };
+    auto store_x = [&](const u32x4(&x)[kTgXPerThread], int stage) {
 #pragma unroll
-            for (int h = 0; h < 2; ++h)
-#pragma unroll
-                for (int r = 0; r < kTgRn; ++r) wcur[h][r] = wnext[h][r];
-        }
-        __syncthreads();
+        for (int i = 0; i < kTgXPerThread; ++i) s_x[stage][xdst[i]] = x[i];
+    };
+    // One k-step of the wave tile: 8 column-tile operands from LDS, 32 MFMAs.  Written as four
+    // inline-assembly blocks because the compiler's scheduler puts every LDS read directly in
+    // front of its first use and then waits for it, which leaves the matrix pipe idle for the
+    // LDS latency eight times per step.  Here the reads of the next operand pair are issued
+    // before the 8 MFMAs of the current pair, and the wait (lgkmcnt(2): everything but the two
+    // reads just issued; LDS returns in order) is satisfied long before it is reached.
+    // lds_addr = byte address in LDS of this lane's 16 bytes of column tile 0 of the stage.
+#define FXP_MFMA8(X0, X1)                                                  \
+    "v_mfma_f32_16x16x32_bf16 %[a0], %[w0], %[" #X0 "], %[a0]\n"              \
+    "v_mfma_f32_16x16x32_bf16 %[a1], %[w1], %[" #X0 "], %[a1]\n"              \
+    "v_mfma_f32_16x16x32_bf16 %[a2], %[w2], %[" #X0 "], %[a2]\n"              \
+    "v_mfma_f32_16x16x32_bf16 %[a3], %[w3], %[" #X0 "], %[a3]\n"              \
+    "v_mfma_f32_16x16x32_bf16 %[b0], %[w0], %[" #X1 "], %[b0]\n"              \
+    "v_mfma_f32_16x16x32_bf16 %[b1], %[w1], %[" #X1 "], %[b1]\n"              \
+    "v_mfma_f32_16x16x32_bf16 %[b2], %[w2], %[" #X1 "], %[b2]\n"              \
+    "v_mfma_f32_16x16x32_bf16 %[b3], %[w3], %[" #X1 "], %[b3]\n"
+#define FXP_ACC8(M)                                                                  \
+    [a0] "+v"(acc[0][M]), [a1] "+v"(acc[1][M]), [a2] "+v"(acc[2][M]), [a3] "+v"(acc[3][M]),         \
+    [b0] "+v"(acc[0][M + 1]), [b1] "+v"(acc[1][M + 1]), [b2] "+v"(acc[2][M + 1]), [b3] "+v"(acc[3][M + 1])
+#define FXP_WOPS [w0] "v"(w[0]), [w1] "v"(w[1]), [w2] "v"(w[2]), [w3] "v"(w[3])
+    auto compute = [&](const u32x4(&w)[kTgRn], uint32_t lds_addr) {
+        u32x4 p0, p1, q0, q1;
+        asm volatile("ds_read_b128 %[p0], %[addr]\n"
+                     "ds_read_b128 %[p1], %[addr] offset:1024\n"
+                     "ds_read_b128 %[q0], %[addr] offset:2048\n"
+                     "ds_read_b128 %[q1], %[addr] offset:3072\n"
+                     "s_waitcnt lgkmcnt(2)\n" FXP_MFMA8(p0, p1)
+                     : [p0] "=&v"(p0), [p1] "=&v"(p1), [q0] "=&v"(q0), [q1] "=&v"(q1), FXP_ACC8(0)
+                     : [addr] "v"(lds_addr), FXP_WOPS
+                     : "memory");
+        u32x4 r0, r1;
+        asm volatile("ds_read_b128 %[r0], %[addr] offset:4096\n"
+                     "ds_read_b128 %[r1], %[addr] offset:5120\n"
+                     "s_waitcnt lgkmcnt(2)\n" FXP_MFMA8(x0, x1)
+                     : [r0] "=&v"(r0), [r1] "=&v"(r1), FXP_ACC8(2)
+                     : [addr] "v"(lds_addr), FXP_WOPS, [x0] "v"(q0), [x1] "v"(q1)
+                     : "memory");
+        u32x4 t0, t1;
+        asm volatile("ds_read_b128 %[t0], %[addr] offset:6144\n"
+                     "ds_read_b128 %[t1], %[addr] offset:7168\n"
+                     "s_waitcnt lgkmcnt(2)\n" FXP_MFMA8(x0, x1)
+                     : [t0] "=&v"(t0), [t1] "=&v"(t1), FXP_ACC8(4)
+                     : [addr] "v"(lds_addr), FXP_WOPS, [x0] "v"(r0), [x1] "v"(r1)
+                     : "memory");
+        asm volatile("s_waitcnt lgkmcnt(0)\n" FXP_MFMA8(x0, x1)
+                     : FXP_ACC8(6)
+                     : FXP_WOPS, [x0] "v"(t0), [x1] "v"(t1)
+                     : "memory");
+    };
+#undef FXP_MFMA8
+#undef FXP_ACC8
+#undef FXP_WOPS
+    // byte address in LDS of this lane's operand slot of column tile 0, for k-step half h of stage 0
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)(&s_x[0][0]);
+    const uint32_t lds_h0 = lds_base + (16 * c + ((col + 2 * c) & 15)) * 16;
+    const uint32_t lds_h1 = lds_base + (kTgRm * 64 + 16 * c + ((col + 2 * c + 8) & 15)) * 16;
+    constexpr uint32_t kStageBytes = kTgXChunks * 16;
+
+    // Weights: ring of three k-steps (w(ks), w(ks+1) resident, w(ks+2) in flight).  Token rows:
+    // stage t+1 is fetched to registers at the start of stage t and written to the other LDS
+    // buffer at its end, one barrier per stage.  Three stages (six k-steps) per trip so that
+    // every register set keeps its name.
+    u32x4 w0[kTgRn], w1[kTgRn], w2[kTgRn], xg[kTgXPerThread];
+    fetch_x(xg, 0);
+    fetch_w(w0, 0);
+    fetch_w(w1, 1);
+    store_x(xg, 0);
+    __syncthreads();
+#define FXP_TG_STAGE(WA, WB, WC2, WD2, KTV)                                   \
+    fetch_x(xg, (KTV) + 1);                                                    \
+    fetch_w(WC2, 2 * (KTV) + 2);                                               \
+    compute(WA, lds_h0 + ((KTV) & 1) * kStageBytes);                           \
+    fetch_w(WD2, 2 * (KTV) + 3);                                               \
+    compute(WB, lds_h1 + ((KTV) & 1) * kStageBytes);                           \
+    store_x(xg, ((KTV) & 1) ^ 1);                                              \
+    __syncthreads();
+    // k-step s lives in weight set s % 3, so the set names repeat every three stages
+    int kt = 0;
+    for (; kt + 3 <= KT; kt += 3) {
+        FXP_TG_STAGE(w0, w1, w2, w0, kt)          // k-steps 6j,   6j+1; fetches w(6j+2) -> w2, w(6j+3) -> w0
+        FXP_TG_STAGE(w2, w0, w1, w2, kt + 1)      // k-steps 6j+2, 6j+3; fetches w(6j+4) -> w1, w(6j+5) -> w2
+        FXP_TG_STAGE(w1, w2, w0, w1, kt + 2)      // k-steps 6j+4, 6j+5; fetches w(6j+6) -> w0, w(6j+7) -> w1
     }
+    if (kt < KT) {
+        FXP_TG_STAGE(w0, w1, w2, w0, kt)
+        if (kt + 1 < KT) { FXP_TG_STAGE(w2, w0, w1, w2, kt + 1) }
+    }
+#undef FXP_TG_STAGE
 
     // ---- epilogue
 #pragma unroll
@@ -145,13 +241,20 @@ hipError_t launch_gemm_tiled(const TiledArgs &a, hipStream_t stream)
 {
     const int tiles_n = (a.NT * 16 + kTgBN - 1) / kTgBN;
     const int tiles_m = (a.M + kTgBM - 1) / kTgBM;
-    dim3 grid(tiles_n * tiles_m);
+    // the XCD-aware numbering covers whole 4 x 8 super-blocks, rounded up to a multiple of 8 of them
+    const int blocks = ((tiles_n + 3) / 4) * ((tiles_m + 7) / 8);
+    dim3 grid((blocks + 7) / 8 * 8 * 32);
+    const bool tail = a.K % 32 != 0;
+#define FXP_TG_LAUNCH(E)                                                                                       \
+    if (tail) hipLaunchKernelGGL((gemm_tiled_kernel<E, true>), grid, dim3(kTgThreads), 0, stream, a);          \
+    else hipLaunchKernelGGL((gemm_tiled_kernel<E, false>), grid, dim3(kTgThreads), 0, stream, a);
     switch (a.epilogue) {
-    case kEpiStore: hipLaunchKernelGGL(gemm_tiled_kernel<kEpiStore>, grid, dim3(kTgThreads), 0, stream, a); break;
-    case kEpiResidual: hipLaunchKernelGGL(gemm_tiled_kernel<kEpiResidual>, grid, dim3(kTgThreads), 0, stream, a); break;
-    case kEpiSwiglu: hipLaunchKernelGGL(gemm_tiled_kernel<kEpiSwiglu>, grid, dim3(kTgThreads), 0, stream, a); break;
+    case kEpiStore: FXP_TG_LAUNCH(kEpiStore) break;
+    case kEpiResidual: FXP_TG_LAUNCH(kEpiResidual) break;
+    case kEpiSwiglu: FXP_TG_LAUNCH(kEpiSwiglu) break;
     default: return hipErrorInvalidValue;
     }
+#undef FXP_TG_LAUNCH
     return hipGetLastError();
 }
 
