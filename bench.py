@@ -41,6 +41,21 @@ def read_traffic(path: str, kernel: str):
 
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 peak
+CALIBRATION_COPY_BYTES = 1 << 30
+
+
+def calibration_copy(torch, dev) -> None:
+    """One plain device-to-device copy of a known size (1 GiB read + 1 GiB written).  It is not
+    timed; a `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` run of this same command reads the
+    counters of this copy kernel next to those of the library's kernels, which gives the factor
+    that turns counter units into bytes."""
+    src = torch.empty(CALIBRATION_COPY_BYTES // 4, dtype=torch.int32, device=dev)
+    src.fill_(3)
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    dst.copy_(src)
+    torch.cuda.synchronize()
+
 
 
 def bench_prefill(args, wl) -> int:
@@ -103,6 +118,7 @@ def bench_prefill(args, wl) -> int:
                      "algorithmic_flops_per_layer": flops_layer, "avg_launch_us": kernels["gemm_tiled"]["avg_us"]},
         "kernels": kernels,
     }
+    calibration_copy(torch, dev)
     print(json.dumps(out))
     return 0
 
@@ -267,6 +283,7 @@ def main() -> int:
                                          f"({int(ctx[sample].sum())} cached tokens), {cpu_s:.2f} s of oracle time",
                                "gpu_vs_oracle_rel_l2": float(np.sqrt(((got - ref) ** 2).sum(axis=1) / (ref ** 2).sum(axis=1)).max()),
                                "gpu_vs_oracle_max_elem": float((np.abs(got - ref) / np.maximum(np.abs(ref), rms)).max())}
+    calibration_copy(torch, dev)
     print(json.dumps(out))
     return 0
 
