@@ -242,6 +242,201 @@ __global__ __launch_bounds__(kDecThreads) void attn_decode_kernel(DecodeAttnArgs
     }
 }
 
+// ---------------------------------------------------------------------------
+// Grouped-query variant (2..16 query heads per kv head).  With G query heads the
+// float pipe would need G FMAs per loaded K or V element and the kernel would be
+// bound by vector ALU long before HBM, so both products run on the matrix cores,
+// 32 keys (two cache blocks) at a time, with the same unit/worker/piece cut:
+//   S^T[key][head]  = K[key][:] . Q[head][:]    row operand = K rows straight from
+//                     the cache block, column operand = the group's query heads
+//                     (columns >= G are zero);  the accumulator leaves lane
+//                     (head j, group c) with keys 4c..4c+3 of each block;
+//   softmax per head column: 8 in-lane values, two cross-lane steps for the max
+//                     (the sum is kept per lane and reduced once per piece);
+//   O^T[dim][head] += V^T[dim][key] . P^T[key][head]   P^T in accumulator layout
+//                     is already the column operand (k slots 8c..8c+3 = block 0
+//                     keys 4c.., 8c+4.. = block 1 keys 4c..); V^T is read with the
+//                     LDS transpose load (ds_read_b64_tr_b16): the wave stores the
+//                     two V blocks row-major in its own LDS region and lane
+//                     (dim i, group c) receives V[key 4c+e][16*dt + i], e < 4.
+// Probabilities enter the second product rounded to bf16.
+template <int D, bool DEBUG>
+__global__ __launch_bounds__(kDecThreads, 2) void attn_decode_mfma_kernel(DecodeAttnArgs a)
+{
+    constexpr int KS = D / 32;                 // k-steps of the score product
+    constexpr int DT = D / 16;                 // 16-dim tiles of the output
+    constexpr int kVPitch = D * 2 + 32;        // bytes per V row in LDS: 8 rows land in 8 distinct 32-byte bank groups
+    constexpr int kVBlock = kBlockTokens * kVPitch;
+    typedef short v4s __attribute__((ext_vector_type(4)));
+
+    extern __shared__ int32_t s_dyn[];         // [num_seqs + 1] block prefix, then the per-wave V regions
+    __shared__ int32_t s_part[kDecThreads];
+    int32_t *s_prefix = s_dyn;
+    scan_blocks(a.ctx_lens, a.num_seqs, s_prefix, s_part);
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int col = lane & 15, c = lane >> 4;
+    const int Hkv = a.n_kv_heads, G = a.n_q_heads / Hkv;
+    char *s_v = reinterpret_cast<char *>(s_dyn) + ((a.num_seqs + 1) * 4 + 255) / 256 * 256 + wave * (2 * kVBlock);
+    const int64_t U = (int64_t)s_prefix[a.num_seqs] * Hkv;
+    const int64_t W = min((int64_t)gridDim.x * kDecWaves, U);
+    const int64_t wk = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * kDecWaves + wave));
+    if (wk >= W) return;
+    int64_t u = worker_begin(wk, U, W);
+    const int64_t u_end = worker_begin(wk + 1, U, W);
+    if (u >= u_end) return;
+
+    const int64_t head_bytes = (int64_t)kBlockTokens * D * 2;
+    const int64_t unit_bytes = 2 * (int64_t)Hkv * head_bytes;
+    const char *layer_base = reinterpret_cast<const char *>(a.pool) + (int64_t)a.layer_local * a.num_blocks * unit_bytes;
+
+    int seq;
+    {
+        int lo = 0, hi = a.num_seqs;
+        while (hi - lo > 1) { const int mid = (lo + hi) >> 1; if ((int64_t)s_prefix[mid] * Hkv <= u) lo = mid; else hi = mid; }
+        seq = lo;
+    }
+    // LDS addresses of this lane: where it stores V (row-major, 16 bytes per lane per load) and
+    // where it points the transpose load (lane j' of a 16-lane group supplies key 4c + j'/4,
+    // dims 4*(j'%4)..+3 of the 16-dim tile; the hardware hands lane i the four keys of dim i)
+    const int v_tr = (4 * c + (col >> 2)) * kVPitch + (col & 3) * 8;               // + dt*32 + block*kVBlock
+
+    while (u < u_end) {
+        while ((int64_t)s_prefix[seq + 1] * Hkv <= u) ++seq;
+        const int nb_seq = s_prefix[seq + 1] - s_prefix[seq];
+        const int64_t r = u - (int64_t)s_prefix[seq] * Hkv;
+        const int hk = (int)(r / nb_seq), blk0 = (int)(r % nb_seq);
+        const int nblk = (int)min((int64_t)(nb_seq - blk0), u_end - u);
+        const int n_keys = a.ctx_lens[seq] + 1;
+        const int32_t *trow = a.block_table + (int64_t)seq * a.max_blocks_per_seq + blk0;
+
+        // column operand: query head col of the group (zero beyond G), dims 32*s + 8*c .. +7
+        u32x4 qop[KS];
+        {
+            const uint16_t *qp = a.q + ((int64_t)seq * a.n_q_heads + hk * G + min(col, G - 1)) * D + c * 8;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const u32x4 v = ld16(qp + ks * 32);
+                qop[ks] = col < G ? v : u32x4{0u, 0u, 0u, 0u};
+            }
+        }
+        f32x4_t o[DT];
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) o[dt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        float m_run = -INFINITY, l_lane = 0.f;
+
+        // loads of one pair of blocks (the second may be missing: it is then the first again, fully masked)
+        auto load_pair = [&](int b, u32x4(&kop)[2][KS], u32x4(&vraw)[2][D / 32]) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int32_t phys = trow[min(b + h, nblk - 1)];
+                const char *kp = layer_base + (int64_t)phys * unit_bytes + (int64_t)hk * head_bytes;
+                const char *vp = kp + (int64_t)Hkv * head_bytes;
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks)      // row operand: key col, dims 32*ks + 8*c
+                    kop[h][ks] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(kp + col * (D * 2) + ks * 64 + c * 16));
+#pragma unroll
+                for (int i = 0; i < D / 32; ++i)     // plain row-major copy of the V block, 1 KiB per load
+                    vraw[h][i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(vp + i * 1024 + lane * 16));
+            }
+        };
+        auto consume_pair = [&](int b, const u32x4(&kop)[2][KS], const u32x4(&vraw)[2][D / 32]) {
+            // V blocks -> this wave's LDS region (rows past the sequence end are zeroed: a zero
+            // probability must not meet an uninitialised, possibly NaN, value)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int tbase = (blk0 + b + h) * kBlockTokens;
+                const bool present = b + h < nblk;
+#pragma unroll
+                for (int i = 0; i < D / 32; ++i) {
+                    constexpr int kRowsPerLoad = 1024 / (D * 2);     // 4 rows (D = 128) or 8 rows (D = 64) per load
+                    const int row = i * kRowsPerLoad + (lane * 16) / (D * 2);
+                    const bool ok = present && tbase + row < n_keys;
+                    *reinterpret_cast<u32x4 *>(s_v + h * kVBlock + row * kVPitch + (lane * 16) % (D * 2)) =
+                        ok ? vraw[h][i] : u32x4{0u, 0u, 0u, 0u};
+                }
+            }
+            // scores of both blocks
+            float sc[2][4];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks)
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kop[h][ks]),
+                                                                  __builtin_bit_cast(bf16x8_t, qop[ks]), acc, 0, 0, 0);
+                const int tbase = (blk0 + b + h) * kBlockTokens;
+                const bool present = b + h < nblk;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int tok = tbase + 4 * c + v;
+                    const float sv = acc[v] * a.scale_log2e;
+                    const bool ok = present && tok < n_keys;
+                    sc[h][v] = ok ? sv : -INFINITY;
+                    if constexpr (DEBUG) {
+                        if (ok && col < G) a.dbg_scores[((int64_t)seq * a.n_q_heads + hk * G + col) * a.dbg_stride + tok] = sv;
+                    }
+                }
+            }
+            float mx = m_run;
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) mx = fmaxf(mx, sc[h][v]);
+            mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float ms = (mx == -INFINITY) ? 0.f : mx;
+            const float alpha = fast_exp2(m_run - ms);
+            m_run = mx;
+            float p[8], psum = 0.f;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) { p[v] = fast_exp2(sc[0][v] - ms); p[4 + v] = fast_exp2(sc[1][v] - ms); }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) psum += p[e];
+            l_lane = l_lane * alpha + psum;
+            const u32x4 pop = {pack_bf16x2(p[0], p[1]), pack_bf16x2(p[2], p[3]), pack_bf16x2(p[4], p[5]), pack_bf16x2(p[6], p[7])};
+            __builtin_amdgcn_wave_barrier();     // the V rows above are in LDS before the transpose loads below
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) {
+                const v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (__attribute__((address_space(3))) v4s *)(s_v + v_tr + dt * 32));
+                const v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (__attribute__((address_space(3))) v4s *)(s_v + kVBlock + v_tr + dt * 32));
+                const u32x2 lo2 = __builtin_bit_cast(u32x2, lo), hi2 = __builtin_bit_cast(u32x2, hi);
+                const u32x4 vop = {lo2.x, lo2.y, hi2.x, hi2.y};
+                o[dt] *= alpha;
+                o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, vop),
+                                                                __builtin_bit_cast(bf16x8_t, pop), o[dt], 0, 0, 0);
+            }
+            __builtin_amdgcn_wave_barrier();     // the next pair's V stores stay behind these loads
+        };
+
+        {
+            u32x4 k0[2][KS], v0[2][D / 32], k1[2][KS], v1[2][D / 32];
+            load_pair(0, k0, v0);
+            for (int b = 0; b < nblk; b += 4) {
+                if (b + 2 < nblk) load_pair(b + 2, k1, v1);
+                consume_pair(b, k0, v0);
+                if (b + 4 < nblk) load_pair(b + 4, k0, v0);
+                if (b + 2 < nblk) consume_pair(b + 2, k1, v1);
+            }
+        }
+
+        // the piece's state: sum over the four lane groups of a head column, then store
+        float l_tot = l_lane;
+        l_tot += __shfl_xor(l_tot, 16, 64);
+        l_tot += __shfl_xor(l_tot, 32, 64);
+        if (col < G) {
+            const int64_t slot = wk + (int64_t)seq * Hkv + hk;
+            float *pa = a.part_acc + (slot * G + col) * D + 4 * c;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) *reinterpret_cast<f32x4_t *>(pa + dt * 16) = o[dt];
+            if (c == 0) { a.part_ml[(slot * G + col) * 2] = m_run; a.part_ml[(slot * G + col) * 2 + 1] = l_tot; }
+        }
+        u += nblk;
+    }
+}
+
 // Merge the pieces of each (sequence, query head) in worker order and normalise:
 // o = sum_p acc_p 2^(m_p - m) / sum_p l_p 2^(m_p - m).  One workgroup per (sequence, kv head).
 template <bool DEBUG>
@@ -309,16 +504,29 @@ hipError_t launch_attn_decode_combine(const DecodeAttnArgs &a, hipStream_t strea
 
 bool decode_attn_supported(int head_dim, int group)
 {
-    return (head_dim == 64 || head_dim == 128) && (group == 1 || group == 2 || group == 4 || group == 8);
+    return (head_dim == 64 || head_dim == 128) && group >= 1 && group <= 16;
+}
+
+template <int D>
+static hipError_t launch_mfma(const DecodeAttnArgs &a, hipStream_t stream)
+{
+    const dim3 grid(a.n_workers / kDecWaves);
+    const size_t lds = ((size_t)(a.num_seqs + 1) * 4 + 255) / 256 * 256 + (size_t)kDecWaves * 2 * kBlockTokens * (D * 2 + 32);
+    if (a.dbg_scores) hipLaunchKernelGGL((attn_decode_mfma_kernel<D, true>), grid, dim3(kDecThreads), lds, stream, a);
+    else hipLaunchKernelGGL((attn_decode_mfma_kernel<D, false>), grid, dim3(kDecThreads), lds, stream, a);
+    return hipGetLastError();
 }
 
 hipError_t launch_attn_decode(const DecodeAttnArgs &a, hipStream_t stream)
 {
     const int G = a.n_q_heads / a.n_kv_heads;
-#define FXP_DG(DD, GG) if (a.head_dim == DD && G == GG) return launch_dg<DD, GG>(a, stream);
-    FXP_DG(128, 1) FXP_DG(128, 2) FXP_DG(128, 4) FXP_DG(128, 8)
-    FXP_DG(64, 1) FXP_DG(64, 2) FXP_DG(64, 4) FXP_DG(64, 8)
-#undef FXP_DG
+    if (G >= 2 && G <= 16) {          // grouped heads: matrix-core kernel
+        if (a.head_dim == 128) return launch_mfma<128>(a, stream);
+        if (a.head_dim == 64) return launch_mfma<64>(a, stream);
+        return hipErrorInvalidValue;
+    }
+    if (a.head_dim == 128 && G == 1) return launch_dg<128, 1>(a, stream);
+    if (a.head_dim == 64 && G == 1) return launch_dg<64, 1>(a, stream);
     return hipErrorInvalidValue;
 }
 

@@ -33,7 +33,8 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline int k_steps(int K) { return (K + 63) / 64 * 2; }                   // 32-wide steps, K padded to 64
 inline size_t packed_bytes(int N, int K) { return (size_t)(N / 16) * k_steps(K) * 1024; }
 
-constexpr int kSkinnyMaxTokens = 128;
+constexpr int kSkinnyMaxTokens = 128;     // up to here the projections run weight-streaming with split-K
+constexpr int kSkinnyWideTokens = 64;     // above this the split-K work goes to the tiled kernel's 128-row tile
 
 int check_desc(const fxp_stage_desc *d)
 {
@@ -44,7 +45,7 @@ int check_desc(const fxp_stage_desc *d)
     if (d->n_kv_heads <= 0 || d->n_q_heads <= 0 || d->n_q_heads % d->n_kv_heads)
         return fail(FXP_EINVAL, "n_q_heads (%d) must be a positive multiple of n_kv_heads (%d)", d->n_q_heads, d->n_kv_heads);
     if (!fxp::decode_attn_supported(d->head_dim, d->n_q_heads / d->n_kv_heads))
-        return fail(FXP_EINVAL, "query heads per kv head must be 1, 2, 4 or 8 (got %d)", d->n_q_heads / d->n_kv_heads);
+        return fail(FXP_EINVAL, "query heads per kv head must be 1..16 (got %d)", d->n_q_heads / d->n_kv_heads);
     if (d->hidden <= 0 || d->hidden % 16 || d->ffn <= 0 || d->ffn % 16)
         return fail(FXP_EINVAL, "hidden (%d) and ffn (%d) must be positive multiples of 16", d->hidden, d->ffn);
     if (!(d->rms_eps >= 0.f) || !(d->rope_base > 1.f)) return fail(FXP_EINVAL, "bad rms_eps or rope_base");
@@ -114,9 +115,11 @@ SkinnyCfg skinny_cfg(int N, int K, int M)
     // per CU streams fastest; more, thinner workgroups lose bandwidth, as do uneven k ranges,
     // hence power-of-two splits.
     c.R = forced_r ? forced_r : ((N >= 16384 && M <= 64) ? 4 : 2);
-    const int wgs_n = (N + 64 * c.R - 1) / (64 * c.R);
+    // above 64 rows the tiled kernel is used: its workgroup covers 256 weight rows
+    const int wgs_n = M > kSkinnyWideTokens ? (N + 255) / 256 : (N + 64 * c.R - 1) / (64 * c.R);
     int s = 1;
-    while (s * 2 <= 8 && s * 2 <= ks / 8 && wgs_n * s * 2 <= max_wgs) s *= 2;
+    const int limit = M > kSkinnyWideTokens ? 2 * max_wgs : max_wgs;    // the tiled kernel wants two workgroups per CU
+    while (s * 2 <= 8 && s * 2 <= ks / 8 && wgs_n * s * 2 <= limit) s *= 2;
     c.S = forced_s ? forced_s : s;
     return c;
 }
@@ -347,6 +350,16 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
     hipError_t e;
 
     auto project_skinny = [&](const char *wbase, const uint16_t *X, int N, int K, int ldx, int *S_out) -> hipError_t {
+        if (T > kSkinnyWideTokens) {
+            // 65..128 token rows: one 128-row tile of the tiled kernel covers the batch; split-K for parallelism
+            fxp::TiledArgs t;
+            t.W = (const uint16_t *)wbase; t.X = X; t.R = nullptr; t.C = nullptr; t.P = w.P;
+            t.M = T; t.K = K; t.KS = k_steps(K); t.NT = N / 16; t.ldx = ldx; t.ldc = 0; t.epilogue = fxp::kEpiPartial;
+            t.S = skinny_cfg(N, K, T).S;
+            *S_out = t.S;
+            KernelTimer kt(kKcSkinny, st);
+            return fxp::launch_gemm_tiled(t, st);
+        }
         fxp::SkinnyArgs a;
         a.W = (const uint16_t *)wbase; a.X = X; a.P = w.P;
         a.M = T; a.N = N; a.K = K; a.KS = k_steps(K); a.NT = N / 16; a.ldx = ldx; a.S = skinny_cfg(N, K, T).S; a.R = skinny_cfg(N, K, T).R; a.U = env_int("FXP_SKINNY_U", 4);
@@ -357,7 +370,7 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
     auto project_tiled = [&](const char *wbase, const uint16_t *X, int N, int K, int ldx, uint16_t *C, int ldc,
                              const uint16_t *R, int epi) -> hipError_t {
         fxp::TiledArgs a;
-        a.W = (const uint16_t *)wbase; a.X = X; a.R = R; a.C = C;
+        a.W = (const uint16_t *)wbase; a.X = X; a.R = R; a.C = C; a.P = nullptr; a.S = 1;
         a.M = T; a.K = K; a.KS = k_steps(K); a.NT = N / 16; a.ldx = ldx; a.ldc = ldc; a.epilogue = epi;
         KernelTimer kt(kKcTiled, st);
         return fxp::launch_gemm_tiled(a, st);

@@ -22,7 +22,9 @@
 // fetched into that L2 once per 8 workgroups, each token k-slice once per 4.
 // Epilogues (in registers, each lane holds 4 consecutive n of one token row):
 //   plain bf16 store; + residual; SwiGLU over gate/up row tiles interleaved at
-//   pack time.
+//   pack time; float partial sums of a k range (grid.y = split-K factor), used for
+//   decode batches of 65..128 tokens where one 128-row tile covers the batch and
+//   the k split supplies the parallelism.
 #include "kernels.h"
 #include "common.hip.h"
 
@@ -91,14 +93,16 @@ __global__ __launch_bounds__(kTgThreads, 2) void gemm_tiled_kernel(TiledArgs a)
 #pragma unroll
         for (int mt = 0; mt < kTgRm; ++mt) acc[r][mt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
+    // stages of 64 k (K is padded to 64); split s of S owns stages [kt0, kt0 + KT)
+    const int kt0 = (int)((int64_t)(KS / 2) * blockIdx.y / gridDim.y);
+    const int KT = (int)((int64_t)(KS / 2) * (blockIdx.y + 1) / gridDim.y) - kt0;
     auto fetch_w = [&](u32x4(&w)[kTgRn], int ks) {
-        const int ksc = min(ks, KS - 1);
+        const int ksc = 2 * kt0 + min(ks, 2 * KT - 1);
 #pragma unroll
         for (int r = 0; r < kTgRn; ++r) w[r] = wp[r][(int64_t)ksc * 64];
     };
-    const int KT = KS / 2;                                    // stages (K is padded to 64)
     auto fetch_x = [&](u32x4(&x)[kTgXPerThread], int kt) {
-        const int ktc = min(kt, KT - 1);
+        const int ktc = kt0 + min(kt, KT - 1);
 #pragma unroll
         for (int i = 0; i < kTgXPerThread; ++i) {
             if constexpr (K_TAIL) {                         // K not a multiple of 64: zero operand past the end
@@ -208,7 +212,14 @@ __global__ __launch_bounds__(kTgThreads, 2) void gemm_tiled_kernel(TiledArgs a)
     for (int mt = 0; mt < kTgRm; ++mt) {
         const int m = m0 + mt * 16 + col;
         if (m >= a.M) continue;
-        if constexpr (EPI == kEpiSwiglu) {
+        if constexpr (EPI == kEpiPartial) {
+#pragma unroll
+            for (int r = 0; r < kTgRn; ++r) {
+                if (nt0 + r >= a.NT) continue;
+                const int n = (nt0 + r) * 16 + 4 * c;
+                *reinterpret_cast<f32x4_t *>(a.P + ((int64_t)blockIdx.y * a.M + m) * (a.NT * 16) + n) = acc[r][mt];
+            }
+        } else if constexpr (EPI == kEpiSwiglu) {
 #pragma unroll
             for (int r = 0; r < kTgRn; r += 2) {
                 if (nt0 + r >= a.NT) continue;          // NT is even and nt0 + r is even: the pair is inside together
@@ -243,7 +254,7 @@ hipError_t launch_gemm_tiled(const TiledArgs &a, hipStream_t stream)
     const int tiles_m = (a.M + kTgBM - 1) / kTgBM;
     // the XCD-aware numbering covers whole 4 x 8 super-blocks, rounded up to a multiple of 8 of them
     const int blocks = ((tiles_n + 3) / 4) * ((tiles_m + 7) / 8);
-    dim3 grid((blocks + 7) / 8 * 8 * 32);
+    dim3 grid((blocks + 7) / 8 * 8 * 32, a.epilogue == kEpiPartial ? a.S : 1);
     const bool tail = a.K % 32 != 0;
 #define FXP_TG_LAUNCH(E)                                                                                       \
     if (tail) hipLaunchKernelGGL((gemm_tiled_kernel<E, true>), grid, dim3(kTgThreads), 0, stream, a);          \
@@ -252,6 +263,7 @@ hipError_t launch_gemm_tiled(const TiledArgs &a, hipStream_t stream)
     case kEpiStore: FXP_TG_LAUNCH(kEpiStore) break;
     case kEpiResidual: FXP_TG_LAUNCH(kEpiResidual) break;
     case kEpiSwiglu: FXP_TG_LAUNCH(kEpiSwiglu) break;
+    case kEpiPartial: FXP_TG_LAUNCH(kEpiPartial) break;
     default: return hipErrorInvalidValue;
     }
 #undef FXP_TG_LAUNCH

@@ -49,13 +49,15 @@ struct SkinnyArgs {
 };
 hipError_t launch_gemm_skinny(const SkinnyArgs &a, hipStream_t stream);
 
-enum { kEpiStore = 0, kEpiResidual = 1, kEpiSwiglu = 2 };
+enum { kEpiStore = 0, kEpiResidual = 1, kEpiSwiglu = 2, kEpiPartial = 3 };
 struct TiledArgs {
     const uint16_t *W;     // packed weights
     const uint16_t *X;     // token rows [M][ldx] bf16
     const uint16_t *R;     // residual [M][ldc] (kEpiResidual), may alias C
     uint16_t *C;           // output [M][ldc] bf16
+    float *P;              // kEpiPartial: float partial sums [S][M][NT*16]
     int M, K, KS, NT, ldx, ldc, epilogue;
+    int S;                 // kEpiPartial: split-K factor (grid.y)
 };
 hipError_t launch_gemm_tiled(const TiledArgs &a, hipStream_t stream);
 
