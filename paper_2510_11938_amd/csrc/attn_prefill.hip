@@ -15,8 +15,9 @@
 //                                         the column operand of the next MFMA
 //                                         (k slots 8c..8c+7 of lane group c are
 //                                         kv 4c..4c+3 of two 16-key sub-tiles);
-//                                         V^T comes from LDS, where the 64-key
-//                                         tile of V was stored transposed.
+//                                         V^T comes from the row-major V tile in
+//                                         LDS through the transpose load
+//                                         (ds_read_b64_tr_b16).
 // A workgroup is 4 waves x 16 query rows of one (sequence, query head); the
 // 64-key K and V tiles are staged once in LDS and shared by the 4 waves.
 // Probabilities enter the second product rounded to bf16; everything else is
@@ -39,9 +40,10 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_kernel(PrefillAttnArg
     constexpr int KS = D / 32;                    // k-steps of the QK product
     constexpr int DT = D / 16;                    // 16-dim tiles of the output
     constexpr int kKPitch = D * 2 + 16;           // bytes per K row in LDS (conflict-free 16-byte reads)
-    constexpr int kVPitch = (kPfKvTile + 4) * 2;  // bytes per V^T row in LDS (8-byte aligned)
+    constexpr int kVPitch = D * 2 + 32;           // bytes per V row in LDS: 8 rows land in 8 distinct 32-byte bank groups
+    typedef short v4s __attribute__((ext_vector_type(4)));
     __shared__ __attribute__((aligned(16))) char s_k[kPfKvTile * kKPitch];
-    __shared__ __attribute__((aligned(16))) char s_vt[D * kVPitch];
+    __shared__ __attribute__((aligned(16))) char s_v[kPfKvTile * kVPitch];
 
     const int qt = blockIdx.x, h = blockIdx.y, seq = blockIdx.z;
     const int t0 = a.cu_seqlens_q[seq];
@@ -82,7 +84,7 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_kernel(PrefillAttnArg
 
     for (int tile = 0; tile < n_tiles; ++tile) {
         const int kv0 = tile * kPfKvTile;
-        // ---- stage K (row-major, padded) and V (transposed) of keys kv0 .. kv0+63
+        // ---- stage K and V (both row-major, padded pitches) of keys kv0 .. kv0+63
         __syncthreads();
 #pragma unroll
         for (int i = 0; i < kChunksPerThread; ++i) {
@@ -98,14 +100,7 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_kernel(PrefillAttnArg
                 vvec = ld16(kp + (int64_t)a.n_kv_heads * head_elems);
             }
             *reinterpret_cast<u32x4 *>(s_k + r * kKPitch + dc * 16) = kvec;
-            uint16_t *vt = reinterpret_cast<uint16_t *>(s_vt);
-            const int d0 = dc * 8;
-            const uint32_t w[4] = {vvec.x, vvec.y, vvec.z, vvec.w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                vt[(d0 + 2 * e) * (kVPitch / 2) + r] = (uint16_t)(w[e] & 0xffffu);
-                vt[(d0 + 2 * e + 1) * (kVPitch / 2) + r] = (uint16_t)(w[e] >> 16);
-            }
+            *reinterpret_cast<u32x4 *>(s_v + r * kVPitch + dc * 16) = vvec;
         }
         __syncthreads();
         if (kv0 > wave_last_pos) continue;          // whole tile is in this wave's future (wave-uniform)
@@ -167,9 +162,11 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_kernel(PrefillAttnArg
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
                 // row operand: dim 16*dt + col; k slots 8c..8c+3 = keys 32u+4c.., 8c+4.. = keys 32u+16+4c..
-                const char *vrow = s_vt + (dt * 16 + col) * kVPitch + (32 * u + 4 * c) * 2;
-                const u32x2 lo = *reinterpret_cast<const u32x2 *>(vrow);
-                const u32x2 hi = *reinterpret_cast<const u32x2 *>(vrow + 32);
+                // LDS transpose load: lane j' of a 16-lane group points at key 4c + j'/4, dims
+                // 4*(j'%4)..+3 of the tile; the hardware hands lane i the four keys of dim i.
+                const char *vsrc = s_v + (32 * u + 4 * c + (col >> 2)) * kVPitch + dt * 32 + (col & 3) * 8;
+                const u32x2 lo = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s *)(vsrc)));
+                const u32x2 hi = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s *)(vsrc + 16 * kVPitch)));
                 const u32x4 vop = {lo.x, lo.y, hi.x, hi.y};
                 o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, vop),
                                                                 __builtin_bit_cast(bf16x8_t, pop[u]), o[dt], 0, 0, 0);
