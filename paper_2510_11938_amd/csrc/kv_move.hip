@@ -9,7 +9,7 @@
 // HBM-bound bit copy.  One launch moves every (job, layer, sequence, logical
 // block) unit.  The lengths live on the device, so each workgroup derives the
 // per-sequence block prefix sums itself (LDS scan over ctx_lens) and then walks
-// a grid-strided list of equal-sized 16 KiB work items: no empty workgroups for
+// a grid-strided list of equal-sized 32 KiB work items: no empty workgroups for
 // short sequences, no host synchronisation, no scratch memory.  Every lane
 // moves 16-byte vectors; a workgroup has four independent 4 KiB loads in flight
 // per lane-row before the first store.
@@ -19,8 +19,8 @@
 namespace fxp {
 
 constexpr int kMoveThreads = 256;
-constexpr int kMoveVecPerThread = 4;                                    // 16-byte vectors in flight per lane
-constexpr int kMoveChunkBytes = kMoveThreads * 16 * kMoveVecPerThread;  // 16 KiB per work item
+constexpr int kMoveVecPerThread = 8;                                    // 16-byte vectors in flight per lane
+constexpr int kMoveChunkBytes = kMoveThreads * 16 * kMoveVecPerThread;  // 32 KiB per work item
 
 __device__ __forceinline__ const char *side_unit_ptr(const KvMoveSide &s, int layer, int seq, int j,
                                                      int blocks_before, int nblk_seq, int64_t unit_bytes)
