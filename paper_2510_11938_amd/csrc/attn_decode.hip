@@ -52,26 +52,15 @@ __device__ __forceinline__ int64_t worker_begin(int64_t w, int64_t U, int64_t W)
 // worker that owns unit u
 __device__ __forceinline__ int64_t worker_of(int64_t u, int64_t U, int64_t W) { return ((u + 1) * W + U - 1) / U - 1; }
 
-// exclusive scan of the per-sequence block counts ceil((ctx+1)/16) into prefix[0..n]
-__device__ __forceinline__ void scan_blocks(const int32_t *ctx_lens, int n, int32_t *prefix, int32_t *part)
+// Blocks (per head) before each sequence, prefix[0..n] with prefix[i] = sum_{j<i} ceil((ctx_j+1)/16):
+// computed once per forward call (the lengths are the same for every layer), copied to LDS here.
+__device__ __forceinline__ void fetch_prefix(const int32_t *blk_prefix, int n, int32_t *s_prefix)
 {
-    const int tid = threadIdx.x, nt = blockDim.x;
-    const int per = (n + nt - 1) / nt;
-    const int lo = min(tid * per, n), hi = min(lo + per, n);
-    int32_t local = 0;
-    for (int i = lo; i < hi; ++i) local += (ctx_lens[i] + 1 + kBlockTokens - 1) / kBlockTokens;
-    part[tid] = local;
-    __syncthreads();
-    if (tid == 0) {
-        int32_t run = 0;
-        for (int t = 0; t < nt; ++t) { const int32_t v = part[t]; part[t] = run; run += v; }
-        prefix[n] = run;
-    }
-    __syncthreads();
-    int32_t run = part[tid];
-    for (int i = lo; i < hi; ++i) { prefix[i] = run; run += (ctx_lens[i] + 1 + kBlockTokens - 1) / kBlockTokens; }
+    for (int i = threadIdx.x; i <= n; i += blockDim.x) s_prefix[i] = blk_prefix[i];
     __syncthreads();
 }
+
+constexpr int kDecTblChunk = 256;   // block-table entries a wavefront stages in LDS at a time (even)
 
 template <int D, int G, bool DEBUG>
 __global__ __launch_bounds__(kDecThreads) void attn_decode_kernel(DecodeAttnArgs a)
@@ -81,8 +70,9 @@ __global__ __launch_bounds__(kDecThreads) void attn_decode_kernel(DecodeAttnArgs
     constexpr int IPB = kBlockTokens / TPI;  // load instructions per block (K or V)
 
     extern __shared__ int32_t s_prefix[];    // [num_seqs + 1] blocks (per head) before each sequence
-    __shared__ int32_t s_part[kDecThreads];
-    scan_blocks(a.ctx_lens, a.num_seqs, s_prefix, s_part);
+    __shared__ int32_t s_tbl_all[kDecWaves][kDecTblChunk];
+    fetch_prefix(a.blk_prefix, a.num_seqs, s_prefix);
+    int32_t *s_tbl = s_tbl_all[threadIdx.x >> 6];
 
     const int lane = threadIdx.x & 63;
     const int Hkv = a.n_kv_heads;
@@ -109,8 +99,9 @@ __global__ __launch_bounds__(kDecThreads) void attn_decode_kernel(DecodeAttnArgs
 
     while (u < u_end) {
         while ((int64_t)s_prefix[seq + 1] * Hkv <= u) ++seq;
-        const int nb_seq = s_prefix[seq + 1] - s_prefix[seq];
-        const int64_t r = u - (int64_t)s_prefix[seq] * Hkv;
+        seq = __builtin_amdgcn_readfirstlane(seq);                       // wave-uniform: keep the piece's bookkeeping in scalar registers
+        const int nb_seq = __builtin_amdgcn_readfirstlane(s_prefix[seq + 1] - s_prefix[seq]);
+        const int64_t r = u - (int64_t)__builtin_amdgcn_readfirstlane(s_prefix[seq]) * Hkv;
         const int hk = (int)(r / nb_seq), blk0 = (int)(r % nb_seq);
         const int nblk = (int)min((int64_t)(nb_seq - blk0), u_end - u);  // blocks of this piece
         const int n_keys = a.ctx_lens[seq] + 1;                          // cached tokens + the one appended this step
@@ -134,8 +125,13 @@ __global__ __launch_bounds__(kDecThreads) void attn_decode_kernel(DecodeAttnArgs
             for (int e = 0; e < 8; ++e) acc[g][e] = 0.f;
         }
 
+        // The table entries of the piece are staged in this wavefront's LDS region, a chunk at a
+        // time.  A table load from global memory inside the block loop would make every wait for
+        // it drain the (in-order) vector-memory counter, i.e. stall until the cache block in
+        // flight has landed before the next one could be requested; LDS has a counter of its own.
+        int c0 = 0;
         auto load_block = [&](int b, u32x4(&k)[IPB], u32x4(&v)[IPB]) {
-            const int32_t phys = trow[b];
+            const int32_t phys = __builtin_amdgcn_readfirstlane(s_tbl[b - c0]);
             const char *kp = layer_base + (int64_t)phys * unit_bytes + (int64_t)hk * head_bytes + lane * 16;
             const char *vp = kp + (int64_t)Hkv * head_bytes;
 #pragma unroll
@@ -201,15 +197,26 @@ __global__ __launch_bounds__(kDecThreads) void attn_decode_kernel(DecodeAttnArgs
             }
         };
 
-        {
+        // Software pipeline over register buffers.  Loads inside the steady-state loop are
+        // unconditional: a load under a branch makes the compiler wait for everything in
+        // flight (also the block just requested) at the next use, which serialises the stream.
+        for (c0 = 0; c0 < nblk; c0 += kDecTblChunk) {
+            const int ce = min(c0 + kDecTblChunk, nblk);
+            for (int j = lane; j < ce - c0; j += 64) s_tbl[j] = trow[c0 + j];
+            __builtin_amdgcn_wave_barrier();
+            int b = c0;
             u32x4 k0[IPB], v0[IPB], k1[IPB], v1[IPB];
-            load_block(0, k0, v0);
-            for (int b = 0; b < nblk; b += 2) {
-                if (b + 1 < nblk) load_block(b + 1, k1, v1);
+            load_block(b, k0, v0);
+            while (b + 2 < ce) {
+                load_block(b + 1, k1, v1);
                 consume(b, k0, v0);
-                if (b + 2 < nblk) load_block(b + 2, k0, v0);
-                if (b + 1 < nblk) consume(b + 1, k1, v1);
+                load_block(b + 2, k0, v0);
+                consume(b + 1, k1, v1);
+                b += 2;
             }
+            if (b + 1 < ce) load_block(b + 1, k1, v1);
+            consume(b, k0, v0);
+            if (b + 1 < ce) consume(b + 1, k1, v1);
         }
 
         // merge the TPI lane groups (butterfly, lower group always the first operand) and store the piece
@@ -270,9 +277,10 @@ __global__ __launch_bounds__(kDecThreads, 2) void attn_decode_mfma_kernel(Decode
     typedef short v4s __attribute__((ext_vector_type(4)));
 
     extern __shared__ int32_t s_dyn[];         // [num_seqs + 1] block prefix, then the per-wave V regions
-    __shared__ int32_t s_part[kDecThreads];
+    __shared__ int32_t s_tbl_all[kDecWaves][kDecTblChunk];
     int32_t *s_prefix = s_dyn;
-    scan_blocks(a.ctx_lens, a.num_seqs, s_prefix, s_part);
+    fetch_prefix(a.blk_prefix, a.num_seqs, s_prefix);
+    int32_t *s_tbl = s_tbl_all[threadIdx.x >> 6];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int col = lane & 15, c = lane >> 4;
@@ -303,8 +311,9 @@ __global__ __launch_bounds__(kDecThreads, 2) void attn_decode_mfma_kernel(Decode
 
     while (u < u_end) {
         while ((int64_t)s_prefix[seq + 1] * Hkv <= u) ++seq;
-        const int nb_seq = s_prefix[seq + 1] - s_prefix[seq];
-        const int64_t r = u - (int64_t)s_prefix[seq] * Hkv;
+        seq = __builtin_amdgcn_readfirstlane(seq);
+        const int nb_seq = __builtin_amdgcn_readfirstlane(s_prefix[seq + 1] - s_prefix[seq]);
+        const int64_t r = u - (int64_t)__builtin_amdgcn_readfirstlane(s_prefix[seq]) * Hkv;
         const int hk = (int)(r / nb_seq), blk0 = (int)(r % nb_seq);
         const int nblk = (int)min((int64_t)(nb_seq - blk0), u_end - u);
         const int n_keys = a.ctx_lens[seq] + 1;
@@ -326,10 +335,11 @@ __global__ __launch_bounds__(kDecThreads, 2) void attn_decode_mfma_kernel(Decode
         float m_run = -INFINITY, l_lane = 0.f;
 
         // loads of one pair of blocks (the second may be missing: it is then the first again, fully masked)
+        int c0 = 0;
         auto load_pair = [&](int b, u32x4(&kop)[2][KS], u32x4(&vraw)[2][D / 32]) {
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                const int32_t phys = trow[min(b + h, nblk - 1)];
+                const int32_t phys = __builtin_amdgcn_readfirstlane(s_tbl[min(b + h, nblk - 1) - c0]);
                 const char *kp = layer_base + (int64_t)phys * unit_bytes + (int64_t)hk * head_bytes;
                 const char *vp = kp + (int64_t)Hkv * head_bytes;
 #pragma unroll
@@ -411,15 +421,25 @@ __global__ __launch_bounds__(kDecThreads, 2) void attn_decode_mfma_kernel(Decode
             __builtin_amdgcn_wave_barrier();     // the next pair's V stores stay behind these loads
         };
 
-        {
+        // table entries through LDS and unconditional loads in the steady-state loop, as in the
+        // kernel above
+        for (c0 = 0; c0 < nblk; c0 += kDecTblChunk) {
+            const int ce = min(c0 + kDecTblChunk, nblk);
+            for (int j = lane; j < ce - c0; j += 64) s_tbl[j] = trow[c0 + j];
+            __builtin_amdgcn_wave_barrier();
             u32x4 k0[2][KS], v0[2][D / 32], k1[2][KS], v1[2][D / 32];
-            load_pair(0, k0, v0);
-            for (int b = 0; b < nblk; b += 4) {
-                if (b + 2 < nblk) load_pair(b + 2, k1, v1);
+            int b = c0;
+            load_pair(b, k0, v0);
+            while (b + 4 < ce) {
+                load_pair(b + 2, k1, v1);
                 consume_pair(b, k0, v0);
-                if (b + 4 < nblk) load_pair(b + 4, k0, v0);
-                if (b + 2 < nblk) consume_pair(b + 2, k1, v1);
+                load_pair(b + 4, k0, v0);
+                consume_pair(b + 2, k1, v1);
+                b += 4;
             }
+            if (b + 2 < ce) load_pair(b + 2, k1, v1);
+            consume_pair(b, k0, v0);
+            if (b + 2 < ce) consume_pair(b + 2, k1, v1);
         }
 
         // the piece's state: sum over the four lane groups of a head column, then store
@@ -442,21 +462,9 @@ __global__ __launch_bounds__(kDecThreads, 2) void attn_decode_mfma_kernel(Decode
 template <bool DEBUG>
 __global__ void attn_decode_combine_kernel(DecodeAttnArgs a)
 {
-    __shared__ int32_t s_red[4];
     const int seq = blockIdx.x / a.n_kv_heads, hk = blockIdx.x % a.n_kv_heads;
     const int D = a.head_dim, G = a.n_q_heads / a.n_kv_heads, Hkv = a.n_kv_heads;
-    // blocks before this sequence and in total (per head)
-    int32_t before = 0, total = 0;
-    for (int i = threadIdx.x; i < a.num_seqs; i += blockDim.x) {
-        const int32_t nb = (a.ctx_lens[i] + 1 + kBlockTokens - 1) / kBlockTokens;
-        total += nb;
-        if (i < seq) before += nb;
-    }
-    for (int o = 32; o > 0; o >>= 1) { before += __shfl_xor(before, o, 64); total += __shfl_xor(total, o, 64); }
-    if ((threadIdx.x & 63) == 0) { s_red[(threadIdx.x >> 6) * 2] = before; s_red[(threadIdx.x >> 6) * 2 + 1] = total; }
-    __syncthreads();
-    before = s_red[0]; total = s_red[1];
-    if (blockDim.x > 64) { before += s_red[2]; total += s_red[3]; }
+    const int32_t before = a.blk_prefix[seq], total = a.blk_prefix[a.num_seqs];   // blocks (per head) before this sequence / in the batch
     const int n_keys = a.ctx_lens[seq] + 1;
     const int nb = (n_keys + kBlockTokens - 1) / kBlockTokens;
     const int64_t U = (int64_t)total * Hkv, W = min((int64_t)a.n_workers, U);

@@ -150,7 +150,9 @@ hipError_t launch_swiglu(const SwigluArgs &a, hipStream_t stream)
 // evaluated in double (it reaches thousands of radians; float would lose the low
 // bits before the range reduction).  Positions are the same for every layer of
 // the stage, so this runs once per forward call.
-__global__ void rope_table_kernel(RopeTableArgs a)
+constexpr int kRopeTableThreads = 128;
+
+__global__ __launch_bounds__(kRopeTableThreads) void rope_table_kernel(RopeTableArgs a)
 {
     __shared__ int s_seq, s_pos;
     const int t = blockIdx.x, half = a.head_dim / 2;
@@ -169,11 +171,33 @@ __global__ void rope_table_kernel(RopeTableArgs a)
         a.cs[(int64_t)t * half + threadIdx.x] = (float)cos(ang);
         a.sn[(int64_t)t * half + threadIdx.x] = (float)sin(ang);
     }
+    // Workgroup 0 also leaves the exclusive prefix sums of the sequences' cache-block counts
+    // (after this step's append), which the decode-attention kernels of every layer cut their
+    // work by: each thread sums a contiguous range of sequences, then a log-step scan in LDS.
+    if (blockIdx.x == 0) {
+        __shared__ int32_t s_scan[kRopeTableThreads];
+        const int n = a.num_seqs, nt = kRopeTableThreads, tid = threadIdx.x;
+        const int per = (n + nt - 1) / nt;
+        const int lo = min(tid * per, n), hi = min(lo + per, n);
+        int32_t local = 0;
+        for (int i = lo; i < hi; ++i) local += (a.ctx_lens[i] + 1 + kBlockTokens - 1) / kBlockTokens;
+        s_scan[tid] = local;
+        __syncthreads();
+        for (int o = 1; o < nt; o <<= 1) {
+            const int32_t v = tid >= o ? s_scan[tid - o] : 0;
+            __syncthreads();
+            s_scan[tid] += v;
+            __syncthreads();
+        }
+        int32_t run = s_scan[tid] - local;
+        for (int i = lo; i < hi; ++i) { a.blk_prefix[i] = run; run += (a.ctx_lens[i] + 1 + kBlockTokens - 1) / kBlockTokens; }
+        if (tid == nt - 1) a.blk_prefix[n] = s_scan[nt - 1];
+    }
 }
 
 hipError_t launch_rope_table(const RopeTableArgs &a, hipStream_t stream)
 {
-    hipLaunchKernelGGL(rope_table_kernel, dim3(a.T), dim3(128), 0, stream, a);
+    hipLaunchKernelGGL(rope_table_kernel, dim3(a.T), dim3(kRopeTableThreads), 0, stream, a);
     return hipGetLastError();
 }
 

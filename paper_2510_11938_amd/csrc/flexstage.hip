@@ -105,6 +105,14 @@ int env_int(const char *name, int dflt)
 // adds a float slice of partial sums that the epilogue has to read back.
 // Depends on shapes only, so results do not depend on anything else.
 struct SkinnyCfg { int R, S; };
+// The gate|up projection applies SwiGLU in its epilogue (no split-K, no partial sums) when its
+// 2F weight rows alone give every CU of a 256-CU chip most of a workgroup (128 rows each).
+bool skinny_fused_swiglu(int N2)
+{
+    static const int off = env_int("FXP_NO_FUSED_SWIGLU", 0);
+    return !off && N2 / 128 >= 128;
+}
+
 SkinnyCfg skinny_cfg(int N, int K, int M)
 {
     static const int forced_s = env_int("FXP_SKINNY_SPLIT", 0), forced_r = env_int("FXP_SKINNY_R", 0);
@@ -172,6 +180,7 @@ struct Workspace {
     uint16_t *x[2], *n, *q, *qkv, *o, *h, *a;
     float *P, *part_acc, *part_ml, *dbg_ml, *rope_cs, *rope_sn;
     int32_t *tok_seq, *tok_pos;
+    int32_t *blk_prefix;    // decode attention: cache blocks (per head) before each sequence, [B + 1]
     int n_workers;
     size_t bytes;
 };
@@ -211,6 +220,7 @@ Workspace carve(const fxp_stage_desc &d, int T, int B, int max_blocks, char *bas
     w.rope_sn = (float *)take(t * (d.head_dim / 2) * 4);
     w.tok_seq = (int32_t *)take(t * 4);
     w.tok_pos = (int32_t *)take(t * 4);
+    w.blk_prefix = (int32_t *)take(((size_t)B + 1) * 4);
     w.bytes = at;
     return w;
 }
@@ -349,7 +359,7 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
     hipError_t e;
 
-    auto project_skinny = [&](const char *wbase, const uint16_t *X, int N, int K, int ldx, int *S_out) -> hipError_t {
+    auto project_skinny = [&](const char *wbase, const uint16_t *X, int N, int K, int ldx, int *S_out, uint16_t *swiglu_out = nullptr) -> hipError_t {
         if (T > kSkinnyWideTokens) {
             // 65..128 token rows: one 128-row tile of the tiled kernel covers the batch; split-K for parallelism
             fxp::TiledArgs t;
@@ -361,8 +371,9 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
             return fxp::launch_gemm_tiled(t, st);
         }
         fxp::SkinnyArgs a;
-        a.W = (const uint16_t *)wbase; a.X = X; a.P = w.P;
+        a.W = (const uint16_t *)wbase; a.X = X; a.P = w.P; a.A = nullptr;
         a.M = T; a.N = N; a.K = K; a.KS = k_steps(K); a.NT = N / 16; a.ldx = ldx; a.S = skinny_cfg(N, K, T).S; a.R = skinny_cfg(N, K, T).R; a.U = env_int("FXP_SKINNY_U", 4);
+        if (swiglu_out) { a.A = swiglu_out; a.S = 1; a.R = 2; }     // SwiGLU in the epilogue: no split, gate and up tile in one wavefront
         *S_out = a.S;
         KernelTimer kt(kKcSkinny, st);
         return fxp::launch_gemm_skinny(a, st);
@@ -378,7 +389,7 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
 
     {   // token -> (sequence, position) and the rotation table: the same for every layer
         fxp::RopeTableArgs rt;
-        rt.cu_seqlens_q = batch->cu_seqlens_q; rt.ctx_lens = batch->ctx_lens; rt.tok_seq = w.tok_seq; rt.tok_pos = w.tok_pos;
+        rt.cu_seqlens_q = batch->cu_seqlens_q; rt.ctx_lens = batch->ctx_lens; rt.tok_seq = w.tok_seq; rt.tok_pos = w.tok_pos; rt.blk_prefix = w.blk_prefix;
         rt.cs = w.rope_cs; rt.sn = w.rope_sn; rt.T = T; rt.num_seqs = B; rt.head_dim = D; rt.rope_base = d.rope_base;
         KernelTimer kt(kKcRopeTable, st);
         if ((e = fxp::launch_rope_table(rt, st))) return hip_fail(e, "rope table");
@@ -421,6 +432,7 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
         if (decode) {
             fxp::DecodeAttnArgs aa;
             aa.q = w.q; aa.pool = (const uint16_t *)pool->base; aa.ctx_lens = batch->ctx_lens; aa.block_table = batch->block_table;
+            aa.blk_prefix = w.blk_prefix;
             aa.part_acc = w.part_acc; aa.part_ml = w.part_ml; aa.out = w.o; aa.dbg_scores = dbg; aa.dbg_stride = probs_stride;
             aa.num_blocks = pool->num_blocks; aa.num_seqs = B; aa.max_blocks_per_seq = batch->max_blocks_per_seq;
             aa.n_workers = w.n_workers; aa.layer_local = ll; aa.n_q_heads = d.n_q_heads; aa.n_kv_heads = d.n_kv_heads;
@@ -454,10 +466,13 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
                 if ((e = fxp::launch_resid_norm(rn, st))) return hip_fail(e, "residual + norm");
             }
             // gate|up projection + SwiGLU
-            if ((e = project_skinny(rec + stage->rec.wgu, w.n, 2 * F, H, H, &S))) return hip_fail(e, "gate/up projection");
-            fxp::SwigluArgs sg;
-            sg.P = w.P; sg.out = w.a; sg.T = T; sg.F = F; sg.S = S; sg.ld_out = F;
-            {
+            // (up to 64 rows the projection is wide enough to fill the chip without split-K and
+            // applies SwiGLU itself; above, the split partial sums go through the SwiGLU kernel)
+            const bool fused_swiglu = T <= kSkinnyWideTokens && skinny_fused_swiglu(2 * F);
+            if ((e = project_skinny(rec + stage->rec.wgu, w.n, 2 * F, H, H, &S, fused_swiglu ? w.a : nullptr))) return hip_fail(e, "gate/up projection");
+            if (!fused_swiglu) {
+                fxp::SwigluArgs sg;
+                sg.P = w.P; sg.out = w.a; sg.T = T; sg.F = F; sg.S = S; sg.ld_out = F;
                 KernelTimer kt(kKcSwiglu, st);
                 if ((e = fxp::launch_swiglu(sg, st))) return hip_fail(e, "swiglu");
             }

@@ -16,7 +16,8 @@
 //     per wavefront while the other buffer is consumed;
 //   - split-K across workgroups fills all 256 CUs; partial sums go to a float
 //     buffer and are reduced in fixed order by the fused epilogue kernels, so
-//     the result is deterministic (no atomics).
+//     the result is deterministic (no atomics).  The gate|up projection is wide
+//     enough without a split and applies SwiGLU in its own epilogue instead.
 #include "kernels.h"
 #include "common.hip.h"
 
@@ -134,6 +135,30 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(SkinnyArgs a)
     // accumulator layout of the 16x16 MFMA: lane l, element v holds D[row 4*(l/16)+v][col l%16]
     // with rows = weight rows n and columns = token rows m: four consecutive n per lane.
     const int mrow = lane & 15;
+    if constexpr (R % 2 == 0) {
+        if (a.A) {
+            // gate|up projection without split-K: tiles alternate gate rows / up rows of the same 16
+            // features, so the lane that holds a gate value holds the matching up value one tile on
+#pragma unroll
+            for (int r = 0; r < R; r += 2) {
+                if (nt0 + r + 1 >= a.NT) continue;
+                const int f = (nt0 + r) / 2 * 16 + 4 * (lane >> 4);
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    const int m = mt * 16 + mrow;
+                    float y[4];
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const float g = acc[r][mt][v];
+                        y[v] = g / (1.f + __expf(-g)) * acc[r + 1][mt][v];
+                    }
+                    if (m < a.M)
+                        *reinterpret_cast<u32x2 *>(a.A + (int64_t)m * (a.N / 2) + f) = u32x2{pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3])};
+                }
+            }
+            return;
+        }
+    }
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         if (nt0 + r >= a.NT) continue;

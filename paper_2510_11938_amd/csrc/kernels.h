@@ -43,6 +43,7 @@ struct SkinnyArgs {
     const uint16_t *W;     // packed weights
     const uint16_t *X;     // token rows [M][ldx] bf16
     float *P;              // partial sums [S][M][N]
+    uint16_t *A;           // optional SwiGLU output [M][N/2] bf16 (gate|up weights, S == 1, even R): replaces P
     int M, N, K, KS, NT, ldx, S;   // KS = padded K / 32, NT = N / 16
     int R;                         // 16-row weight tiles per wavefront: 1, 2 or 4
     int U;                         // k-steps per prefetch group: 4 or 8 (8 only for R <= 2, M <= 32)
@@ -85,6 +86,7 @@ hipError_t launch_swiglu(const SwigluArgs &a, hipStream_t stream);
 struct RopeTableArgs {
     const int32_t *cu_seqlens_q, *ctx_lens;
     int32_t *tok_seq, *tok_pos;   // [T]
+    int32_t *blk_prefix;          // [num_seqs + 1] exclusive prefix of ceil((ctx+1)/16): the decode kernels' work cut
     float *cs, *sn;               // [T][D/2]
     int T, num_seqs, head_dim;
     float rope_base;
@@ -112,6 +114,7 @@ struct DecodeAttnArgs {
     const uint16_t *q;     // [num_seqs][Hq][D] bf16 (rotated)
     const uint16_t *pool;
     const int32_t *ctx_lens, *block_table;
+    const int32_t *blk_prefix;   // [num_seqs + 1] from the rope-table kernel
     float *part_acc;       // [n_workers + num_seqs*Hkv][G][D]   one row group per piece
     float *part_ml;        // [n_workers + num_seqs*Hkv][G][2]
     uint16_t *out;         // [num_seqs][Hq*D] bf16

@@ -26,6 +26,7 @@ TINY = synth.TINY
 GQA64 = synth.ModelShape(hidden=512, n_q_heads=8, n_kv_heads=2, head_dim=64, ffn=1376)
 MID128 = synth.ModelShape(hidden=512, n_q_heads=4, n_kv_heads=4, head_dim=128, ffn=1024)
 GQA128 = synth.ModelShape(hidden=1024, n_q_heads=8, n_kv_heads=1, head_dim=128, ffn=1536)
+WIDE_FFN = synth.ModelShape(hidden=256, n_q_heads=4, n_kv_heads=4, head_dim=64, ffn=8208)   # gate|up wide enough for the unsplit, SwiGLU-fused projection
 
 
 class Case:
@@ -85,6 +86,8 @@ DECODE_CASES = [
     ("gqa64", GQA64, 2, [700, 16, 1, 513, 90, 1100, 15]),          # several context splits, ragged, tiny
     ("mid128", MID128, 2, [1535, 47, 512, 2000, 1]),
     ("gqa128-8", GQA128, 1, [300, 1025, 31]),
+    ("wide-ffn", WIDE_FFN, 2, [33, 200, 64, 7, 150]),             # SwiGLU in the projection epilogue, ragged last tile pair
+    ("wide-ffn-40", WIDE_FFN, 1, list(range(5, 45))),
     ("batch-40", TINY, 1, list(range(5, 45))),                     # 3 row tiles, ragged
     ("batch-100", TINY, 1, [17 + (i * 7) % 90 for i in range(100)]),   # 7 row tiles
 ]
