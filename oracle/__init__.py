@@ -63,6 +63,7 @@ def lib():
         _lib.orc_silu.restype = C.c_double
         _lib.orc_silu.argtypes = [C.c_double]
         _lib.orc_kv_packed_elems.restype = C.c_int64
+        _lib.orc_kv_packed_tokens_elems.restype = C.c_int64
     return _lib
 
 
@@ -272,3 +273,53 @@ def kv_unpack(shape: Shape, packed: np.ndarray, dst: KVView, lb: int, le: int, c
 def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
     """Exact widening of bf16 bit patterns (uint16) to float32."""
     return (np.ascontiguousarray(bits, dtype=np.uint16).astype(np.uint32) << 16).view(np.float32)
+
+
+def kv_repartition_range(shape: Shape, src: Sequence[KVView], dst: Sequence[KVView], from_lens, to_lens) -> None:
+    """Incremental repartition: only tokens [from_i, to_i) of every sequence (Section 6.3, Eq. 10 with a
+    per-sequence range as the validity mask)."""
+    keep: list = []
+    itemsize = src[0].pool.dtype.itemsize
+    assert all(v.pool.dtype.itemsize == itemsize for v in list(src) + list(dst))
+    fl, tl = _i32(from_lens), _i32(to_lens)
+    assert fl.shape == tl.shape
+    sh = shape.c()
+    rc = lib().orc_kv_repartition_range(C.byref(sh), C.c_int32(itemsize), _views(src, keep), C.c_int32(len(src)),
+                                        _views(dst, keep), C.c_int32(len(dst)), _p(fl), _p(tl), C.c_int32(tl.shape[0]))
+    if rc != 0:
+        raise ValueError("orc_kv_repartition_range: layer ranges, tables or token ranges malformed")
+
+
+def kv_packed_tokens_elems(shape: Shape, lb: int, le: int, from_lens, to_lens) -> int:
+    fl, tl = _i32(from_lens), _i32(to_lens)
+    sh = shape.c()
+    return int(lib().orc_kv_packed_tokens_elems(C.byref(sh), C.c_int32(lb), C.c_int32(le), _p(fl), _p(tl),
+                                                C.c_int32(tl.shape[0])))
+
+
+def kv_pack_tokens(shape: Shape, src: KVView, lb: int, le: int, from_lens, to_lens) -> np.ndarray:
+    keep: list = []
+    fl, tl = _i32(from_lens), _i32(to_lens)
+    if np.any(fl < 0) or np.any(fl > tl):
+        raise ValueError("orc_kv_pack_tokens: malformed token range")
+    out = np.empty(kv_packed_tokens_elems(shape, lb, le, fl, tl), dtype=src.pool.dtype)
+    v = src.c(keep); sh = shape.c()
+    rc = lib().orc_kv_pack_tokens(C.byref(sh), C.c_int32(src.pool.dtype.itemsize), C.byref(v), C.c_int32(lb),
+                                  C.c_int32(le), _p(fl), _p(tl), C.c_int32(tl.shape[0]), _p(out))
+    if rc != 0:
+        raise ValueError("orc_kv_pack_tokens: malformed argument")
+    return out
+
+
+def kv_unpack_tokens(shape: Shape, packed: np.ndarray, dst: KVView, lb: int, le: int, from_lens, to_lens) -> None:
+    keep: list = []
+    fl, tl = _i32(from_lens), _i32(to_lens)
+    assert packed.dtype.itemsize == dst.pool.dtype.itemsize and packed.flags.c_contiguous
+    if np.any(fl < 0) or np.any(fl > tl):
+        raise ValueError("orc_kv_unpack_tokens: malformed token range")
+    assert packed.size == kv_packed_tokens_elems(shape, lb, le, fl, tl)
+    v = dst.c(keep); sh = shape.c()
+    rc = lib().orc_kv_unpack_tokens(C.byref(sh), C.c_int32(dst.pool.dtype.itemsize), _p(packed), C.byref(v),
+                                    C.c_int32(lb), C.c_int32(le), _p(fl), _p(tl), C.c_int32(tl.shape[0]))
+    if rc != 0:
+        raise ValueError("orc_kv_unpack_tokens: malformed argument")

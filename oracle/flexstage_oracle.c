@@ -32,7 +32,8 @@
  * heads == replicated heads; library cross-checks (float64 matmul, float64
  * scaled-dot-product attention); an independent float64 re-statement of the
  * whole layer; split == unsplit; cached decode == recompute; repartition
- * against an independent index walk and brute force.
+ * against an independent index walk and brute force; incremental repartition:
+ * snapshot pass + delta pass == one pass, rows outside the range untouched.
  *
  * Layouts (all row-major, last index fastest):
  *   weight matrices      [out_features][in_features]
@@ -40,6 +41,7 @@
  *   kv pool              [layer - layer_begin][block][2: K,V][kv_head][slot][head_dim]
  *   block table          [sequence][max_blocks_per_seq]   (physical block ids)
  *   packed kv buffer     [sequence][layer - lb][logical block][2][kv_head][slot][head_dim]
+ *   token-dense buffer   [sequence][layer - lb][2][kv_head][token - from_i][head_dim]
  */
 #include <math.h>
 #include <stdint.h>
@@ -385,4 +387,117 @@ int orc_kv_unpack(const orc_shape *sh, int32_t elem_bytes, const void *packed, c
                   int32_t lb, int32_t le, const int32_t *ctx_lens, int32_t num_seqs)
 {
     return pack_or_unpack(sh, elem_bytes, dst, lb, le, ctx_lens, num_seqs, (unsigned char *)packed, 0);
+}
+
+/* ---------------------------------------------------------------------------
+ * Incremental repartition.  Section 6.3 lets the cache transfer run while
+ * inference continues on the old configuration, so a first pass moves a
+ * snapshot and later passes move what was appended since.  The validity mask of
+ * Eq. 10 ("tokens that need synchronization") is then, per sequence i, the
+ * token range [from_i, to_i):
+ *   - every row of a token r with from_i <= r < to_i is copied as in
+ *     orc_kv_repartition;
+ *   - if the range is not empty, the slots r >= to_i of the block that holds
+ *     token to_i - 1 are zero (the mask's zeros);
+ *   - nothing else is written: rows of tokens r < from_i (moved by an earlier
+ *     pass) and blocks outside the range keep their contents.
+ * With from_i = 0 this is orc_kv_repartition. */
+int orc_kv_repartition_range(const orc_shape *sh, int32_t elem_bytes,
+                             const orc_kv_view *src, int32_t n_src,
+                             const orc_kv_view *dst, int32_t n_dst,
+                             const int32_t *from_lens, const int32_t *to_lens, int32_t num_seqs)
+{
+    if (!views_cover_same_range(src, n_src, dst, n_dst)) return -1;
+    int32_t bs = sh->kv_block_size, D = sh->head_dim, Hkv = sh->n_kv_heads;
+    size_t row_bytes = (size_t)D * (size_t)elem_bytes;
+    for (int32_t i = 0; i < num_seqs; ++i)
+        if (from_lens[i] < 0 || from_lens[i] > to_lens[i]) return -1;
+    for (int32_t d = 0; d < n_dst; ++d) {
+        const orc_kv_view *dv = &dst[d];
+        for (int32_t layer = dv->layer_begin; layer < dv->layer_end; ++layer) {
+            const orc_kv_view *sv = view_with_layer(src, n_src, layer);
+            if (!sv) return -1;
+            for (int32_t i = 0; i < num_seqs; ++i) {
+                int32_t lo = from_lens[i], hi = to_lens[i];
+                if (lo == hi) continue;
+                int32_t nblk = (hi + bs - 1) / bs;
+                if (nblk > sv->max_blocks_per_seq || nblk > dv->max_blocks_per_seq) return -1;
+                const int32_t *srow = sv->block_table + (size_t)i * sv->max_blocks_per_seq;
+                const int32_t *drow = dv->block_table + (size_t)i * dv->max_blocks_per_seq;
+                for (int32_t r = lo; r < nblk * bs; ++r)
+                    for (int32_t kv = 0; kv < 2; ++kv)
+                        for (int32_t h = 0; h < Hkv; ++h) {
+                            size_t so = pool_row(sh, sv->num_blocks, layer - sv->layer_begin, srow[r / bs], kv, h, r % bs);
+                            size_t dof = pool_row(sh, dv->num_blocks, layer - dv->layer_begin, drow[r / bs], kv, h, r % bs);
+                            unsigned char *dp = (unsigned char *)dv->base + dof * (size_t)elem_bytes;
+                            if (r < hi) memcpy(dp, (const unsigned char *)sv->base + so * (size_t)elem_bytes, row_bytes);
+                            else memset(dp, 0, row_bytes);
+                        }
+            }
+        }
+    }
+    return 0;
+}
+
+/* Token-dense packed form of the same range: only the rows of tokens
+ * [from_i, to_i), no padding to whole blocks, ordered
+ * [sequence][layer - lb][K,V][kv_head][token - from_i][head_dim].
+ * This is what a delta pass between devices would carry: a few tokens per
+ * sequence, where the block-granular buffer would be mostly padding. */
+int64_t orc_kv_packed_tokens_elems(const orc_shape *sh, int32_t lb, int32_t le,
+                                   const int32_t *from_lens, const int32_t *to_lens, int32_t num_seqs)
+{
+    int64_t tokens = 0;
+    for (int32_t i = 0; i < num_seqs; ++i) tokens += to_lens[i] - from_lens[i];
+    return tokens * (int64_t)(le - lb) * 2 * sh->n_kv_heads * sh->head_dim;
+}
+
+/* to_packed: gather the rows into the buffer.  Otherwise: scatter them into the
+ * view and zero the slots after to_i - 1 in its block, as the range repartition
+ * does, so that pack followed by unpack equals orc_kv_repartition_range. */
+static int pack_or_unpack_tokens(const orc_shape *sh, int32_t elem_bytes, const orc_kv_view *view,
+                                 int32_t lb, int32_t le, const int32_t *from_lens, const int32_t *to_lens,
+                                 int32_t num_seqs, unsigned char *packed, int to_packed)
+{
+    if (lb < view->layer_begin || le > view->layer_end || lb >= le) return -1;
+    int32_t bs = sh->kv_block_size, D = sh->head_dim, Hkv = sh->n_kv_heads;
+    size_t row_bytes = (size_t)D * (size_t)elem_bytes;
+    for (int32_t i = 0; i < num_seqs; ++i)
+        if (from_lens[i] < 0 || from_lens[i] > to_lens[i]) return -1;
+    size_t cursor = 0; /* in rows of D elements */
+    for (int32_t i = 0; i < num_seqs; ++i) {
+        int32_t lo = from_lens[i], hi = to_lens[i];
+        if (lo == hi) continue;
+        int32_t nblk = (hi + bs - 1) / bs;
+        if (nblk > view->max_blocks_per_seq) return -1;
+        const int32_t *row = view->block_table + (size_t)i * view->max_blocks_per_seq;
+        for (int32_t layer = lb; layer < le; ++layer)
+            for (int32_t kv = 0; kv < 2; ++kv)
+                for (int32_t h = 0; h < Hkv; ++h) {
+                    for (int32_t r = lo; r < hi; ++r, ++cursor) {
+                        size_t po = pool_row(sh, view->num_blocks, layer - view->layer_begin, row[r / bs], kv, h, r % bs);
+                        unsigned char *pp = (unsigned char *)view->base + po * (size_t)elem_bytes;
+                        unsigned char *bp = packed + cursor * row_bytes;
+                        if (to_packed) memcpy(bp, pp, row_bytes); else memcpy(pp, bp, row_bytes);
+                    }
+                    if (!to_packed)
+                        for (int32_t r = hi; r < nblk * bs; ++r) {
+                            size_t po = pool_row(sh, view->num_blocks, layer - view->layer_begin, row[r / bs], kv, h, r % bs);
+                            memset((unsigned char *)view->base + po * (size_t)elem_bytes, 0, row_bytes);
+                        }
+                }
+    }
+    return 0;
+}
+
+int orc_kv_pack_tokens(const orc_shape *sh, int32_t elem_bytes, const orc_kv_view *src, int32_t lb, int32_t le,
+                       const int32_t *from_lens, const int32_t *to_lens, int32_t num_seqs, void *packed)
+{
+    return pack_or_unpack_tokens(sh, elem_bytes, src, lb, le, from_lens, to_lens, num_seqs, (unsigned char *)packed, 1);
+}
+
+int orc_kv_unpack_tokens(const orc_shape *sh, int32_t elem_bytes, const void *packed, const orc_kv_view *dst,
+                         int32_t lb, int32_t le, const int32_t *from_lens, const int32_t *to_lens, int32_t num_seqs)
+{
+    return pack_or_unpack_tokens(sh, elem_bytes, dst, lb, le, from_lens, to_lens, num_seqs, (unsigned char *)packed, 0);
 }

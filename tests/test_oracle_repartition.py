@@ -148,3 +148,111 @@ def test_pack_layout_and_unpack_inverse():
     dstf = KVView(dst2.pool.astype(np.float32), 3, 5, dst2.block_table)
     oracle.kv_unpack(SH, oracle.kv_pack(SH, srcf, lb, le, lens), dstf, lb, le, lens)
     assert np.array_equal(dstf.pool, dst.pool.astype(np.float32))
+
+
+# ---------------------------------------------------------------------------
+# Incremental repartition (Section 6.3: the transfer runs while inference goes on,
+# so a snapshot pass is followed by delta passes; the validity mask of Eq. 10 is a
+# per-sequence token range) and the token-dense packed form.
+
+def range_dict(shape, views, lo, hi):
+    """{(layer, seq, token, kv, head): row} for tokens lo_i <= r < hi_i only."""
+    bs = shape.kv_block_size
+    out = {}
+    for v in views:
+        for layer in range(v.layer_begin, v.layer_end):
+            for i in range(len(hi)):
+                for r in range(int(lo[i]), int(hi[i])):
+                    blk = v.block_table[i, r // bs]
+                    for kv in range(2):
+                        for h in range(shape.n_kv_heads):
+                            out[(layer, i, r, kv, h)] = tuple(v.pool[layer - v.layer_begin, blk, kv, h, r % bs])
+    return out
+
+
+def test_range_from_zero_is_the_plain_repartition():
+    lens = np.array([5, 8, 1, 0, 11], dtype=np.int32)
+    src = random_stage_caches(SH, [(0, 3)], lens, seed=21)
+    d1 = random_stage_caches(SH, [(0, 1), (1, 3)], lens, seed=22)
+    d2 = random_stage_caches(SH, [(0, 1), (1, 3)], lens, seed=22)
+    oracle.kv_repartition(SH, src, d1, lens)
+    oracle.kv_repartition_range(SH, src, d2, np.zeros_like(lens), lens)
+    assert all(np.array_equal(a.pool, b.pool) for a, b in zip(d1, d2))
+
+
+def test_snapshot_pass_plus_delta_pass_equals_one_pass():
+    """Decode appends tokens between the passes; the source stays where it is."""
+    snap = np.array([5, 8, 1, 0, 11, 3], dtype=np.int32)
+    now = np.array([7, 8, 6, 2, 12, 20], dtype=np.int32)     # grown by 2, 0, 5 (crosses a block), 2 (from empty), 1 (into a new block), 17
+    src = random_stage_caches(SH, [(0, 2), (2, 4)], now, seed=23)
+    one = random_stage_caches(SH, [(0, 4)], now, seed=24)
+    two = random_stage_caches(SH, [(0, 4)], now, seed=24)
+    oracle.kv_repartition(SH, src, one, now)
+    oracle.kv_repartition(SH, src, two, snap)
+    oracle.kv_repartition_range(SH, src, two, snap, now)
+    assert np.array_equal(one[0].pool, two[0].pool)
+
+
+def test_range_pass_writes_only_its_tokens_and_the_masked_tail():
+    lo = np.array([5, 8, 0, 3, 4, 9], dtype=np.int32)
+    hi = np.array([7, 8, 6, 3, 12, 10], dtype=np.int32)
+    src = random_stage_caches(SH, [(1, 3)], hi, seed=25)
+    dst = random_stage_caches(SH, [(1, 2), (2, 3)], hi, seed=26, spare=2)
+    before = [v.pool.copy() for v in dst]
+    want = range_dict(SH, src, lo, hi)
+    oracle.kv_repartition_range(SH, src, dst, lo, hi)
+    assert range_dict(SH, dst, lo, hi) == want
+    bs = SH.kv_block_size
+    for v, b in zip(dst, before):
+        touched = np.zeros(v.pool.shape[:2] + (bs,), dtype=bool)          # [layer, block, slot]
+        for i in range(len(hi)):
+            if lo[i] == hi[i]:
+                continue
+            for r in range(int(lo[i]), int(-(-hi[i] // bs) * bs)):
+                touched[:, v.block_table[i, r // bs], r % bs] = True
+                if r >= hi[i]:
+                    assert np.all(v.pool[:, v.block_table[i, r // bs], :, :, r % bs, :] == 0)
+        same = np.broadcast_to(~touched[:, :, None, None, :, None], v.pool.shape)
+        assert np.array_equal(v.pool[same], b[same])                       # earlier tokens, other blocks: untouched
+    assert any((~np.equal(v.pool, b)).any() for v, b in zip(dst, before))
+
+
+def test_range_rejects_malformed_ranges():
+    lens = np.array([4, 4], dtype=np.int32)
+    src = random_stage_caches(SH, [(0, 1)], lens, seed=27)
+    dst = random_stage_caches(SH, [(0, 1)], lens, seed=28)
+    with pytest.raises(ValueError):
+        oracle.kv_repartition_range(SH, src, dst, np.array([5, 0], dtype=np.int32), lens)     # from > to
+    with pytest.raises(ValueError):
+        oracle.kv_repartition_range(SH, src, dst, np.array([-1, 0], dtype=np.int32), lens)
+    with pytest.raises(ValueError):
+        oracle.kv_pack_tokens(SH, src[0], 0, 1, np.array([5, 0], dtype=np.int32), lens)
+
+
+def test_token_dense_pack_layout_and_unpack_equals_range_repartition():
+    lo = np.array([5, 8, 0, 3, 4], dtype=np.int32)
+    hi = np.array([7, 8, 6, 3, 12], dtype=np.int32)
+    src = random_stage_caches(SH, [(2, 5)], hi, seed=29)
+    lb, le = 3, 5
+    packed = oracle.kv_pack_tokens(SH, src[0], lb, le, lo, hi)
+    assert packed.size == int((hi - lo).sum()) * (le - lb) * 2 * SH.n_kv_heads * SH.head_dim
+    assert packed.size == oracle.kv_packed_tokens_elems(SH, lb, le, lo, hi)
+    # layout [sequence][layer][K,V][head][token][dim], by an independent walk
+    rows = packed.reshape(-1, SH.head_dim)
+    want = range_dict(SH, src, lo, hi)
+    at = 0
+    for i in range(len(hi)):
+        for layer in range(lb, le):
+            for kv in range(2):
+                for h in range(SH.n_kv_heads):
+                    for r in range(int(lo[i]), int(hi[i])):
+                        assert tuple(rows[at]) == want[(layer, i, r, kv, h)]
+                        at += 1
+    assert at == rows.shape[0]
+    # unpack into a fresh table == the fused range pass
+    d1 = random_stage_caches(SH, [(3, 5)], hi, seed=30)
+    d2 = random_stage_caches(SH, [(3, 5)], hi, seed=30)
+    oracle.kv_unpack_tokens(SH, packed, d1[0], lb, le, lo, hi)
+    src35 = [KVView(src[0].pool[1:], 3, 5, src[0].block_table)]
+    oracle.kv_repartition_range(SH, src35, d2, lo, hi)
+    assert np.array_equal(d1[0].pool, d2[0].pool)
