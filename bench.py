@@ -238,6 +238,44 @@ def main() -> int:
     move_ms = ev0.elapsed_time(ev1) / reps
     move_gbps = move_bytes / (move_ms * 1e-3) / 1e9
 
+    # ---- incremental repartition (Section 6.3: transfers run while inference continues) -----
+    # (a) the snapshot pass on a second stream while decode steps run on the first: both are
+    #     HBM-bound, so each slows the other; (b) a delta pass over the last 16 tokens of every
+    #     sequence, the work left after 16 decode steps went by during the snapshot.
+    side = torch.cuda.Stream()
+    reps_o = 8
+    steps_o = max(1, int(round(reps_o * move_ms / ms_per_step)))      # about the same time alone
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        ev[0].record()
+        for _ in range(reps_o):
+            binding.kv_repartition(ms, [cache], dst, cl)
+        ev[1].record()
+    ev[2].record()
+    for _ in range(steps_o):
+        step()
+    ev[3].record()
+    torch.cuda.synchronize()
+    move_ms_o = ev[0].elapsed_time(ev[1]) / reps_o
+    step_ms_o = ev[2].elapsed_time(ev[3]) / steps_o
+    delta_from = torch.clamp(cl - 16, min=0)
+    for _ in range(3):
+        binding.kv_repartition_range(ms, [cache], dst, delta_from, cl)
+    torch.cuda.synchronize()
+    ev0.record()
+    for _ in range(20):
+        binding.kv_repartition_range(ms, [cache], dst, delta_from, cl)
+    ev1.record()
+    torch.cuda.synchronize()
+    delta_us = ev0.elapsed_time(ev1) / 20 * 1e3
+    delta_bytes = 2 * int(np.minimum(ctx, 16).sum()) * L * kv_bytes_per_token
+    incremental = {"snapshot_pass_concurrent_with_decode": {
+                       "repartition_ms": move_ms_o, "repartition_GBps": move_bytes / (move_ms_o * 1e-3) / 1e9,
+                       "decode_ms_per_step": step_ms_o, "decode_steps": steps_o, "repartitions": reps_o,
+                       "hbm_GBps_both": (move_bytes / move_ms_o + (L * weight_bytes_layer + L * attn_bytes) / step_ms_o) / 1e6},
+                   "delta_pass_last_16_tokens": {"us": delta_us, "bytes_read_plus_written": delta_bytes}}
+
     out = {
         "metric": "stage decode tokens/s (7B shape, 4 layers, B=32); KV repartition GB/s vs HBM",
         "value": tokens_per_s, "unit": "tokens/s",
@@ -254,6 +292,7 @@ def main() -> int:
                      "frac": attn_gbps / HBM_PEAK_GBPS,
                      "traffic": read_traffic(os.path.join(ROOT, "profiles", "attn_decode_c2_pmc.txt"), "attn_decode_kernel"),
                      "algorithmic_bytes_per_launch": attn_bytes, "avg_launch_us": attn_us},
+        "incremental_repartition": incremental,
         "kernels": kernels,
         "setup_s": setup_s,
     }

@@ -176,6 +176,48 @@ int    fxp_kv_unpack(const fxp_stage_desc *desc, const void *packed, size_t pack
                      const fxp_kv_view *dst, int32_t layer_begin, int32_t layer_end,
                      const int32_t *ctx_lens, int32_t num_seqs, void *hip_stream);
 
+/* ---- incremental repartition --------------------------------------------------
+ * Section 6.3 lets the cache transfer run while inference continues on the old
+ * configuration: a first pass moves a snapshot, later passes move what decoding
+ * appended meanwhile.  The validity mask of Eq. 10 is then, per sequence i, the
+ * token range [from_lens[i], to_lens[i]):
+ *   - the K and V rows of every token in the range are copied as above;
+ *   - if the range is not empty, the slots at or beyond to_lens[i] in the block
+ *     of token to_lens[i] - 1 arrive as zero;
+ *   - nothing else is written: rows of tokens before from_lens[i] and all other
+ *     blocks keep their contents.  A sequence with from >= to (or from < 0)
+ *     moves nothing.
+ * A pass over [0, c) followed by a pass over [c, c') leaves exactly what one
+ * pass over [0, c') leaves.  from_lens, to_lens: DEVICE [num_seqs].  All other
+ * arguments, errors and the no-overlap rule are those of fxp_kv_repartition,
+ * which is this call with from_lens = 0. */
+int    fxp_kv_repartition_range(const fxp_stage_desc *desc,
+                                const fxp_kv_view *src, int32_t n_src,
+                                const fxp_kv_view *dst, int32_t n_dst,
+                                const int32_t *from_lens, const int32_t *to_lens,
+                                int32_t num_seqs, void *hip_stream);
+
+/* Token-dense halves of an incremental pass that crosses devices: only the rows
+ * of the tokens in the range, without padding to whole blocks,
+ *   [sequence][layer - layer_begin][2: K,V][kv_head][token - from_lens[i]][head_dim]
+ * (a delta pass carries a few tokens per sequence, where the block-granular
+ * buffer would be mostly padding).  unpack also zeroes the slots after token
+ * to_lens[i] - 1 in its block, so pack + unpack equals fxp_kv_repartition_range.
+ * fxp_kv_packed_tokens_bytes computes the size from lengths in HOST memory;
+ * as for fxp_kv_pack, `packed_bytes` is the size the caller really has and no
+ * call touches memory past it (rows that do not fit are skipped on both
+ * sides); FXP_ENOSPC only if packed_bytes < 16. */
+size_t fxp_kv_packed_tokens_bytes(const fxp_stage_desc *desc, int32_t layer_begin, int32_t layer_end,
+                                  const int32_t *from_lens_host, const int32_t *to_lens_host, int32_t num_seqs);
+int    fxp_kv_pack_tokens(const fxp_stage_desc *desc, const fxp_kv_view *src,
+                          int32_t layer_begin, int32_t layer_end,
+                          const int32_t *from_lens, const int32_t *to_lens, int32_t num_seqs,
+                          void *packed, size_t packed_bytes, void *hip_stream);
+int    fxp_kv_unpack_tokens(const fxp_stage_desc *desc, const void *packed, size_t packed_bytes,
+                            const fxp_kv_view *dst, int32_t layer_begin, int32_t layer_end,
+                            const int32_t *from_lens, const int32_t *to_lens, int32_t num_seqs,
+                            void *hip_stream);
+
 /* ---- per-kernel timing for benchmarks ---------------------------------------
  * While enabled, every kernel launch the library makes is bracketed by a pair
  * of HIP events recorded on the caller's stream (up to 8192 launches; later

@@ -24,6 +24,7 @@ EXPORTS = (
     "fxp_stage_weight_arena_bytes", "fxp_stage_create", "fxp_stage_destroy",
     "fxp_stage_workspace_bytes", "fxp_stage_forward", "fxp_stage_forward_debug",
     "fxp_kv_repartition", "fxp_kv_packed_bytes", "fxp_kv_pack", "fxp_kv_unpack",
+    "fxp_kv_repartition_range", "fxp_kv_packed_tokens_bytes", "fxp_kv_pack_tokens", "fxp_kv_unpack_tokens",
     "fxp_profile_enable", "fxp_profile_num_classes", "fxp_profile_class_name", "fxp_profile_read", "fxp_profile_read_launch",
     "fxp_last_error", "fxp_version",
 )
@@ -102,6 +103,14 @@ def lib() -> C.CDLL:
                                   C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
         l.fxp_kv_unpack.argtypes = [C.POINTER(StageDesc), C.c_void_p, C.c_size_t, C.POINTER(KvView), C.c_int32,
                                     C.c_int32, C.c_void_p, C.c_int32, C.c_void_p]
+        l.fxp_kv_repartition_range.argtypes = [C.POINTER(StageDesc), C.POINTER(KvView), C.c_int32, C.POINTER(KvView),
+                                               C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
+        l.fxp_kv_packed_tokens_bytes.restype = C.c_size_t
+        l.fxp_kv_packed_tokens_bytes.argtypes = [C.POINTER(StageDesc), C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32]
+        l.fxp_kv_pack_tokens.argtypes = [C.POINTER(StageDesc), C.POINTER(KvView), C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                         C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
+        l.fxp_kv_unpack_tokens.argtypes = [C.POINTER(StageDesc), C.c_void_p, C.c_size_t, C.POINTER(KvView), C.c_int32,
+                                           C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
         l.fxp_profile_class_name.restype = C.c_char_p
         l.fxp_profile_class_name.argtypes = [C.c_int]
         l.fxp_profile_read.argtypes = [C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
@@ -275,3 +284,48 @@ def kv_unpack(shape, packed: torch.Tensor, dst: KVCache, layer_begin: int, layer
     v = dst.c_view(keep)
     _check(lib().fxp_kv_unpack(C.byref(desc), packed.data_ptr(), packed.numel() * packed.element_size(), C.byref(v),
                                layer_begin, layer_end, ctx_lens.data_ptr(), ctx_lens.shape[0], _stream()))
+
+
+def _lens_ptr(t: torch.Tensor) -> int:
+    assert t.is_cuda and t.dtype == torch.int32 and t.is_contiguous()
+    return t.data_ptr()
+
+
+def kv_repartition_range(shape, src: Sequence[KVCache], dst: Sequence[KVCache], from_lens: torch.Tensor,
+                         to_lens: torch.Tensor) -> None:
+    """Incremental pass: only tokens [from_lens[i], to_lens[i]) of every sequence."""
+    keep: list = []
+    desc = make_desc(shape, 0, 1)
+    s = (KvView * len(src))(*[v.c_view(keep) for v in src])
+    d = (KvView * len(dst))(*[v.c_view(keep) for v in dst])
+    assert from_lens.shape == to_lens.shape
+    _check(lib().fxp_kv_repartition_range(C.byref(desc), s, len(src), d, len(dst), _lens_ptr(from_lens), _lens_ptr(to_lens),
+                                          to_lens.shape[0], _stream()))
+
+
+def kv_packed_tokens_bytes(shape, layer_begin: int, layer_end: int, from_lens_host, to_lens_host) -> int:
+    import numpy as np
+    fl = np.ascontiguousarray(from_lens_host, dtype=np.int32)
+    tl = np.ascontiguousarray(to_lens_host, dtype=np.int32)
+    assert fl.shape == tl.shape
+    desc = make_desc(shape, 0, 1)
+    return lib().fxp_kv_packed_tokens_bytes(C.byref(desc), layer_begin, layer_end, fl.ctypes.data, tl.ctypes.data, tl.shape[0])
+
+
+def kv_pack_tokens(shape, src: KVCache, layer_begin: int, layer_end: int, from_lens: torch.Tensor, to_lens: torch.Tensor,
+                   packed: torch.Tensor) -> None:
+    keep: list = []
+    desc = make_desc(shape, 0, 1)
+    v = src.c_view(keep)
+    _check(lib().fxp_kv_pack_tokens(C.byref(desc), C.byref(v), layer_begin, layer_end, _lens_ptr(from_lens), _lens_ptr(to_lens),
+                                    to_lens.shape[0], packed.data_ptr(), packed.numel() * packed.element_size(), _stream()))
+
+
+def kv_unpack_tokens(shape, packed: torch.Tensor, dst: KVCache, layer_begin: int, layer_end: int, from_lens: torch.Tensor,
+                     to_lens: torch.Tensor) -> None:
+    keep: list = []
+    desc = make_desc(shape, 0, 1)
+    v = dst.c_view(keep)
+    _check(lib().fxp_kv_unpack_tokens(C.byref(desc), packed.data_ptr(), packed.numel() * packed.element_size(), C.byref(v),
+                                      layer_begin, layer_end, _lens_ptr(from_lens), _lens_ptr(to_lens), to_lens.shape[0],
+                                      _stream()))

@@ -538,24 +538,28 @@ static fxp::KvMoveSide pool_side(const fxp_kv_view &v)
     fxp::KvMoveSide s;
     s.base = (char *)v.pool->base; s.table = v.block_table; s.num_blocks = v.pool->num_blocks; s.limit_bytes = 0;
     s.layer_base = v.pool->layer_begin; s.n_layers = v.pool->layer_end - v.pool->layer_begin; s.max_blocks_per_seq = v.max_blocks_per_seq;
+    s.token_dense = 0;
     return s;
 }
 
-static fxp::KvMoveSide packed_side(const void *buf, size_t bytes, int lb, int le)
+static fxp::KvMoveSide packed_side(const void *buf, size_t bytes, int lb, int le, bool token_dense = false)
 {
     fxp::KvMoveSide s;
     s.base = (char *)buf; s.table = nullptr; s.num_blocks = 0; s.limit_bytes = (int64_t)bytes;
     s.layer_base = lb; s.n_layers = le - lb; s.max_blocks_per_seq = 0;
+    s.token_dense = token_dense ? 1 : 0;
     return s;
 }
 
 static int move_grid(const fxp::KvMoveArgs &a, int max_blocks_per_seq)
 {
-    const int64_t chunks = (a.unit_bytes + 16383) / 16384;
+    const int64_t chunks = (a.unit_bytes + fxp::kv_move_chunk_bytes() - 1) / fxp::kv_move_chunk_bytes();
     int64_t items = 0;
     for (int j = 0; j < a.n_jobs; ++j)
         items += (int64_t)a.num_seqs * max_blocks_per_seq * (a.jobs[j].layer_end - a.jobs[j].layer_begin) * chunks;
-    int64_t grid = (int64_t)device_cus() * env_int("FXP_MOVE_WGS_PER_CU", 8);
+    // persistent grid: as many workgroups as are resident (the token-dense variant needs more registers)
+    const bool dense = a.n_jobs > 0 && (a.jobs[0].src.token_dense || a.jobs[0].dst.token_dense);
+    int64_t grid = (int64_t)device_cus() * (dense ? 4 : env_int("FXP_MOVE_WGS_PER_CU", 8));
     if (grid > items) grid = items;
     return (int)(grid < 1 ? 1 : grid);
 }
@@ -569,8 +573,8 @@ static int launch_moves(fxp::KvMoveArgs &a, int max_blocks_per_seq, hipStream_t 
     return FXP_OK;
 }
 
-int fxp_kv_repartition(const fxp_stage_desc *desc, const fxp_kv_view *src, int32_t n_src, const fxp_kv_view *dst,
-                       int32_t n_dst, const int32_t *ctx_lens, int32_t num_seqs, void *hip_stream)
+static int repartition_impl(const fxp_stage_desc *desc, const fxp_kv_view *src, int32_t n_src, const fxp_kv_view *dst,
+                            int32_t n_dst, const int32_t *from_lens, const int32_t *ctx_lens, int32_t num_seqs, void *hip_stream)
 {
     if (int rc = check_kv_geom(desc)) return rc;
     if (!src || !dst || n_src <= 0 || n_dst <= 0) return fail(FXP_EINVAL, "empty view list");
@@ -592,7 +596,7 @@ int fxp_kv_repartition(const fxp_stage_desc *desc, const fxp_kv_view *src, int32
     if (!ctx_lens) return fail(FXP_EINVAL, "ctx_lens is null");
 
     fxp::KvMoveArgs a;
-    a.ctx_lens = ctx_lens; a.unit_bytes = unit; a.num_seqs = num_seqs; a.head_dim = desc->head_dim; a.n_jobs = 0;
+    a.from_lens = from_lens; a.to_lens = ctx_lens; a.unit_bytes = unit; a.num_seqs = num_seqs; a.head_dim = desc->head_dim; a.n_jobs = 0;
     int max_blocks = 0;
     for (int t = 0; t < n_dst; ++t)
         for (int s = 0; s < n_src; ++s) {
@@ -611,6 +615,19 @@ int fxp_kv_repartition(const fxp_stage_desc *desc, const fxp_kv_view *src, int32
     return launch_moves(a, max_blocks, (hipStream_t)hip_stream);
 }
 
+int fxp_kv_repartition(const fxp_stage_desc *desc, const fxp_kv_view *src, int32_t n_src, const fxp_kv_view *dst,
+                       int32_t n_dst, const int32_t *ctx_lens, int32_t num_seqs, void *hip_stream)
+{
+    return repartition_impl(desc, src, n_src, dst, n_dst, nullptr, ctx_lens, num_seqs, hip_stream);
+}
+
+int fxp_kv_repartition_range(const fxp_stage_desc *desc, const fxp_kv_view *src, int32_t n_src, const fxp_kv_view *dst,
+                             int32_t n_dst, const int32_t *from_lens, const int32_t *to_lens, int32_t num_seqs, void *hip_stream)
+{
+    if (num_seqs > 0 && !from_lens) return fail(FXP_EINVAL, "from_lens is null");
+    return repartition_impl(desc, src, n_src, dst, n_dst, from_lens, to_lens, num_seqs, hip_stream);
+}
+
 size_t fxp_kv_packed_bytes(const fxp_stage_desc *desc, int32_t layer_begin, int32_t layer_end,
                            const int32_t *ctx_lens_host, int32_t num_seqs)
 {
@@ -624,8 +641,9 @@ size_t fxp_kv_packed_bytes(const fxp_stage_desc *desc, int32_t layer_begin, int3
     return blocks * (size_t)(layer_end - layer_begin) * 2 * desc->n_kv_heads * 16 * desc->head_dim * 2;
 }
 
-static int pack_or_unpack(const fxp_stage_desc *desc, const fxp_kv_view *view, int lb, int le, const int32_t *ctx_lens,
-                          int num_seqs, void *packed, size_t packed_bytes, bool to_packed, void *hip_stream)
+static int pack_or_unpack(const fxp_stage_desc *desc, const fxp_kv_view *view, int lb, int le, const int32_t *from_lens,
+                          const int32_t *ctx_lens, int num_seqs, void *packed, size_t packed_bytes, bool to_packed,
+                          bool token_dense, void *hip_stream)
 {
     if (int rc = check_kv_geom(desc)) return rc;
     if (!view) return fail(FXP_EINVAL, "view is null");
@@ -634,28 +652,61 @@ static int pack_or_unpack(const fxp_stage_desc *desc, const fxp_kv_view *view, i
         return fail(FXP_EINVAL, "layers [%d,%d) are not inside the pool's [%d,%d)", lb, le, view->pool->layer_begin, view->pool->layer_end);
     if (num_seqs < 0 || num_seqs > 16383) return fail(FXP_EINVAL, "num_seqs %d out of range [0,16383]", num_seqs);
     if (num_seqs == 0) return FXP_OK;
-    if (!ctx_lens || !packed) return fail(FXP_EINVAL, "null buffer");
+    if (!ctx_lens || !packed || (token_dense && !from_lens)) return fail(FXP_EINVAL, "null buffer");
     const int64_t unit = 2ll * desc->n_kv_heads * 16 * desc->head_dim * 2;
-    if (packed_bytes < (size_t)unit * (size_t)(le - lb)) return fail(FXP_ENOSPC, "packed buffer smaller than one block per layer");
+    if (token_dense) {
+        if (packed_bytes < 16) return fail(FXP_ENOSPC, "packed buffer smaller than one vector");
+    } else if (packed_bytes < (size_t)unit * (size_t)(le - lb)) {
+        return fail(FXP_ENOSPC, "packed buffer smaller than one block per layer");
+    }
     fxp::KvMoveArgs a;
-    a.ctx_lens = ctx_lens; a.unit_bytes = unit; a.num_seqs = num_seqs; a.head_dim = desc->head_dim; a.n_jobs = 1;
+    a.from_lens = from_lens; a.to_lens = ctx_lens; a.unit_bytes = unit; a.num_seqs = num_seqs; a.head_dim = desc->head_dim; a.n_jobs = 1;
     fxp::KvMoveJob &j = a.jobs[0];
     j.layer_begin = lb; j.layer_end = le;
-    if (to_packed) { j.src = pool_side(*view); j.dst = packed_side(packed, packed_bytes, lb, le); }
-    else           { j.src = packed_side(packed, packed_bytes, lb, le); j.dst = pool_side(*view); }
+    if (to_packed) { j.src = pool_side(*view); j.dst = packed_side(packed, packed_bytes, lb, le, token_dense); }
+    else           { j.src = packed_side(packed, packed_bytes, lb, le, token_dense); j.dst = pool_side(*view); }
     return launch_moves(a, view->max_blocks_per_seq, (hipStream_t)hip_stream);
 }
 
 int fxp_kv_pack(const fxp_stage_desc *desc, const fxp_kv_view *src, int32_t layer_begin, int32_t layer_end,
                 const int32_t *ctx_lens, int32_t num_seqs, void *packed, size_t packed_bytes, void *hip_stream)
 {
-    return pack_or_unpack(desc, src, layer_begin, layer_end, ctx_lens, num_seqs, packed, packed_bytes, true, hip_stream);
+    return pack_or_unpack(desc, src, layer_begin, layer_end, nullptr, ctx_lens, num_seqs, packed, packed_bytes, true, false, hip_stream);
 }
 
 int fxp_kv_unpack(const fxp_stage_desc *desc, const void *packed, size_t packed_bytes, const fxp_kv_view *dst,
                   int32_t layer_begin, int32_t layer_end, const int32_t *ctx_lens, int32_t num_seqs, void *hip_stream)
 {
-    return pack_or_unpack(desc, dst, layer_begin, layer_end, ctx_lens, num_seqs, const_cast<void *>(packed), packed_bytes, false, hip_stream);
+    return pack_or_unpack(desc, dst, layer_begin, layer_end, nullptr, ctx_lens, num_seqs, const_cast<void *>(packed), packed_bytes, false, false, hip_stream);
+}
+
+size_t fxp_kv_packed_tokens_bytes(const fxp_stage_desc *desc, int32_t layer_begin, int32_t layer_end,
+                                  const int32_t *from_lens_host, const int32_t *to_lens_host, int32_t num_seqs)
+{
+    if (check_kv_geom(desc) != FXP_OK) return 0;
+    if (layer_begin < 0 || layer_end <= layer_begin || num_seqs < 0 || (num_seqs > 0 && (!from_lens_host || !to_lens_host))) {
+        fail(FXP_EINVAL, "bad argument to fxp_kv_packed_tokens_bytes");
+        return 0;
+    }
+    size_t tokens = 0;
+    for (int i = 0; i < num_seqs; ++i)
+        if (from_lens_host[i] >= 0 && to_lens_host[i] > from_lens_host[i]) tokens += (size_t)(to_lens_host[i] - from_lens_host[i]);
+    return tokens * (size_t)(layer_end - layer_begin) * 2 * desc->n_kv_heads * desc->head_dim * 2;
+}
+
+int fxp_kv_pack_tokens(const fxp_stage_desc *desc, const fxp_kv_view *src, int32_t layer_begin, int32_t layer_end,
+                       const int32_t *from_lens, const int32_t *to_lens, int32_t num_seqs, void *packed, size_t packed_bytes,
+                       void *hip_stream)
+{
+    return pack_or_unpack(desc, src, layer_begin, layer_end, from_lens, to_lens, num_seqs, packed, packed_bytes, true, true, hip_stream);
+}
+
+int fxp_kv_unpack_tokens(const fxp_stage_desc *desc, const void *packed, size_t packed_bytes, const fxp_kv_view *dst,
+                         int32_t layer_begin, int32_t layer_end, const int32_t *from_lens, const int32_t *to_lens,
+                         int32_t num_seqs, void *hip_stream)
+{
+    return pack_or_unpack(desc, dst, layer_begin, layer_end, from_lens, to_lens, num_seqs, const_cast<void *>(packed), packed_bytes,
+                          false, true, hip_stream);
 }
 
 }  // extern "C"

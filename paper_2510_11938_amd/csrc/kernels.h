@@ -20,6 +20,7 @@ struct KvMoveSide {
     int32_t layer_base;          // model layer stored at index 0
     int32_t n_layers;            // packed: layers in the buffer
     int32_t max_blocks_per_seq;
+    int32_t token_dense;         // 1: buffer of token rows [sequence][layer][K,V][head][token - from][dim]
 };
 struct KvMoveJob {
     KvMoveSide src, dst;
@@ -27,11 +28,13 @@ struct KvMoveJob {
 };
 struct KvMoveArgs {
     KvMoveJob jobs[kMaxMoveJobs];
-    const int32_t *ctx_lens;     // device [num_seqs]
+    const int32_t *from_lens;    // device [num_seqs] or nullptr (= 0): first token of each sequence to move
+    const int32_t *to_lens;      // device [num_seqs]: one past the last valid token
     int64_t unit_bytes;          // bytes of one (layer, block): 2 * Hkv * 16 * D * 2
     int32_t n_jobs, num_seqs, head_dim;
 };
 hipError_t launch_kv_move(const KvMoveArgs &args, int grid, hipStream_t stream);
+int kv_move_chunk_bytes();     // bytes of one work item
 
 // ---------------------------------------------------------------- weights
 // W[N][K] row-major bf16 -> packed[n_tile][k_step][lane][8] (k zero-padded to k_steps*32).

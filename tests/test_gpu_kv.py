@@ -183,3 +183,99 @@ def test_full_size_7b_repartition_sampled_against_oracle():
         for i in sample:
             blocks = dv.block_table[i, : nblk[i]].cpu().numpy()
             assert np.array_equal(gp[:, blocks], hp[:, blocks])
+
+
+# ---------------------------------------------------------------------------
+# Incremental passes (Section 6.3: the transfer runs while decoding continues) and
+# the token-dense packed form: same bit-exact bar against the oracle.
+
+RANGE_CASES = [
+    # (Hkv, D, src ranges, dst ranges, from, to)
+    (4, 64, [(0, 2)], [(0, 1), (1, 2)], [30, 128, 0, 100], [37, 128, 32, 117]),                # none / zero-length / from empty / crosses a block
+    (2, 8, [(3, 5), (5, 9)], [(3, 6), (6, 7), (7, 9)], [5, 16, 1, 0, 11, 250], [6, 17, 1, 0, 40, 251]),
+    (3, 128, [(0, 3)], [(0, 1), (1, 3)], [299, 0, 63], [300, 17, 97]),                         # 24 KiB units
+    (8, 128, [(0, 4)], [(0, 2), (2, 4)], [1000, 333, 2047, 16, 0], [1024, 334, 2050, 16, 700]),  # 64 KiB units
+    (32, 128, [(0, 2)], [(0, 1), (1, 2)], [199, 512], [200, 530]),                             # 256 KiB units (7B shape)
+]
+
+
+@pytest.mark.parametrize("hkv,d,src_r,dst_r,lo,hi", RANGE_CASES)
+def test_range_repartition_matches_oracle_bit_exact(hkv, d, src_r, dst_r, lo, hi):
+    ms = geom(hkv, d)
+    lo, hi = np.array(lo, dtype=np.int32), np.array(hi, dtype=np.int32)
+    hs, ds = make_views(ms, src_r, hi, seed=11)
+    hd, dd = make_views(ms, dst_r, hi, seed=12, spare=3)
+    oracle.kv_repartition_range(oracle_shape(ms), hs, hd, lo, hi)
+    binding.kv_repartition_range(ms, ds, dd, dev_i32(lo), dev_i32(hi))
+    torch.cuda.synchronize()
+    for h, g in zip(hd, dd):
+        assert np.array_equal(host_bits(g.pool), h.pool)          # moved rows, zeroed tail, everything else untouched
+    for h, g in zip(hs, ds):
+        assert np.array_equal(host_bits(g.pool), h.pool)
+
+
+def test_snapshot_pass_then_delta_pass_equals_one_pass_on_gpu():
+    ms = geom(4, 64)
+    snap = np.array([37, 128, 0, 100, 15], dtype=np.int32)
+    now = np.array([40, 128, 5, 117, 16], dtype=np.int32)
+    _, src = make_views(ms, [(0, 1), (1, 3)], now, seed=13)
+    _, one = make_views(ms, [(0, 3)], now, seed=14)
+    _, two = make_views(ms, [(0, 3)], now, seed=14)
+    binding.kv_repartition(ms, src, one, dev_i32(now))
+    binding.kv_repartition(ms, src, two, dev_i32(snap))
+    binding.kv_repartition_range(ms, src, two, dev_i32(snap), dev_i32(now))
+    torch.cuda.synchronize()
+    assert np.array_equal(host_bits(one[0].pool), host_bits(two[0].pool))
+
+
+def test_range_with_inverted_or_negative_range_moves_nothing_for_that_sequence():
+    ms = geom(2, 64)
+    hi = np.array([20, 20, 20], dtype=np.int32)
+    lo = np.array([25, -3, 4], dtype=np.int32)                    # the library reads lengths on the device: it cannot reject these
+    hs, ds = make_views(ms, [(0, 1)], hi, seed=15)
+    hd, dd = make_views(ms, [(0, 1)], hi, seed=16)
+    ok_lo, ok_hi = np.array([0, 0, 4], dtype=np.int32), np.array([0, 0, 20], dtype=np.int32)
+    oracle.kv_repartition_range(oracle_shape(ms), hs, hd, ok_lo, ok_hi)     # what must happen: only sequence 2 moves
+    binding.kv_repartition_range(ms, ds, dd, dev_i32(lo), dev_i32(hi))
+    torch.cuda.synchronize()
+    assert np.array_equal(host_bits(dd[0].pool), hd[0].pool)
+
+
+@pytest.mark.parametrize("hkv,d,lo,hi", [(4, 64, [30, 0, 128, 5, 9], [37, 0, 128, 40, 10]), (3, 128, [0, 16], [300, 17]),
+                                          (8, 128, [990, 2047, 0], [1000, 2050, 1])])
+def test_token_dense_pack_and_unpack_match_oracle(hkv, d, lo, hi):
+    ms = geom(hkv, d)
+    osh = oracle_shape(ms)
+    lo, hi = np.array(lo, dtype=np.int32), np.array(hi, dtype=np.int32)
+    hs, ds = make_views(ms, [(2, 6)], hi, seed=17)
+    lb, le = 3, 6
+    want = oracle.kv_pack_tokens(osh, hs[0], lb, le, lo, hi)
+    nbytes = binding.kv_packed_tokens_bytes(ms, lb, le, lo, hi)
+    assert nbytes == want.size * 2
+    pad = 64                                                       # guard words after the buffer must survive
+    packed = torch.full((nbytes // 2 + pad,), 0x5555, dtype=torch.int16, device="cuda")
+    dlo, dhi = dev_i32(lo), dev_i32(hi)
+    binding.kv_pack_tokens(ms, ds[0], lb, le, dlo, dhi, packed[:nbytes // 2])
+    torch.cuda.synchronize()
+    got = host_bits(packed)
+    assert np.array_equal(got[:nbytes // 2], want)
+    assert np.all(got[nbytes // 2:] == 0x5555)
+    hd, dd = make_views(ms, [(3, 6)], hi, seed=18, spare=1)
+    oracle.kv_unpack_tokens(osh, want, hd[0], lb, le, lo, hi)
+    binding.kv_unpack_tokens(ms, packed[:nbytes // 2], dd[0], lb, le, dlo, dhi)
+    torch.cuda.synchronize()
+    assert np.array_equal(host_bits(dd[0].pool), hd[0].pool)
+
+
+def test_token_dense_pack_never_writes_past_a_short_buffer():
+    ms = geom(4, 64)
+    lo, hi = np.array([0, 3], dtype=np.int32), np.array([50, 40], dtype=np.int32)
+    hs, ds = make_views(ms, [(0, 2)], hi, seed=19)
+    want = oracle.kv_pack_tokens(oracle_shape(ms), hs[0], 0, 2, lo, hi)
+    short = want.size // 3 // 8 * 8                                # a third of the needed size, whole 16-byte vectors
+    packed = torch.full((want.size,), 0x5555, dtype=torch.int16, device="cuda")
+    binding.kv_pack_tokens(ms, ds[0], 0, 2, dev_i32(lo), dev_i32(hi), packed[:short])
+    torch.cuda.synchronize()
+    got = host_bits(packed)
+    assert np.array_equal(got[:short], want[:short])               # what fits is right
+    assert np.all(got[short:] == 0x5555)                           # nothing beyond the size given
