@@ -114,6 +114,23 @@ int    fxp_stage_create(const fxp_stage_desc *desc, const fxp_layer_weights *lay
                         fxp_stage **out);
 int    fxp_stage_destroy(fxp_stage *stage);
 
+/* ---- refinement and consolidation of stages (Section 6: a stage is split when
+ * burst capacity is needed and stages are merged in stable periods; Section 5:
+ * the parameters of a group stay contiguous so that merged stages reuse the
+ * existing layout).  Both calls are host-only metadata operations: the new
+ * handles point into the arena of the stages they came from, no weight is
+ * moved and nothing is enqueued on any stream.  The inputs stay valid and are
+ * destroyed separately; the arena must outlive every handle that points into it.
+ * split: layer_mid strictly inside the stage's range, else FXP_EINVAL.
+ * merge: `upper` must start at the layer where `lower` ends, have the same model
+ * geometry, and its layer records must directly follow `lower`'s in memory (true
+ * for the halves of a split, or for stages created side by side in one arena);
+ * otherwise FXP_EINVAL and the caller builds the merged stage with
+ * fxp_stage_create.  fxp_stage_layers reports a handle's layer range. */
+int    fxp_stage_split(const fxp_stage *stage, int32_t layer_mid, fxp_stage **lower, fxp_stage **upper);
+int    fxp_stage_merge(const fxp_stage *lower, const fxp_stage *upper, fxp_stage **out);
+int    fxp_stage_layers(const fxp_stage *stage, int32_t *layer_begin, int32_t *layer_end);
+
 /* ---- stage forward (Section 3.2, Table 2 "Compute": per-stage inference) ---
  * hidden_out = layers [l0,l1) applied to hidden_in, both DEVICE bf16
  * [num_tokens][hidden] (they may be the same buffer).  Each layer is the

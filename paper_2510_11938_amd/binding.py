@@ -23,6 +23,7 @@ FXP_OK, FXP_EINVAL, FXP_ENOSPC, FXP_EHIP = 0, -1, -2, -3
 EXPORTS = (
     "fxp_stage_weight_arena_bytes", "fxp_stage_create", "fxp_stage_destroy",
     "fxp_stage_workspace_bytes", "fxp_stage_forward", "fxp_stage_forward_debug",
+    "fxp_stage_split", "fxp_stage_merge", "fxp_stage_layers",
     "fxp_kv_repartition", "fxp_kv_packed_bytes", "fxp_kv_pack", "fxp_kv_unpack",
     "fxp_kv_repartition_range", "fxp_kv_packed_tokens_bytes", "fxp_kv_pack_tokens", "fxp_kv_unpack_tokens",
     "fxp_profile_enable", "fxp_profile_num_classes", "fxp_profile_class_name", "fxp_profile_read", "fxp_profile_read_launch",
@@ -89,6 +90,9 @@ def lib() -> C.CDLL:
         l.fxp_stage_create.argtypes = [C.POINTER(StageDesc), C.POINTER(LayerWeights), C.c_void_p, C.c_size_t,
                                        C.c_void_p, C.POINTER(C.c_void_p)]
         l.fxp_stage_destroy.argtypes = [C.c_void_p]
+        l.fxp_stage_split.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p)]
+        l.fxp_stage_merge.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p)]
+        l.fxp_stage_layers.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
         l.fxp_stage_workspace_bytes.restype = C.c_size_t
         l.fxp_stage_workspace_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32]
         l.fxp_stage_forward.argtypes = [C.c_void_p, C.POINTER(KvPool), C.POINTER(Batch), C.c_void_p, C.c_void_p,
@@ -207,6 +211,31 @@ class Stage:
         _check(lib().fxp_stage_create(C.byref(self.desc), arr, self.arena.data_ptr(), nbytes, _stream(), C.byref(handle)))
         self.handle = handle
         self._ws: Optional[torch.Tensor] = None
+
+    @classmethod
+    def _adopt(cls, shape, handle: C.c_void_p, arena: torch.Tensor) -> "Stage":
+        """Wrap a handle made by fxp_stage_split / fxp_stage_merge; ``arena`` is kept alive with it."""
+        st = cls.__new__(cls)
+        lb, le = C.c_int32(), C.c_int32()
+        _check(lib().fxp_stage_layers(handle, C.byref(lb), C.byref(le)))
+        st.shape, st.desc, st.arena, st.handle, st._ws = shape, make_desc(shape, lb.value, le.value), arena, handle, None
+        return st
+
+    @property
+    def layers(self):
+        return self.desc.layer_begin, self.desc.layer_end
+
+    def split(self, layer_mid: int):
+        """fxp_stage_split: two stages over [begin, mid) and [mid, end) sharing this stage's arena."""
+        lo, hi = C.c_void_p(), C.c_void_p()
+        _check(lib().fxp_stage_split(self.handle, layer_mid, C.byref(lo), C.byref(hi)))
+        return Stage._adopt(self.shape, lo, self.arena), Stage._adopt(self.shape, hi, self.arena)
+
+    def merge(self, upper: "Stage") -> "Stage":
+        """fxp_stage_merge: one stage over both ranges; the records must be adjacent in one arena."""
+        out = C.c_void_p()
+        _check(lib().fxp_stage_merge(self.handle, upper.handle, C.byref(out)))
+        return Stage._adopt(self.shape, out, self.arena)
 
     def close(self) -> None:
         if getattr(self, "handle", None):

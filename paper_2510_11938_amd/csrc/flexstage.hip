@@ -325,6 +325,48 @@ int fxp_stage_destroy(fxp_stage *stage)
     return FXP_OK;
 }
 
+int fxp_stage_layers(const fxp_stage *stage, int32_t *layer_begin, int32_t *layer_end)
+{
+    if (!stage || !layer_begin || !layer_end) return fail(FXP_EINVAL, "null argument to fxp_stage_layers");
+    *layer_begin = stage->d.layer_begin; *layer_end = stage->d.layer_end;
+    return FXP_OK;
+}
+
+// Refinement / consolidation of stages on handles.  Every layer is one contiguous record of the
+// arena, so a stage over a sub-range is the same arena seen from another record on: no weight is
+// moved, re-tiled or copied, and no kernel runs.
+int fxp_stage_split(const fxp_stage *stage, int32_t layer_mid, fxp_stage **lower, fxp_stage **upper)
+{
+    if (!stage || !lower || !upper) return fail(FXP_EINVAL, "null argument to fxp_stage_split");
+    if (layer_mid <= stage->d.layer_begin || layer_mid >= stage->d.layer_end)
+        return fail(FXP_EINVAL, "split point %d is not inside (%d,%d)", layer_mid, stage->d.layer_begin, stage->d.layer_end);
+    fxp_stage *lo = new (std::nothrow) fxp_stage(*stage), *hi = new (std::nothrow) fxp_stage(*stage);
+    if (!lo || !hi) { delete lo; delete hi; return fail(FXP_ENOSPC, "out of host memory"); }
+    lo->d.layer_end = layer_mid; lo->n_layers = layer_mid - stage->d.layer_begin;
+    hi->d.layer_begin = layer_mid; hi->n_layers = stage->d.layer_end - layer_mid;
+    hi->arena = stage->arena + stage->rec.bytes * (size_t)lo->n_layers;
+    *lower = lo; *upper = hi;
+    return FXP_OK;
+}
+
+int fxp_stage_merge(const fxp_stage *lower, const fxp_stage *upper, fxp_stage **out)
+{
+    if (!lower || !upper || !out) return fail(FXP_EINVAL, "null argument to fxp_stage_merge");
+    const fxp_stage_desc &a = lower->d, &b = upper->d;
+    if (a.layer_end != b.layer_begin) return fail(FXP_EINVAL, "stages [%d,%d) and [%d,%d) are not adjacent", a.layer_begin, a.layer_end, b.layer_begin, b.layer_end);
+    if (a.hidden != b.hidden || a.n_q_heads != b.n_q_heads || a.n_kv_heads != b.n_kv_heads || a.head_dim != b.head_dim ||
+        a.ffn != b.ffn || a.rms_eps != b.rms_eps || a.rope_base != b.rope_base || a.kv_block_size != b.kv_block_size)
+        return fail(FXP_EINVAL, "stages differ in model geometry");
+    if (upper->arena != lower->arena + lower->rec.bytes * (size_t)lower->n_layers)
+        return fail(FXP_EINVAL, "the upper stage's layer records do not follow the lower stage's in memory; "
+                                "create the merged stage with fxp_stage_create instead");
+    fxp_stage *m = new (std::nothrow) fxp_stage(*lower);
+    if (!m) return fail(FXP_ENOSPC, "out of host memory");
+    m->d.layer_end = b.layer_end; m->n_layers = lower->n_layers + upper->n_layers;
+    *out = m;
+    return FXP_OK;
+}
+
 size_t fxp_stage_workspace_bytes(const fxp_stage *stage, int32_t max_tokens, int32_t max_seqs, int32_t max_blocks_per_seq)
 {
     if (!stage || max_tokens < 0 || max_seqs < 0 || max_blocks_per_seq < 0) { fail(FXP_EINVAL, "bad argument to fxp_stage_workspace_bytes"); return 0; }

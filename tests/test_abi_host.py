@@ -70,3 +70,14 @@ def test_null_and_malformed_repartition_arguments():
     assert lib.fxp_kv_repartition(C.byref(d), C.byref(va), 1, C.byref(vb), 1, 0x4000, 1 << 20, None) == binding.FXP_EINVAL
     assert lib.fxp_stage_forward(None, None, None, None, None, None, 0, None) == binding.FXP_EINVAL
     assert lib.fxp_stage_workspace_bytes(None, 1, 1, 1) == 0
+
+
+def test_split_and_merge_reject_null_handles_without_touching_the_gpu():
+    import ctypes as C
+    l = binding.lib()
+    a, b = C.c_void_p(), C.c_void_p()
+    assert l.fxp_stage_split(None, 1, C.byref(a), C.byref(b)) == binding.FXP_EINVAL
+    assert l.fxp_stage_merge(None, None, C.byref(a)) == binding.FXP_EINVAL
+    lo, hi = C.c_int32(), C.c_int32()
+    assert l.fxp_stage_layers(None, C.byref(lo), C.byref(hi)) == binding.FXP_EINVAL
+    assert b"null" in l.fxp_last_error()

@@ -186,6 +186,57 @@ def test_split_stages_compose_to_unsplit_stage_bit_exact_on_gpu(kind):
     assert torch.equal(y_all.view(torch.int16), y_split.view(torch.int16))
 
 
+def test_stage_split_and_merge_on_handles_share_the_arena_and_change_no_arithmetic():
+    """Refinement and consolidation as metadata operations (Section 6; layout rule of Section 5):
+    the halves of a split behave exactly like stages created from scratch, their composition is
+    the unsplit stage, and merging them back gives the original -- all bit for bit."""
+    ms, L = TINY, 3
+    case = Case(ms, L, [37, 128, 32, 100], [1] * 4, seed=21)
+    whole = make_stage(ms, case.w, 0, L)
+    y_all, _ = case.gpu_run(stage=whole)
+    lo, hi = whole.split(1)
+    assert lo.layers == (0, 1) and hi.layers == (1, 3)
+    assert lo.arena.data_ptr() == whole.arena.data_ptr() == hi.arena.data_ptr()      # no copy of the weights
+
+    def run_pair(a, b):
+        c0, c1 = case.gpu_cache(0, 1), case.gpu_cache(1, 3)
+        mid = a.forward(c0, dev_i32(case.cu), dev_i32(case.ctx), dev_bf16(case.hidden_bits), 1)
+        out = b.forward(c1, dev_i32(case.cu), dev_i32(case.ctx), mid, 1)
+        torch.cuda.synchronize()
+        return mid, out
+
+    mid_h, y_h = run_pair(lo, hi)
+    mid_f, y_f = run_pair(make_stage(ms, case.w, 0, 1), make_stage(ms, case.w, 1, 3))
+    assert torch.equal(mid_h.view(torch.int16), mid_f.view(torch.int16))
+    assert torch.equal(y_h.view(torch.int16), y_f.view(torch.int16))
+    assert torch.equal(y_h.view(torch.int16), y_all.view(torch.int16))
+    hi_a, hi_b = hi.split(2)                                                          # split of a split
+    merged = lo.merge(hi_a).merge(hi_b)
+    assert merged.layers == (0, 3)
+    y_m, _ = case.gpu_run(stage=merged)
+    assert torch.equal(y_m.view(torch.int16), y_all.view(torch.int16))
+    whole.close()                                                                     # handles are independent of their parent
+    y_m2, _ = case.gpu_run(stage=merged)
+    assert torch.equal(y_m2.view(torch.int16), y_all.view(torch.int16))
+    with pytest.raises(binding.FxpError):
+        whole_again = make_stage(ms, case.w, 0, L)
+        whole_again.split(0)                                                          # not strictly inside
+    with pytest.raises(binding.FxpError):
+        hi_a.merge(lo)                                                                # wrong order
+    # adjacent layers but separate arenas: at most one of two lower stages can sit directly
+    # before the upper one in memory, so at least one merge must be refused
+    a, c, b = make_stage(ms, case.w, 0, 1), make_stage(ms, case.w, 0, 1), make_stage(ms, case.w, 1, 3)
+    refused = 0
+    for lower in (a, c):
+        try:
+            lower.merge(b)
+        except binding.FxpError:
+            refused += 1
+    assert refused >= 1
+    with pytest.raises(binding.FxpError):
+        lo.merge(make_stage(MID128, make_weights(MID128, 3, 2), 1, 2))                # other geometry
+
+
 def test_bit_exact_under_block_permutation_and_run_to_run():
     ms, L = GQA64, 2
     ctx = [700, 16, 1, 513, 90]
