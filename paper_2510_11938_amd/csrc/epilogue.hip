@@ -15,6 +15,7 @@ namespace fxp {
 
 constexpr int kRowThreads = 256;
 
+template <int THREADS = kRowThreads>
 __device__ __forceinline__ float block_sum(float v, float *red)
 {
     v = wave_sum(v);
@@ -24,7 +25,7 @@ __device__ __forceinline__ float block_sum(float v, float *red)
     __syncthreads();
     float t = 0.f;
 #pragma unroll
-    for (int w = 0; w < kRowThreads / 64; ++w) t += red[w];
+    for (int w = 0; w < THREADS / 64; ++w) t += red[w];
     return t;
 }
 
@@ -37,17 +38,35 @@ __device__ __forceinline__ u32x4 pack8(const float (&f)[8])
 {
     return u32x4{pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]), pack_bf16x2(f[6], f[7])};
 }
-// sum over the S split-K slices of 8 consecutive columns of row t, in slice order
+// sum over the S split-K slices of 8 consecutive columns of row t, in slice order.
+// The loads of a group of G slices are all issued before the first add (a loop over a
+// run-time S issues them one latency after the other); indices past S are clamped to the
+// last slice and their values dropped.
+template <int G>
+__device__ __forceinline__ void partial8_group(const float *P, int S, int s0, int64_t slice_stride, int64_t off, float (&f)[8])
+{
+    f32x4_t a[G], b[G];
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+        const float *p = P + (int64_t)min(s0 + j, S - 1) * slice_stride + off;
+        a[j] = *reinterpret_cast<const f32x4_t *>(p);
+        b[j] = *reinterpret_cast<const f32x4_t *>(p + 4);
+    }
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+        if (s0 + j < S) {
+            f[0] += a[j][0]; f[1] += a[j][1]; f[2] += a[j][2]; f[3] += a[j][3];
+            f[4] += b[j][0]; f[5] += b[j][1]; f[6] += b[j][2]; f[7] += b[j][3];
+        }
+    }
+}
 __device__ __forceinline__ void partial8(const float *P, int S, int64_t slice_stride, int64_t off, float (&f)[8])
 {
 #pragma unroll
     for (int e = 0; e < 8; ++e) f[e] = 0.f;
-    for (int s = 0; s < S; ++s) {
-        const f32x4_t a = *reinterpret_cast<const f32x4_t *>(P + s * slice_stride + off);
-        const f32x4_t b = *reinterpret_cast<const f32x4_t *>(P + s * slice_stride + off + 4);
-        f[0] += a[0]; f[1] += a[1]; f[2] += a[2]; f[3] += a[3];
-        f[4] += b[0]; f[5] += b[1]; f[6] += b[2]; f[7] += b[3];
-    }
+    if (S <= 2) partial8_group<2>(P, S, 0, slice_stride, off, f);
+    else if (S <= 4) partial8_group<4>(P, S, 0, slice_stride, off, f);
+    else for (int s0 = 0; s0 < S; s0 += 8) partial8_group<8>(P, S, s0, slice_stride, off, f);
 }
 
 // ---------------------------------------------------------------- rmsnorm
@@ -82,13 +101,17 @@ hipError_t launch_rmsnorm(const void *x, const void *g, void *out, int T, int H,
 }
 
 // ---------------------------------------------------------------- residual (+ norm)
-__global__ __launch_bounds__(kRowThreads) void resid_norm_kernel(ResidNormArgs a)
+// (512 threads: at hidden 4096 every thread owns one 8-wide chunk, so all partial-sum loads of
+// a row are in flight at once)
+constexpr int kNormThreads = 512;
+
+__global__ __launch_bounds__(kNormThreads) void resid_norm_kernel(ResidNormArgs a)
 {
-    __shared__ float red[kRowThreads / 64];
+    __shared__ float red[kNormThreads / 64];
     const int t = blockIdx.x;
     const int64_t row = (int64_t)t * a.H;
     float ss = 0.f;
-    for (int c = threadIdx.x; c < a.H / 8; c += kRowThreads) {
+    for (int c = threadIdx.x; c < a.H / 8; c += kNormThreads) {
         float f[8], p[8];
         unpack8(ld16(a.x + row + c * 8), f);
         partial8(a.P, a.S, (int64_t)a.T * a.H, row + c * 8, p);
@@ -101,8 +124,8 @@ __global__ __launch_bounds__(kRowThreads) void resid_norm_kernel(ResidNormArgs a
         for (int e = 0; e < 8; ++e) ss += f[e] * f[e];
     }
     if (!a.g) return;
-    const float rstd = rsqrtf(block_sum(ss, red) / (float)a.H + a.eps);
-    for (int c = threadIdx.x; c < a.H / 8; c += kRowThreads) {
+    const float rstd = rsqrtf(block_sum<kNormThreads>(ss, red) / (float)a.H + a.eps);
+    for (int c = threadIdx.x; c < a.H / 8; c += kNormThreads) {
         float f[8], gg[8];
         unpack8(ld16(a.h + row + c * 8), f);    // written by this same thread above
         unpack8(ld16(a.g + c * 8), gg);
@@ -114,7 +137,7 @@ __global__ __launch_bounds__(kRowThreads) void resid_norm_kernel(ResidNormArgs a
 
 hipError_t launch_resid_norm(const ResidNormArgs &a, hipStream_t stream)
 {
-    hipLaunchKernelGGL(resid_norm_kernel, dim3(a.T), dim3(kRowThreads), 0, stream, a);
+    hipLaunchKernelGGL(resid_norm_kernel, dim3(a.T), dim3(kNormThreads), 0, stream, a);
     return hipGetLastError();
 }
 
