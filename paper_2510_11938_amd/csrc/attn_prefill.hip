@@ -82,50 +82,83 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_kernel(PrefillAttnArg
     constexpr int kChunksPerRow = D / 8;
     constexpr int kChunksPerThread = kPfKvTile * kChunksPerRow / kPfThreads;
 
+    // The K and V rows of the next tile travel from the cache to registers while the current
+    // tile is being multiplied: the table look-up and the cache read are two dependent memory
+    // round trips that would otherwise sit between every two tiles.
+    // Thread tid owns chunk dc of rows r0 + i * kRowsPerPass of a tile; kRowsPerPass is a multiple
+    // of the cache block, so its slot inside a block and its byte offset inside a unit never change
+    // and only the block-table entry differs from load to load.
+    constexpr int kRowsPerPass = kPfThreads / kChunksPerRow;
+    static_assert(kRowsPerPass % kBlockTokens == 0, "a pass of the staging loop covers whole cache blocks");
+    const int r0 = tid / kChunksPerRow, dc0 = tid % kChunksPerRow;
+    const uint16_t *lane_base = layer_base + (int64_t)hk * head_elems + (int64_t)(r0 % kBlockTokens) * D + dc0 * 8;
+    const int64_t v_off = (int64_t)a.n_kv_heads * head_elems;
+    const int last_blk = (n_keys - 1) / kBlockTokens;
+    u32x4 kreg[kChunksPerThread], vreg[kChunksPerThread];
+    auto fetch_tile = [&](int tile) {
+        const int kv0 = tile * kPfKvTile;
+#pragma unroll
+        for (int i = 0; i < kChunksPerThread; ++i) {
+            const int r = r0 + i * kRowsPerPass;
+            const int32_t phys = table[min((kv0 + r) / kBlockTokens, last_blk)];   // unconditional loads, rows past the end zeroed below
+            const uint16_t *kp = lane_base + (int64_t)phys * unit_elems;
+            const u32x4 kvec = ld16(kp);
+            const u32x4 vvec = ld16(kp + v_off);
+            const bool ok = kv0 + r < n_keys;
+            kreg[i] = ok ? kvec : u32x4{0u, 0u, 0u, 0u};
+            vreg[i] = ok ? vvec : u32x4{0u, 0u, 0u, 0u};
+        }
+    };
+    fetch_tile(0);
+
     for (int tile = 0; tile < n_tiles; ++tile) {
         const int kv0 = tile * kPfKvTile;
         // ---- stage K and V (both row-major, padded pitches) of keys kv0 .. kv0+63
         __syncthreads();
 #pragma unroll
         for (int i = 0; i < kChunksPerThread; ++i) {
-            const int qd = i * kPfThreads + tid;
-            const int r = qd / kChunksPerRow, dc = qd % kChunksPerRow;
-            const int kv = kv0 + r;
-            u32x4 kvec = {0u, 0u, 0u, 0u}, vvec = {0u, 0u, 0u, 0u};
-            if (kv < n_keys) {
-                const int32_t phys = table[kv / kBlockTokens];
-                const uint16_t *kp = layer_base + (int64_t)phys * unit_elems + (int64_t)hk * head_elems
-                                     + (int64_t)(kv % kBlockTokens) * D + dc * 8;
-                kvec = ld16(kp);
-                vvec = ld16(kp + (int64_t)a.n_kv_heads * head_elems);
-            }
-            *reinterpret_cast<u32x4 *>(s_k + r * kKPitch + dc * 16) = kvec;
-            *reinterpret_cast<u32x4 *>(s_v + r * kVPitch + dc * 16) = vvec;
+            const int r = r0 + i * kRowsPerPass;
+            *reinterpret_cast<u32x4 *>(s_k + r * kKPitch + dc0 * 16) = kreg[i];
+            *reinterpret_cast<u32x4 *>(s_v + r * kVPitch + dc0 * 16) = vreg[i];
         }
         __syncthreads();
+        if (tile + 1 < n_tiles) fetch_tile(tile + 1);
         if (kv0 > wave_last_pos) continue;          // whole tile is in this wave's future (wave-uniform)
 
         // ---- S^T = K . Q^T for the 4 sub-tiles of 16 keys
+        // (below the diagonal every key of the tile is visible to every query row of the wave:
+        // no mask arithmetic there)
+        const bool full_tile = !DEBUG && kv0 + kPfKvTile - 1 <= ctx + j0;
         float s[4][4];
+        f32x4_t acc[4];
 #pragma unroll
         for (int st = 0; st < 4; ++st) {
-            f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+            acc[st] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
                 const u32x4 kop = *reinterpret_cast<const u32x4 *>(s_k + (st * 16 + col) * kKPitch + ks * 64 + c * 16);
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kop),
-                                                              __builtin_bit_cast(bf16x8_t, qreg[ks]), acc, 0, 0, 0);
+                acc[st] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kop),
+                                                                  __builtin_bit_cast(bf16x8_t, qreg[ks]), acc[st], 0, 0, 0);
             }
+        }
+        if (full_tile) {
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int kv = kv0 + st * 16 + 4 * c + v;
-                const float sv = acc[v] * a.scale_log2e;
-                s[st][v] = (kv <= q_pos) ? sv : -INFINITY;
-                if constexpr (DEBUG) {
-                    if (q_ok && kv <= q_pos)
-                        a.dbg_scores[((int64_t)(t0 + jq) * a.n_q_heads + h) * a.dbg_stride + kv] = sv;
+            for (int st = 0; st < 4; ++st)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) s[st][v] = acc[st][v] * a.scale_log2e;
+        } else {
+#pragma unroll
+            for (int st = 0; st < 4; ++st)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int kv = kv0 + st * 16 + 4 * c + v;
+                    const float sv = acc[st][v] * a.scale_log2e;
+                    s[st][v] = (kv <= q_pos) ? sv : -INFINITY;
+                    if constexpr (DEBUG) {
+                        if (q_ok && kv <= q_pos)
+                            a.dbg_scores[((int64_t)(t0 + jq) * a.n_q_heads + h) * a.dbg_stride + kv] = sv;
+                    }
                 }
-            }
         }
         // ---- online softmax per query column (lanes col, col+16, col+32, col+48)
         float mx = m_run;
@@ -152,13 +185,14 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_kernel(PrefillAttnArg
             for (int e = 0; e < 8; ++e) psum += p[e];
             pop[u] = u32x4{pack_bf16x2(p[0], p[1]), pack_bf16x2(p[2], p[3]), pack_bf16x2(p[4], p[5]), pack_bf16x2(p[6], p[7])};
         }
-        psum += __shfl_xor(psum, 16, 64);
-        psum += __shfl_xor(psum, 32, 64);
-        l_run = l_run * alpha + psum;
-        // ---- O^T = O^T * alpha + V^T . P^T
+        l_run = l_run * alpha + psum;                 // per lane; the four lanes of a column are added once at the end
+        // ---- O^T = O^T * alpha + V^T . P^T  (the rescale only when some row's maximum moved)
+        if (__builtin_amdgcn_ballot_w64(alpha != 1.f)) {
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) o[dt] *= alpha;
+        }
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
-            o[dt] *= alpha;
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
                 // row operand: dim 16*dt + col; k slots 8c..8c+3 = keys 32u+4c.., 8c+4.. = keys 32u+16+4c..
@@ -174,6 +208,8 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_kernel(PrefillAttnArg
         }
     }
 
+    l_run += __shfl_xor(l_run, 16, 64);
+    l_run += __shfl_xor(l_run, 32, 64);
     if (!q_ok) return;
     const float inv = 1.f / l_run;
     uint16_t *op = a.out + ((int64_t)(t0 + jq) * a.n_q_heads + h) * D + 4 * c;
