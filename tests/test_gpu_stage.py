@@ -90,6 +90,7 @@ DECODE_CASES = [
     ("wide-ffn-40", WIDE_FFN, 1, list(range(5, 45))),
     ("batch-40", TINY, 1, list(range(5, 45))),                     # 3 row tiles, ragged
     ("batch-100", TINY, 1, [17 + (i * 7) % 90 for i in range(100)]),   # 7 row tiles
+    ("batch-150", TINY, 2, [9 + (i * 11) % 120 for i in range(150)]),  # above 128 rows: tiled projections feed the decode attention
 ]
 
 
