@@ -235,6 +235,44 @@ int    fxp_kv_unpack_tokens(const fxp_stage_desc *desc, const void *packed, size
                             const int32_t *from_lens, const int32_t *to_lens, int32_t num_seqs,
                             void *hip_stream);
 
+/* ---- granularity controller (host only; nothing is enqueued) ------------------
+ * The scalar decision formulas of the method, to be fed with stage throughput
+ * and latency measured through fxp_stage_forward at the candidate stage depths.
+ * All pointers are HOST memory.
+ *   fxp_ctl_cv                   nu_t = sigma_t / mu_t of the request arrival
+ *                                intervals (Section 6; population deviation).
+ *   fxp_ctl_select_granularity   Eq. 4: score_k = [alpha T_k/T_max + (1-alpha)
+ *                                L_min/L_k] exp(-|nu_t - nu_k| / sigma) with T_max,
+ *                                L_min over the candidates; *best_out = arg max
+ *                                (lowest index on ties); scores_out[n_cand] may
+ *                                be NULL.
+ *   fxp_ctl_parallel_instances   Eq. 5: floor(capacity_total / (T_k / (beta1 +
+ *                                beta2 eta_k))); -1 on a bad argument.
+ *   fxp_ctl_multiplexing_penalty gamma(CV) = gamma0 (1 + alpha CV^2), Section 6.2.
+ *   fxp_ctl_scaling_granularity  Eq. 11: floor(G_max / (1 + beta exp(-gamma cv
+ *                                min(q/Q_max, 1)))); -1 on a bad argument.
+ *   fxp_ctl_slo_satisfied        Section 7: 1 if (deadline - init_time) *
+ *                                sum_k stage_throughput[k] / queue_len >=
+ *                                requests, 0 if not, FXP_EINVAL on a bad argument.
+ * The constants alpha, sigma, nu_k, beta, gamma are not published: parameters. */
+typedef struct {
+    int32_t n_stages;      /* eta_k */
+    int32_t batch;         /* b_k   */
+    double  throughput;    /* T_k, any unit, > 0 */
+    double  latency;       /* L_k, any unit, > 0 */
+    double  cv_opt;        /* nu_k: the CV this granularity suits best */
+} fxp_granularity;
+int     fxp_ctl_cv(const double *intervals, int32_t n, double *cv_out);
+int     fxp_ctl_select_granularity(const fxp_granularity *cand, int32_t n_cand, double cv_now, double alpha,
+                                   double sigma, double *scores_out, int32_t *best_out);
+int64_t fxp_ctl_parallel_instances(double capacity_total, double throughput, double beta1, double beta2,
+                                   int32_t n_stages);
+double  fxp_ctl_multiplexing_penalty(double gamma0, double alpha, double cv);
+int32_t fxp_ctl_scaling_granularity(int32_t g_max, double beta, double gamma, double cv, double queue_len,
+                                    double queue_cap);
+int     fxp_ctl_slo_satisfied(double deadline, double init_time, const double *stage_throughput, int32_t n_stages,
+                              double queue_len, double requests);
+
 /* ---- per-kernel timing for benchmarks ---------------------------------------
  * While enabled, every kernel launch the library makes is bracketed by a pair
  * of HIP events recorded on the caller's stream (up to 8192 launches; later

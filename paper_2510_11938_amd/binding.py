@@ -26,9 +26,16 @@ EXPORTS = (
     "fxp_stage_split", "fxp_stage_merge", "fxp_stage_layers",
     "fxp_kv_repartition", "fxp_kv_packed_bytes", "fxp_kv_pack", "fxp_kv_unpack",
     "fxp_kv_repartition_range", "fxp_kv_packed_tokens_bytes", "fxp_kv_pack_tokens", "fxp_kv_unpack_tokens",
+    "fxp_ctl_cv", "fxp_ctl_select_granularity", "fxp_ctl_parallel_instances", "fxp_ctl_multiplexing_penalty",
+    "fxp_ctl_scaling_granularity", "fxp_ctl_slo_satisfied",
     "fxp_profile_enable", "fxp_profile_num_classes", "fxp_profile_class_name", "fxp_profile_read", "fxp_profile_read_launch",
     "fxp_last_error", "fxp_version",
 )
+
+
+class Granularity(C.Structure):
+    _fields_ = [("n_stages", C.c_int32), ("batch", C.c_int32), ("throughput", C.c_double), ("latency", C.c_double),
+                ("cv_opt", C.c_double)]
 
 
 class FxpError(RuntimeError):
@@ -115,6 +122,16 @@ def lib() -> C.CDLL:
                                          C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
         l.fxp_kv_unpack_tokens.argtypes = [C.POINTER(StageDesc), C.c_void_p, C.c_size_t, C.POINTER(KvView), C.c_int32,
                                            C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
+        l.fxp_ctl_cv.argtypes = [C.POINTER(C.c_double), C.c_int32, C.POINTER(C.c_double)]
+        l.fxp_ctl_select_granularity.argtypes = [C.POINTER(Granularity), C.c_int32, C.c_double, C.c_double, C.c_double,
+                                                 C.POINTER(C.c_double), C.POINTER(C.c_int32)]
+        l.fxp_ctl_parallel_instances.restype = C.c_int64
+        l.fxp_ctl_parallel_instances.argtypes = [C.c_double, C.c_double, C.c_double, C.c_double, C.c_int32]
+        l.fxp_ctl_multiplexing_penalty.restype = C.c_double
+        l.fxp_ctl_multiplexing_penalty.argtypes = [C.c_double, C.c_double, C.c_double]
+        l.fxp_ctl_scaling_granularity.restype = C.c_int32
+        l.fxp_ctl_scaling_granularity.argtypes = [C.c_int32, C.c_double, C.c_double, C.c_double, C.c_double, C.c_double]
+        l.fxp_ctl_slo_satisfied.argtypes = [C.c_double, C.c_double, C.POINTER(C.c_double), C.c_int32, C.c_double, C.c_double]
         l.fxp_profile_class_name.restype = C.c_char_p
         l.fxp_profile_class_name.argtypes = [C.c_int]
         l.fxp_profile_read.argtypes = [C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
@@ -358,3 +375,47 @@ def kv_unpack_tokens(shape, packed: torch.Tensor, dst: KVCache, layer_begin: int
     _check(lib().fxp_kv_unpack_tokens(C.byref(desc), packed.data_ptr(), packed.numel() * packed.element_size(), C.byref(v),
                                       layer_begin, layer_end, _lens_ptr(from_lens), _lens_ptr(to_lens), to_lens.shape[0],
                                       _stream()))
+
+
+# ---- granularity controller (host only) ------------------------------------------------
+
+def ctl_cv(intervals) -> float:
+    arr = (C.c_double * len(intervals))(*[float(v) for v in intervals])
+    out = C.c_double()
+    _check(lib().fxp_ctl_cv(arr, len(intervals), C.byref(out)))
+    return out.value
+
+
+def ctl_select_granularity(cands: Sequence[Granularity], cv_now: float, alpha: float, sigma: float):
+    """Eq. 4: returns (index of the best candidate, list of scores)."""
+    arr = (Granularity * len(cands))(*cands)
+    scores = (C.c_double * len(cands))()
+    best = C.c_int32()
+    _check(lib().fxp_ctl_select_granularity(arr, len(cands), cv_now, alpha, sigma, scores, C.byref(best)))
+    return best.value, list(scores)
+
+
+def ctl_parallel_instances(capacity_total: float, throughput: float, beta1: float, beta2: float, n_stages: int) -> int:
+    r = lib().fxp_ctl_parallel_instances(capacity_total, throughput, beta1, beta2, n_stages)
+    if r < 0:
+        raise FxpError(FXP_EINVAL, lib().fxp_last_error().decode())
+    return r
+
+
+def ctl_multiplexing_penalty(gamma0: float, alpha: float, cv: float) -> float:
+    return lib().fxp_ctl_multiplexing_penalty(gamma0, alpha, cv)
+
+
+def ctl_scaling_granularity(g_max: int, beta: float, gamma: float, cv: float, queue_len: float, queue_cap: float) -> int:
+    r = lib().fxp_ctl_scaling_granularity(g_max, beta, gamma, cv, queue_len, queue_cap)
+    if r < 0:
+        raise FxpError(FXP_EINVAL, lib().fxp_last_error().decode())
+    return r
+
+
+def ctl_slo_satisfied(deadline: float, init_time: float, stage_throughput, queue_len: float, requests: float) -> bool:
+    arr = (C.c_double * len(stage_throughput))(*[float(v) for v in stage_throughput])
+    r = lib().fxp_ctl_slo_satisfied(deadline, init_time, arr, len(stage_throughput), queue_len, requests)
+    if r < 0:
+        raise FxpError(r, lib().fxp_last_error().decode())
+    return bool(r)

@@ -11,7 +11,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libflexstage.so")
-UNITS = ["flexstage", "kv_move", "weight_pack", "gemm_skinny", "gemm_tiled", "epilogue", "attn_decode", "attn_prefill"]
+UNITS = ["flexstage", "kv_move", "weight_pack", "gemm_skinny", "gemm_tiled", "epilogue", "attn_decode", "attn_prefill",
+         "granularity"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -167,6 +167,11 @@ struct KernelTimer {     // records an event pair around the launches made durin
 
 }  // namespace
 
+namespace fxp {
+// error reporting for the host-only translation units of the library
+int ctl_fail(int code, const char *msg) { return fail(code, "%s", msg); }
+}
+
 struct fxp_stage {
     fxp_stage_desc d;
     int n_layers;

@@ -1,0 +1,107 @@
+"""Stage time against stage depth, and the granularity the controller would pick.
+
+The method chooses between pipeline granularities from their throughput T_k and latency
+L_k (Section 6.1, Eq. 4); the paper tabulates per-stage compute and communication time for
+several stage counts (Table 2).  This script measures the compute side on the GPU it runs
+on -- one decode step of a stage of 1, 2, 4, 8 ... layers through fxp_stage_forward -- and
+models the hand-off between stages (one [batch, hidden] bf16 transfer per step over a link of
+given bandwidth and latency).  With one GPU per stage and the pipeline full,
+    T_k = batch / (t_stage + t_handoff)          tokens/s
+    L_k = n_stages * (t_stage + t_handoff)       seconds per token through the pipeline
+and fxp_ctl_select_granularity scores the candidates for a range of traffic CVs.
+
+    python -m paper_2510_11938_amd.granularity_profile --layers-total 32 --depths 1,2,4,8
+
+Inputs are synthetic (random weights and cache contents; only the sizes matter for time).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import sys
+
+import numpy as np
+import torch
+
+from . import binding, synth
+
+
+def measure_stage_ms(ms: synth.ModelShape, depth: int, batch: int, ctx: np.ndarray, steps: int) -> float:
+    dev = torch.device("cuda:0")
+    g = torch.Generator(device=dev); g.manual_seed(depth)
+
+    def rnd(*shape, scale=0.02):
+        return (torch.randn(*shape, device=dev, generator=g) * scale).to(torch.bfloat16)
+
+    H, D, F = ms.hidden, ms.head_dim, ms.ffn
+    layers = [dict(g_attn=1 + rnd(H), wq=rnd(ms.n_q_heads * D, H), wk=rnd(ms.n_kv_heads * D, H), wv=rnd(ms.n_kv_heads * D, H),
+                   wo=rnd(H, ms.n_q_heads * D), g_ffn=1 + rnd(H), w_gate=rnd(F, H), w_up=rnd(F, H), w_down=rnd(H, F))
+              for _ in range(depth)]
+    stage = binding.Stage(ms, 0, depth, layers)
+    torch.cuda.synchronize()
+    del layers
+    table, nblk = synth.block_table(ctx + 1, 16, seed=depth)
+    pool = torch.empty((depth, nblk, 2, ms.n_kv_heads, 16, D), dtype=torch.bfloat16, device=dev).normal_(generator=g)
+    cache = binding.KVCache(pool, 0, depth, torch.from_numpy(table).to(dev))
+    x = rnd(batch, H, scale=1.0)
+    y = torch.empty_like(x)
+    cu = torch.arange(batch + 1, dtype=torch.int32, device=dev)
+    cl = torch.from_numpy(ctx).to(dev)
+    for _ in range(3):
+        stage.forward(cache, cu, cl, x, 1, hidden_out=y)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        stage.forward(cache, cu, cl, x, 1, hidden_out=y)
+    e1.record()
+    torch.cuda.synchronize()
+    stage.close()
+    return e0.elapsed_time(e1) / steps
+
+
+def main(argv=None) -> int:
+    ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
+    ap.add_argument("--layers-total", type=int, default=32)
+    ap.add_argument("--depths", default="1,2,4,8", help="layers per stage to measure")
+    ap.add_argument("--batch", type=int, default=32)
+    ap.add_argument("--ctx", default="512,4096", help="uniform context length range")
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--link-gbps", type=float, default=153.0, help="stage-to-stage link, GB/s (one xGMI link)")
+    ap.add_argument("--link-latency-us", type=float, default=10.0)
+    ap.add_argument("--alpha", type=float, default=0.5)
+    ap.add_argument("--sigma", type=float, default=1.0)
+    ap.add_argument("--cvs", default="0.25,1,2,4", help="traffic CVs to score")
+    args = ap.parse_args(argv)
+    ms = synth.LLAMA2_7B
+    lo, hi = (int(v) for v in args.ctx.split(","))
+    ctx = synth.draw_lengths(("uniform", lo, hi), args.batch, seed=1)
+    handoff_ms = (args.batch * ms.hidden * 2 / (args.link_gbps * 1e9) + args.link_latency_us * 1e-6) * 1e3
+    rows, cands = [], []
+    depths = [int(v) for v in args.depths.split(",")]
+    for depth in depths:
+        n_stages = args.layers_total // depth
+        t = measure_stage_ms(ms, depth, args.batch, ctx, args.steps)
+        thr = args.batch / ((t + handoff_ms) * 1e-3)
+        lat = n_stages * (t + handoff_ms)
+        rows.append({"layers_per_stage": depth, "n_stages": n_stages, "compute_ms": t, "handoff_ms": handoff_ms,
+                     "throughput_tokens_s": thr, "latency_ms": lat})
+        print(f"depth {depth:2d}: {n_stages:2d} stages, compute {t:7.3f} ms, hand-off {handoff_ms:6.3f} ms, "
+              f"T = {thr:9.0f} tokens/s, L = {lat:7.2f} ms", file=sys.stderr, flush=True)
+        # nu_k: finer granularities suit burstier traffic; spread the candidates over the CV range scored
+        cands.append(binding.Granularity(n_stages, args.batch, thr, lat, 0.0))
+    cvs = [float(v) for v in args.cvs.split(",")]
+    order = np.argsort([c.n_stages for c in cands])
+    for rank, k in enumerate(order):
+        cands[k].cv_opt = cvs[min(rank * len(cvs) // len(cands), len(cvs) - 1)]
+    picks = []
+    for cv in cvs:
+        best, scores = binding.ctl_select_granularity(cands, cv, args.alpha, args.sigma)
+        picks.append({"cv": cv, "selected_n_stages": cands[best].n_stages, "scores": scores})
+    print(json.dumps({"model": "7B shape", "batch": args.batch, "ctx_range": [lo, hi], "stages": rows,
+                      "cv_opt": [c.cv_opt for c in cands], "alpha": args.alpha, "sigma": args.sigma, "picks": picks}))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
