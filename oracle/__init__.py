@@ -62,6 +62,8 @@ def lib():
         _lib = C.CDLL(build())
         _lib.orc_silu.restype = C.c_double
         _lib.orc_silu.argtypes = [C.c_double]
+        _lib.orc_relu.restype = C.c_double
+        _lib.orc_relu.argtypes = [C.c_double]
         _lib.orc_kv_packed_elems.restype = C.c_int64
         _lib.orc_kv_packed_tokens_elems.restype = C.c_int64
     return _lib
@@ -323,3 +325,66 @@ def kv_unpack_tokens(shape: Shape, packed: np.ndarray, dst: KVView, lb: int, le:
                                     C.c_int32(lb), C.c_int32(le), _p(fl), _p(tl), C.c_int32(tl.shape[0]))
     if rc != 0:
         raise ValueError("orc_kv_unpack_tokens: malformed argument")
+
+
+# ---------------------------------------------------------------- OPT-style layer
+OPT_LAYER_TENSORS = ("ln1_g", "ln1_b", "wq", "bq", "wk", "bk", "wv", "bv", "wo", "bo",
+                     "ln2_g", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
+
+
+class _OptLayer(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in OPT_LAYER_TENSORS]
+
+
+def layernorm(x, g, b, eps: float) -> np.ndarray:
+    x = _f64(x); g = _f32(g); b = _f32(b)
+    y = np.empty_like(x)
+    rows = x.reshape(-1, x.shape[-1]); out = y.reshape(-1, x.shape[-1])
+    for r in range(rows.shape[0]):
+        lib().orc_layernorm(_p(rows[r]), _p(g), _p(b), C.c_int32(x.shape[-1]), C.c_double(eps), _p(out[r]))
+    return y
+
+
+def linear_bias(x, W, bias) -> np.ndarray:
+    x = _f64(x); W = _f32(W); bias = _f32(bias)
+    T, K = x.shape
+    N = W.shape[0]
+    assert W.shape[1] == K and bias.shape == (N,)
+    y = np.empty((T, N), dtype=np.float64)
+    lib().orc_linear_bias(_p(x), C.c_int32(T), _p(W), _p(bias), C.c_int32(N), C.c_int32(K), _p(y))
+    return y
+
+
+def relu(z: float) -> float:
+    return float(lib().orc_relu(C.c_double(z)))
+
+
+def stage_forward_opt(shape: Shape, layers: Sequence[dict], pool: np.ndarray,
+                      cu_seqlens_q, ctx_lens, block_table, hidden_in, probs_stride: int = 0):
+    """stage_forward for OPT-style layers (``layers[k]`` maps the OPT_LAYER_TENSORS names to
+    float32 arrays); ``shape.rms_eps`` is the LayerNorm epsilon."""
+    assert pool.dtype == np.float32 and pool.flags.c_contiguous
+    n_layers = len(layers)
+    assert pool.shape[0] == n_layers
+    keep = []
+    arr = (_OptLayer * max(n_layers, 1))()
+    for k, lw in enumerate(layers):
+        for name in OPT_LAYER_TENSORS:
+            a = _f32(lw[name]); keep.append(a)
+            setattr(arr[k], name, a.ctypes.data)
+    cu = _i32(cu_seqlens_q); cl = _i32(ctx_lens); bt = _i32(block_table)
+    num_seqs = cl.shape[0]
+    assert bt.ndim == 2 and bt.shape[0] == num_seqs and cu.shape[0] == num_seqs + 1
+    x = _f64(hidden_in)
+    T = int(cu[-1]) if num_seqs else 0
+    assert x.shape == (T, shape.hidden)
+    y = np.empty_like(x)
+    probs = (np.zeros((n_layers, T, shape.n_q_heads, probs_stride), dtype=np.float64) if probs_stride else None)
+    sh = shape.c()
+    rc = lib().orc_stage_forward_opt(
+        C.byref(sh), arr, C.c_int32(n_layers), _p(pool), C.c_int64(pool.shape[1]),
+        C.c_int32(num_seqs), _p(cu), _p(cl), _p(bt), C.c_int32(bt.shape[1]),
+        _p(x), _p(y), _p(probs) if probs_stride else None, C.c_int64(probs_stride))
+    if rc != 0:
+        raise ValueError("orc_stage_forward_opt: malformed argument")
+    return (y, probs) if probs_stride else y

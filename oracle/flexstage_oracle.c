@@ -21,6 +21,11 @@
  * feed-forward, two residual adds); that choice, and every other reading of a
  * point the paper leaves open, is listed in the design document.
  *
+ * A second layer kind states the OPT-style decoder layer (the model family the
+ * paper's own per-stage numbers are for, Table 2: OPT-66B): LayerNorm with bias
+ * before each block, biased linear maps, no rotary embedding (positions enter
+ * before the first layer, outside any stage), ReLU feed-forward.
+ *
  * Precision: weights, inputs and cache contents arrive as float (the tests feed
  * values that are exactly representable in bf16); every intermediate is double;
  * nothing is rounded between operations.  The cache this oracle appends to is
@@ -500,4 +505,115 @@ int orc_kv_unpack_tokens(const orc_shape *sh, int32_t elem_bytes, const void *pa
                          int32_t lb, int32_t le, const int32_t *from_lens, const int32_t *to_lens, int32_t num_seqs)
 {
     return pack_or_unpack_tokens(sh, elem_bytes, dst, lb, le, from_lens, to_lens, num_seqs, (unsigned char *)packed, 0);
+}
+
+/* ------------------------------------------------------------------ */
+/* OPT-style layer (Table 2's model family)                           */
+/* ------------------------------------------------------------------ */
+
+typedef struct {
+    const float *ln1_g, *ln1_b, *wq, *bq, *wk, *bk, *wv, *bv, *wo, *bo;
+    const float *ln2_g, *ln2_b, *w_fc1, *b_fc1, *w_fc2, *b_fc2;
+} orc_opt_layer;
+
+/* LayerNorm: y_k = (x_k - mean) / sqrt(var + eps) * g_k + b_k, var = mean((x - mean)^2). */
+void orc_layernorm(const double *x, const float *g, const float *b, int32_t H, double eps, double *y)
+{
+    double mean = 0.0;
+    for (int32_t k = 0; k < H; ++k) mean += x[k];
+    mean /= (double)H;
+    double var = 0.0;
+    for (int32_t k = 0; k < H; ++k) var += (x[k] - mean) * (x[k] - mean);
+    var /= (double)H;
+    double r = 1.0 / sqrt(var + eps);
+    for (int32_t k = 0; k < H; ++k) y[k] = (x[k] - mean) * r * (double)g[k] + (double)b[k];
+}
+
+/* y[t][n] = sum_k x[t][k] W[n][k] + bias[n] */
+void orc_linear_bias(const double *x, int32_t T, const float *W, const float *bias, int32_t N, int32_t K, double *y)
+{
+    orc_linear(x, T, W, N, K, y);
+    for (int32_t t = 0; t < T; ++t)
+        for (int32_t n = 0; n < N; ++n) y[(size_t)t * N + n] += (double)bias[n];
+}
+
+double orc_relu(double z) { return z > 0.0 ? z : 0.0; }
+
+/* One stage of OPT-style layers over a ragged batch; arguments and cache
+ * handling as in orc_stage_forward (sh->rms_eps is the LayerNorm epsilon,
+ * sh->rope_base is unused).  Per layer and token:
+ *   n = LN(x; ln1)            q,k,v = W n + b        k, v appended to the cache
+ *   o = causal softmax attention (scores scaled by 1/sqrt(D))
+ *   h = x + Wo o + bo         m = LN(h; ln2)
+ *   y = h + W2 relu(W1 m + b1) + b2 */
+int orc_stage_forward_opt(const orc_shape *sh, const orc_opt_layer *layers, int32_t n_layers,
+                          float *pool, int64_t num_blocks,
+                          int32_t num_seqs, const int32_t *cu_seqlens_q, const int32_t *ctx_lens,
+                          const int32_t *block_table, int32_t max_blocks_per_seq,
+                          const double *hidden_in, double *hidden_out,
+                          double *probs, int64_t probs_stride)
+{
+    if (!sh || !layers || n_layers < 0 || num_seqs < 0 || sh->n_kv_heads <= 0 || sh->n_q_heads % sh->n_kv_heads) return -1;
+    int32_t H = sh->hidden, D = sh->head_dim, Hq = sh->n_q_heads, Hkv = sh->n_kv_heads;
+    int32_t F = sh->ffn, bs = sh->kv_block_size;
+    int32_t T = num_seqs ? cu_seqlens_q[num_seqs] : 0;
+    if (T == 0) return 0;
+    for (int32_t i = 0; i < num_seqs; ++i) {
+        int64_t after = (int64_t)ctx_lens[i] + (cu_seqlens_q[i + 1] - cu_seqlens_q[i]);
+        if ((after + bs - 1) / bs > max_blocks_per_seq) return -1;
+    }
+    int32_t *tok_seq = (int32_t *)malloc(sizeof(int32_t) * (size_t)T);
+    int64_t *tok_pos = (int64_t *)malloc(sizeof(int64_t) * (size_t)T);
+    for (int32_t i = 0; i < num_seqs; ++i)
+        for (int32_t t = cu_seqlens_q[i]; t < cu_seqlens_q[i + 1]; ++t) {
+            tok_seq[t] = i;
+            tok_pos[t] = (int64_t)ctx_lens[i] + (t - cu_seqlens_q[i]);
+        }
+    size_t TH = (size_t)T * H, TQ = (size_t)T * Hq * D, TK = (size_t)T * Hkv * D, TF = (size_t)T * F;
+    double *x = (double *)malloc(sizeof(double) * TH);
+    double *nrm = (double *)malloc(sizeof(double) * TH);
+    double *q = (double *)malloc(sizeof(double) * TQ);
+    double *k = (double *)malloc(sizeof(double) * TK);
+    double *v = (double *)malloc(sizeof(double) * TK);
+    double *o = (double *)malloc(sizeof(double) * TQ);
+    double *proj = (double *)malloc(sizeof(double) * TH);
+    double *hmid = (double *)malloc(sizeof(double) * TH);
+    double *act = (double *)malloc(sizeof(double) * TF);
+    memcpy(x, hidden_in, sizeof(double) * TH);
+
+    for (int32_t ll = 0; ll < n_layers; ++ll) {
+        const orc_opt_layer *L = &layers[ll];
+        for (int32_t t = 0; t < T; ++t) orc_layernorm(x + (size_t)t * H, L->ln1_g, L->ln1_b, H, sh->rms_eps, nrm + (size_t)t * H);
+        orc_linear_bias(nrm, T, L->wq, L->bq, Hq * D, H, q);
+        orc_linear_bias(nrm, T, L->wk, L->bk, Hkv * D, H, k);
+        orc_linear_bias(nrm, T, L->wv, L->bv, Hkv * D, H, v);
+        for (int32_t t = 0; t < T; ++t) {
+            int64_t p = tok_pos[t];
+            const int32_t *row = block_table + (size_t)tok_seq[t] * max_blocks_per_seq;
+            for (int32_t h = 0; h < Hkv; ++h) {
+                const double *kh = k + ((size_t)t * Hkv + h) * D, *vh = v + ((size_t)t * Hkv + h) * D;
+                float *kdst = pool + pool_row(sh, num_blocks, ll, row[p / bs], 0, h, (int32_t)(p % bs));
+                float *vdst = pool + pool_row(sh, num_blocks, ll, row[p / bs], 1, h, (int32_t)(p % bs));
+                for (int32_t d = 0; d < D; ++d) { kdst[d] = (float)kh[d]; vdst[d] = (float)vh[d]; }
+            }
+        }
+#pragma omp parallel for schedule(dynamic, 1)
+        for (int32_t t = 0; t < T; ++t) {
+            const int32_t *row = block_table + (size_t)tok_seq[t] * max_blocks_per_seq;
+            double *pr = probs ? probs + (((size_t)ll * T + t) * Hq) * (size_t)probs_stride : NULL;
+            orc_attend_token(sh, pool, num_blocks, ll, row, tok_pos[t],
+                             q + (size_t)t * Hq * D, o + (size_t)t * Hq * D, pr, probs_stride);
+        }
+        orc_linear_bias(o, T, L->wo, L->bo, H, Hq * D, proj);
+        for (size_t e = 0; e < TH; ++e) hmid[e] = x[e] + proj[e];
+        for (int32_t t = 0; t < T; ++t) orc_layernorm(hmid + (size_t)t * H, L->ln2_g, L->ln2_b, H, sh->rms_eps, nrm + (size_t)t * H);
+        orc_linear_bias(nrm, T, L->w_fc1, L->b_fc1, F, H, act);
+        for (size_t e = 0; e < TF; ++e) act[e] = orc_relu(act[e]);
+        orc_linear_bias(act, T, L->w_fc2, L->b_fc2, H, F, proj);
+        for (size_t e = 0; e < TH; ++e) x[e] = hmid[e] + proj[e];
+    }
+    memcpy(hidden_out, x, sizeof(double) * TH);
+    free(tok_seq); free(tok_pos); free(x); free(nrm); free(q); free(k); free(v); free(o);
+    free(proj); free(hmid); free(act);
+    return 0;
 }

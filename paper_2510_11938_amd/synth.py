@@ -21,7 +21,7 @@ import numpy as np
 LAYER_TENSORS = ("g_attn", "wq", "wk", "wv", "wo", "g_ffn", "w_gate", "w_up", "w_down")
 
 # stream tags for the per-purpose generators
-_TAG_WEIGHT, _TAG_LENS, _TAG_PERM, _TAG_HIDDEN, _TAG_CACHE = 1, 2, 3, 4, 5
+_TAG_WEIGHT, _TAG_LENS, _TAG_PERM, _TAG_HIDDEN, _TAG_CACHE, _TAG_OPT_WEIGHT = 1, 2, 3, 4, 5, 6
 
 
 @dataclass(frozen=True)
@@ -34,6 +34,7 @@ class ModelShape:
     rms_eps: float = 1e-5
     rope_base: float = 10000.0
     kv_block_size: int = 16
+    arch: int = 0          # 0: Llama-style layer (RMSNorm, rotary, SwiGLU); 1: OPT-style (LayerNorm, biases, ReLU)
 
     @property
     def qkv_out(self) -> int:
@@ -47,6 +48,8 @@ class ModelShape:
     @property
     def params_per_layer(self) -> int:
         H, D, F = self.hidden, self.head_dim, self.ffn
+        if self.arch == 1:
+            return self.qkv_out * H + H * self.n_q_heads * D + 2 * F * H + self.qkv_out + 2 * H + F + 4 * H
         return (self.qkv_out * H + H * self.n_q_heads * D + 3 * F * H + 2 * H)
 
 
@@ -62,6 +65,8 @@ class Workload:
 
 
 TINY = ModelShape(hidden=256, n_q_heads=4, n_kv_heads=4, head_dim=64, ffn=688)
+TINY_OPT = ModelShape(hidden=256, n_q_heads=4, n_kv_heads=4, head_dim=64, ffn=1024, arch=1)
+OPT_66B = ModelShape(hidden=9216, n_q_heads=72, n_kv_heads=72, head_dim=128, ffn=36864, arch=1)
 LLAMA2_7B = ModelShape(hidden=4096, n_q_heads=32, n_kv_heads=32, head_dim=128, ffn=11008)
 LLAMA2_13B = ModelShape(hidden=5120, n_q_heads=40, n_kv_heads=40, head_dim=128, ffn=13824)
 LLAMA3_70B = ModelShape(hidden=8192, n_q_heads=64, n_kv_heads=8, head_dim=128, ffn=28672)
@@ -106,6 +111,29 @@ def layer_weights(shape: ModelShape, seed: int, layer: int) -> Dict[str, np.ndar
     for name in LAYER_TENSORS:
         a = g.standard_normal(dims[name], dtype=np.float32) * np.float32(0.02)
         if name.startswith("g_"):
+            a = a + np.float32(1.0)
+        out[name] = f32_to_bf16_bits(a)
+    return out
+
+
+OPT_LAYER_TENSORS = ("ln1_g", "ln1_b", "wq", "bq", "wk", "bk", "wv", "bv", "wo", "bo",
+                     "ln2_g", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
+
+
+def opt_layer_weights(shape: ModelShape, seed: int, layer: int) -> Dict[str, np.ndarray]:
+    """bf16 bit patterns of one OPT-style layer: matrices and biases ~ N(0, 0.02), LayerNorm gains
+    1 + N(0, 0.02)."""
+    g = _rng(seed, _TAG_OPT_WEIGHT, layer)
+    H, D, F = shape.hidden, shape.head_dim, shape.ffn
+    Nq, Nkv = shape.n_q_heads * D, shape.n_kv_heads * D
+    dims = {
+        "ln1_g": (H,), "ln1_b": (H,), "wq": (Nq, H), "bq": (Nq,), "wk": (Nkv, H), "bk": (Nkv,), "wv": (Nkv, H), "bv": (Nkv,),
+        "wo": (H, Nq), "bo": (H,), "ln2_g": (H,), "ln2_b": (H,), "w_fc1": (F, H), "b_fc1": (F,), "w_fc2": (H, F), "b_fc2": (H,),
+    }
+    out = {}
+    for name in OPT_LAYER_TENSORS:
+        a = g.standard_normal(dims[name], dtype=np.float32) * np.float32(0.02)
+        if name.endswith("_g"):
             a = a + np.float32(1.0)
         out[name] = f32_to_bf16_bits(a)
     return out

@@ -51,3 +51,40 @@ class DenseStage:
             m = F.rms_norm(h, (s.hidden,), L["g_ffn"], eps=s.rms_eps)
             x = h + (F.silu(m @ L["w_gate"].T) * (m @ L["w_up"].T)) @ L["w_down"].T
         return x
+
+
+class DenseOptStage:
+    """The OPT-style layer (LayerNorm with bias, biased projections, no rotary embedding, ReLU
+    feed-forward) re-stated with torch library ops on dense per-sequence K/V histories."""
+
+    def __init__(self, shape, layers_f32):
+        self.s = shape
+        self.layers = [{k: torch.from_numpy(v).double() for k, v in lw.items()} for lw in layers_f32]
+        self.hist = {}
+
+    def forward(self, seq_ids, q_lens, ctx_lens, hidden):
+        s = self.s
+        x = hidden.clone()
+        rep = s.n_q_heads // s.n_kv_heads
+        for li, L in enumerate(self.layers):
+            n = F.layer_norm(x, (s.hidden,), L["ln1_g"], L["ln1_b"], eps=s.rms_eps)
+            q = F.linear(n, L["wq"], L["bq"]).view(-1, s.n_q_heads, s.head_dim)
+            k = F.linear(n, L["wk"], L["bk"]).view(-1, s.n_kv_heads, s.head_dim)
+            v = F.linear(n, L["wv"], L["bv"]).view(-1, s.n_kv_heads, s.head_dim)
+            o = torch.empty_like(q)
+            at = 0
+            for sid, ql, c in zip(seq_ids, q_lens, ctx_lens):
+                pos = torch.arange(c, c + ql)
+                Kh, Vh = self.hist.get((li, sid), (k[:0], k[:0]))
+                assert Kh.shape[0] == c
+                Kh = torch.cat([Kh, k[at:at + ql]]); Vh = torch.cat([Vh, v[at:at + ql]])
+                self.hist[(li, sid)] = (Kh, Vh)
+                mask = torch.arange(c + ql)[None, :] <= pos[:, None]
+                o[at:at + ql] = F.scaled_dot_product_attention(
+                    q[at:at + ql].permute(1, 0, 2), Kh.permute(1, 0, 2).repeat_interleave(rep, 0),
+                    Vh.permute(1, 0, 2).repeat_interleave(rep, 0), attn_mask=mask[None]).permute(1, 0, 2)
+                at += ql
+            h = x + F.linear(o.reshape(-1, s.n_q_heads * s.head_dim), L["wo"], L["bo"])
+            m = F.layer_norm(h, (s.hidden,), L["ln2_g"], L["ln2_b"], eps=s.rms_eps)
+            x = h + F.linear(F.relu(F.linear(m, L["w_fc1"], L["b_fc1"])), L["w_fc2"], L["b_fc2"])
+        return x
