@@ -52,7 +52,16 @@ typedef struct {
     float   rms_eps;
     float   rope_base;
     int32_t kv_block_size;                    /* tokens per cache block: must be 16      */
+    int32_t arch;                             /* FXP_ARCH_LLAMA or FXP_ARCH_OPT          */
 } fxp_stage_desc;
+
+/* Layer kinds.  LLAMA: RMSNorm, rotary embedding, SwiGLU feed-forward, no biases.
+ * OPT (the model family of the paper's per-stage measurements, Table 2):
+ * LayerNorm with bias (rms_eps is its epsilon), biased projections, no rotary
+ * embedding (positions enter before the first layer, outside any stage; rope_base
+ * is ignored), feed-forward relu(W1 m + b1) then W2 . + b2. */
+#define FXP_ARCH_LLAMA 0
+#define FXP_ARCH_OPT   1
 
 /* One decoder layer's parameters.  DEVICE, bf16, every matrix row-major
  * [out_features][in_features]; gains are [hidden]. */
@@ -63,6 +72,14 @@ typedef struct {
     const void *g_ffn;                        /* [H]            feed-forward RMSNorm gain*/
     const void *w_gate, *w_up;                /* [F][H]                                  */
     const void *w_down;                       /* [H][F]                                  */
+    /* FXP_ARCH_OPT only (ignored for FXP_ARCH_LLAMA): w_gate must be NULL, w_up is the
+     * first and w_down the second feed-forward matrix, g_attn / g_ffn are the LayerNorm
+     * gains, and these biases are added: */
+    const void *b_attn_norm, *b_ffn_norm;     /* [H]            LayerNorm biases         */
+    const void *bq, *bk, *bv;                 /* [Hq*D], [Hkv*D], [Hkv*D]                */
+    const void *bo;                           /* [H]                                     */
+    const void *b_up;                         /* [F]                                     */
+    const void *b_down;                       /* [H]                                     */
 } fxp_layer_weights;
 
 /* A stage's paged KV cache.  DEVICE, bf16, caller-owned, logical shape

@@ -49,15 +49,21 @@ class StageDesc(C.Structure):
         ("layer_begin", C.c_int32), ("layer_end", C.c_int32), ("hidden", C.c_int32),
         ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
         ("ffn", C.c_int32), ("rms_eps", C.c_float), ("rope_base", C.c_float),
-        ("kv_block_size", C.c_int32),
+        ("kv_block_size", C.c_int32), ("arch", C.c_int32),
     ]
 
 
+ARCH_LLAMA, ARCH_OPT = 0, 1
 LAYER_TENSORS = ("g_attn", "wq", "wk", "wv", "wo", "g_ffn", "w_gate", "w_up", "w_down")
+BIAS_TENSORS = ("b_attn_norm", "b_ffn_norm", "bq", "bk", "bv", "bo", "b_up", "b_down")
+# an OPT-style layer's tensors by their usual names -> fields of fxp_layer_weights
+OPT_TENSOR_FIELDS = {"ln1_g": "g_attn", "ln1_b": "b_attn_norm", "wq": "wq", "bq": "bq", "wk": "wk", "bk": "bk", "wv": "wv", "bv": "bv",
+                     "wo": "wo", "bo": "bo", "ln2_g": "g_ffn", "ln2_b": "b_ffn_norm", "w_fc1": "w_up", "b_fc1": "b_up",
+                     "w_fc2": "w_down", "b_fc2": "b_down"}
 
 
 class LayerWeights(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in LAYER_TENSORS]
+    _fields_ = [(n, C.c_void_p) for n in LAYER_TENSORS + BIAS_TENSORS]
 
 
 class KvPool(C.Structure):
@@ -182,7 +188,8 @@ def make_desc(shape, layer_begin: int, layer_end: int) -> StageDesc:
     """``shape`` is any object with hidden / n_q_heads / n_kv_heads / head_dim / ffn /
     rms_eps / rope_base / kv_block_size attributes."""
     return StageDesc(layer_begin, layer_end, shape.hidden, shape.n_q_heads, shape.n_kv_heads,
-                     shape.head_dim, shape.ffn, shape.rms_eps, shape.rope_base, shape.kv_block_size)
+                     shape.head_dim, shape.ffn, shape.rms_eps, shape.rope_base, shape.kv_block_size,
+                     int(getattr(shape, "arch", ARCH_LLAMA)))
 
 
 @dataclass
@@ -215,11 +222,14 @@ class Stage:
         if len(layers) != n:
             raise ValueError("one weight dict per layer")
         arr = (LayerWeights * n)()
+        opt = self.desc.arch == ARCH_OPT
         for k, lw in enumerate(layers):
-            for name in LAYER_TENSORS:
+            # Llama-style: the nine fields by name; OPT-style: the sixteen tensors by their usual names
+            fields = OPT_TENSOR_FIELDS if opt else {n: n for n in LAYER_TENSORS}
+            for name, field in fields.items():
                 t = lw[name]
                 assert t.is_cuda and t.is_contiguous() and t.element_size() == 2, name
-                setattr(arr[k], name, t.data_ptr())
+                setattr(arr[k], field, t.data_ptr())
         nbytes = lib().fxp_stage_weight_arena_bytes(C.byref(self.desc))
         if nbytes == 0:
             raise FxpError(FXP_EINVAL, lib().fxp_last_error().decode())

@@ -69,34 +69,66 @@ __device__ __forceinline__ void partial8(const float *P, int S, int64_t slice_st
     else for (int s0 = 0; s0 < S; s0 += 8) partial8_group<8>(P, S, s0, slice_stride, off, f);
 }
 
-// ---------------------------------------------------------------- rmsnorm
-__global__ __launch_bounds__(kRowThreads) void rmsnorm_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ g,
-                                                              uint16_t *__restrict__ out, int H, float eps)
+// ---------------------------------------------------------------- rmsnorm / layernorm
+// Sum over the row of f(x) by all threads of the workgroup.
+template <int THREADS, typename F>
+__device__ __forceinline__ float row_reduce(const uint16_t *row, int H, float *red, F f)
 {
-    __shared__ float red[kRowThreads / 64];
-    const int64_t row = (int64_t)blockIdx.x * H;
-    float ss = 0.f;
-    for (int c = threadIdx.x; c < H / 8; c += kRowThreads) {
-        float f[8];
-        unpack8(ld16(x + row + c * 8), f);
+    float acc = 0.f;
+    for (int c = threadIdx.x; c < H / 8; c += THREADS) {
+        float v[8];
+        unpack8(ld16(row + c * 8), v);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) ss += f[e] * f[e];
+        for (int e = 0; e < 8; ++e) acc += f(v[e]);
     }
-    const float rstd = rsqrtf(block_sum(ss, red) / (float)H + eps);
-    for (int c = threadIdx.x; c < H / 8; c += kRowThreads) {
+    return block_sum<THREADS>(acc, red);
+}
+
+// The normalisation of one row that is already in memory as bf16: RMSNorm when nb is null,
+// LayerNorm (mean removed, variance of the deviations, bias added) otherwise.  ss is the row's
+// sum of squares when the caller has it already (RMSNorm only), negative otherwise.
+template <int THREADS>
+__device__ __forceinline__ void norm_row(const uint16_t *row, const uint16_t *g, const uint16_t *nb, uint16_t *out, int H,
+                                         float eps, float ss, float *red)
+{
+    float mean = 0.f, rstd;
+    if (nb) {
+        mean = row_reduce<THREADS>(row, H, red, [](float v) { return v; }) / (float)H;
+        const float var = row_reduce<THREADS>(row, H, red, [mean](float v) { return (v - mean) * (v - mean); }) / (float)H;
+        rstd = rsqrtf(var + eps);
+    } else {
+        if (ss < 0.f) ss = row_reduce<THREADS>(row, H, red, [](float v) { return v * v; });
+        rstd = rsqrtf(ss / (float)H + eps);
+    }
+    for (int c = threadIdx.x; c < H / 8; c += THREADS) {
         float f[8], gg[8];
-        unpack8(ld16(x + row + c * 8), f);
+        unpack8(ld16(row + c * 8), f);
         unpack8(ld16(g + c * 8), gg);
+        if (nb) {
+            float bb[8];
+            unpack8(ld16(nb + c * 8), bb);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) f[e] = f[e] * rstd * gg[e];
-        st16(out + row + c * 8, pack8(f));
+            for (int e = 0; e < 8; ++e) f[e] = (f[e] - mean) * rstd * gg[e] + bb[e];
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) f[e] = f[e] * rstd * gg[e];
+        }
+        st16(out + c * 8, pack8(f));
     }
 }
 
-hipError_t launch_rmsnorm(const void *x, const void *g, void *out, int T, int H, float eps, hipStream_t stream)
+__global__ __launch_bounds__(kRowThreads) void rmsnorm_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ g,
+                                                              const uint16_t *__restrict__ b, uint16_t *__restrict__ out, int H, float eps)
+{
+    __shared__ float red[kRowThreads / 64];
+    const int64_t row = (int64_t)blockIdx.x * H;
+    norm_row<kRowThreads>(x + row, g, b, out + row, H, eps, -1.f, red);
+}
+
+hipError_t launch_rmsnorm(const void *x, const void *g, const void *b, void *out, int T, int H, float eps, hipStream_t stream)
 {
     hipLaunchKernelGGL(rmsnorm_kernel, dim3(T), dim3(kRowThreads), 0, stream, static_cast<const uint16_t *>(x),
-                       static_cast<const uint16_t *>(g), static_cast<uint16_t *>(out), H, eps);
+                       static_cast<const uint16_t *>(g), static_cast<const uint16_t *>(b), static_cast<uint16_t *>(out), H, eps);
     return hipGetLastError();
 }
 
@@ -115,6 +147,12 @@ __global__ __launch_bounds__(kNormThreads) void resid_norm_kernel(ResidNormArgs 
         float f[8], p[8];
         unpack8(ld16(a.x + row + c * 8), f);
         partial8(a.P, a.S, (int64_t)a.T * a.H, row + c * 8, p);
+        if (a.bias) {
+            float bb[8];
+            unpack8(ld16(a.bias + c * 8), bb);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) p[e] += bb[e];
+        }
 #pragma unroll
         for (int e = 0; e < 8; ++e) f[e] += p[e];
         const u32x4 hv = pack8(f);
@@ -124,15 +162,9 @@ __global__ __launch_bounds__(kNormThreads) void resid_norm_kernel(ResidNormArgs 
         for (int e = 0; e < 8; ++e) ss += f[e] * f[e];
     }
     if (!a.g) return;
-    const float rstd = rsqrtf(block_sum<kNormThreads>(ss, red) / (float)a.H + a.eps);
-    for (int c = threadIdx.x; c < a.H / 8; c += kNormThreads) {
-        float f[8], gg[8];
-        unpack8(ld16(a.h + row + c * 8), f);    // written by this same thread above
-        unpack8(ld16(a.g + c * 8), gg);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) f[e] = f[e] * rstd * gg[e];
-        st16(a.n + row + c * 8, pack8(f));
-    }
+    // (every thread reads back only the chunks it wrote itself)
+    if (a.nb) norm_row<kNormThreads>(a.h + row, a.g, a.nb, a.n + row, a.H, a.eps, -1.f, red);
+    else norm_row<kNormThreads>(a.h + row, a.g, nullptr, a.n + row, a.H, a.eps, block_sum<kNormThreads>(ss, red), red);
 }
 
 hipError_t launch_resid_norm(const ResidNormArgs &a, hipStream_t stream)
@@ -149,14 +181,23 @@ __global__ __launch_bounds__(kRowThreads) void swiglu_kernel(SwigluArgs a)
     const int t = blockIdx.x;
     const int c = blockIdx.y * kRowThreads + threadIdx.x;       // 8-wide output chunk of row t
     if (c >= a.F / 8) return;
-    const int64_t prow = (int64_t)t * 2 * a.F;
     const int f0 = c * 8;
-    const int64_t col = 32 * (f0 / 16) + (f0 % 16);
-    float gt[8], up[8];
-    partial8(a.P, a.S, (int64_t)a.T * 2 * a.F, prow + col, gt);
-    partial8(a.P, a.S, (int64_t)a.T * 2 * a.F, prow + col + 16, up);
+    float gt[8];
+    if (a.act == 1) {                       // relu(sum + bias), columns in natural order
+        float bb[8];
+        partial8(a.P, a.S, (int64_t)a.T * a.F, (int64_t)t * a.F + f0, gt);
+        unpack8(ld16(a.bias + f0), bb);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) gt[e] = gt[e] / (1.f + __expf(-gt[e])) * up[e];
+        for (int e = 0; e < 8; ++e) gt[e] = fmaxf(gt[e] + bb[e], 0.f);
+    } else {
+        const int64_t prow = (int64_t)t * 2 * a.F;
+        const int64_t col = 32 * (f0 / 16) + (f0 % 16);
+        float up[8];
+        partial8(a.P, a.S, (int64_t)a.T * 2 * a.F, prow + col, gt);
+        partial8(a.P, a.S, (int64_t)a.T * 2 * a.F, prow + col + 16, up);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) gt[e] = gt[e] / (1.f + __expf(-gt[e])) * up[e];
+    }
     st16(a.out + (int64_t)t * a.ld_out + f0, pack8(gt));
 }
 
@@ -191,8 +232,8 @@ __global__ __launch_bounds__(kRopeTableThreads) void rope_table_kernel(RopeTable
     __syncthreads();
     if ((int)threadIdx.x < half) {
         const double ang = (double)s_pos * pow((double)a.rope_base, -2.0 * (double)threadIdx.x / (double)a.head_dim);
-        a.cs[(int64_t)t * half + threadIdx.x] = (float)cos(ang);
-        a.sn[(int64_t)t * half + threadIdx.x] = (float)sin(ang);
+        a.cs[(int64_t)t * half + threadIdx.x] = a.identity ? 1.f : (float)cos(ang);
+        a.sn[(int64_t)t * half + threadIdx.x] = a.identity ? 0.f : (float)sin(ang);
     }
     // Workgroup 0 also leaves the exclusive prefix sums of the sequences' cache-block counts
     // (after this step's append), which the decode-attention kernels of every layer cut their
@@ -244,8 +285,17 @@ __global__ __launch_bounds__(kRowThreads) void qkv_rope_kvwrite_kernel(RopeArgs 
     const int64_t blk = ((int64_t)a.layer_local * a.num_blocks + phys) * 2;
 
     auto fetch8 = [&](int64_t col, float (&f)[8]) {
-        if constexpr (FROM_PARTIAL) partial8(a.P, a.S, (int64_t)a.T * Nall, src_row + col, f);
-        else unpack8(ld16(a.qkv + src_row + col), f);
+        if constexpr (FROM_PARTIAL) {
+            partial8(a.P, a.S, (int64_t)a.T * Nall, src_row + col, f);
+            if (a.bias) {
+                float bb[8];
+                unpack8(ld16(a.bias + col), bb);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) f[e] += bb[e];
+            }
+        } else {
+            unpack8(ld16(a.qkv + src_row + col), f);
+        }
     };
 
     if (c < n_rot) {

@@ -48,7 +48,8 @@ int check_desc(const fxp_stage_desc *d)
         return fail(FXP_EINVAL, "query heads per kv head must be 1..16 (got %d)", d->n_q_heads / d->n_kv_heads);
     if (d->hidden <= 0 || d->hidden % 16 || d->ffn <= 0 || d->ffn % 16)
         return fail(FXP_EINVAL, "hidden (%d) and ffn (%d) must be positive multiples of 16", d->hidden, d->ffn);
-    if (!(d->rms_eps >= 0.f) || !(d->rope_base > 1.f)) return fail(FXP_EINVAL, "bad rms_eps or rope_base");
+    if (d->arch != FXP_ARCH_LLAMA && d->arch != FXP_ARCH_OPT) return fail(FXP_EINVAL, "unknown layer kind %d", d->arch);
+    if (!(d->rms_eps >= 0.f) || (d->arch == FXP_ARCH_LLAMA && !(d->rope_base > 1.f))) return fail(FXP_EINVAL, "bad rms_eps or rope_base");
     return FXP_OK;
 }
 
@@ -64,6 +65,7 @@ int check_kv_geom(const fxp_stage_desc *d)
 
 struct LayerRecord {           // offsets into one layer's contiguous record in the arena
     size_t wqkv, wo, wgu, wd, g_attn, g_ffn, bytes;
+    size_t b_attn, b_ffn, b_qkv, b_o, b_up, b_down;     // OPT-style layers only
 };
 
 LayerRecord layer_record(const fxp_stage_desc &d)
@@ -73,10 +75,20 @@ LayerRecord layer_record(const fxp_stage_desc &d)
     size_t at = 0;
     r.wqkv = at; at += align_up(packed_bytes(Nqkv, d.hidden), 256);
     r.wo = at;   at += align_up(packed_bytes(d.hidden, Nq), 256);
-    r.wgu = at;  at += align_up(packed_bytes(2 * d.ffn, d.hidden), 256);
+    const bool opt = d.arch == FXP_ARCH_OPT;
+    r.wgu = at;  at += align_up(packed_bytes((opt ? 1 : 2) * d.ffn, d.hidden), 256);     // gate|up interleaved, or the first feed-forward matrix
     r.wd = at;   at += align_up(packed_bytes(d.hidden, d.ffn), 256);
     r.g_attn = at; at += align_up((size_t)d.hidden * 2, 256);
     r.g_ffn = at;  at += align_up((size_t)d.hidden * 2, 256);
+    r.b_attn = r.b_ffn = r.b_qkv = r.b_o = r.b_up = r.b_down = 0;
+    if (opt) {
+        r.b_attn = at; at += align_up((size_t)d.hidden * 2, 256);
+        r.b_ffn = at;  at += align_up((size_t)d.hidden * 2, 256);
+        r.b_qkv = at;  at += align_up((size_t)Nqkv * 2, 256);
+        r.b_o = at;    at += align_up((size_t)d.hidden * 2, 256);
+        r.b_up = at;   at += align_up((size_t)d.ffn * 2, 256);
+        r.b_down = at; at += align_up((size_t)d.hidden * 2, 256);
+    }
     r.bytes = at;
     return r;
 }
@@ -301,8 +313,11 @@ int fxp_stage_create(const fxp_stage_desc *desc, const fxp_layer_weights *layers
     const int H = d.hidden, D = d.head_dim, Nq = d.n_q_heads * D, Nkv = d.n_kv_heads * D, F = d.ffn;
     for (int l = 0; l < L; ++l) {
         const fxp_layer_weights &w = layers[l];
-        if (!w.g_attn || !w.wq || !w.wk || !w.wv || !w.wo || !w.g_ffn || !w.w_gate || !w.w_up || !w.w_down)
+        const bool opt = d.arch == FXP_ARCH_OPT;
+        if (!w.g_attn || !w.wq || !w.wk || !w.wv || !w.wo || !w.g_ffn || (!opt && !w.w_gate) || !w.w_up || !w.w_down)
             return fail(FXP_EINVAL, "layer %d has a null weight pointer", d.layer_begin + l);
+        if (opt && (w.w_gate || !w.b_attn_norm || !w.b_ffn_norm || !w.bq || !w.bk || !w.bv || !w.bo || !w.b_up || !w.b_down))
+            return fail(FXP_EINVAL, "layer %d: an OPT-style layer has no gate matrix and needs every bias", d.layer_begin + l);
         char *base = (char *)weight_arena + rec.bytes * (size_t)l;
         hipError_t e;
         // q | k | v rows concatenated
@@ -310,9 +325,19 @@ int fxp_stage_create(const fxp_stage_desc *desc, const fxp_layer_weights *layers
         if ((e = fxp::launch_weight_pack(w.wk, Nkv, H, base + rec.wqkv, k_steps(H), Nq / 16, 1, st))) return hip_fail(e, "pack wk");
         if ((e = fxp::launch_weight_pack(w.wv, Nkv, H, base + rec.wqkv, k_steps(H), (Nq + Nkv) / 16, 1, st))) return hip_fail(e, "pack wv");
         if ((e = fxp::launch_weight_pack(w.wo, H, Nq, base + rec.wo, k_steps(Nq), 0, 1, st))) return hip_fail(e, "pack wo");
-        // gate and up rows interleaved in 16-row tiles
-        if ((e = fxp::launch_weight_pack(w.w_gate, F, H, base + rec.wgu, k_steps(H), 0, 2, st))) return hip_fail(e, "pack w_gate");
-        if ((e = fxp::launch_weight_pack(w.w_up, F, H, base + rec.wgu, k_steps(H), 1, 2, st))) return hip_fail(e, "pack w_up");
+        if (opt) {
+            if ((e = fxp::launch_weight_pack(w.w_up, F, H, base + rec.wgu, k_steps(H), 0, 1, st))) return hip_fail(e, "pack w_up");
+            const struct { const void *src; size_t off, n; } vecs[] = {
+                {w.b_attn_norm, rec.b_attn, (size_t)H}, {w.b_ffn_norm, rec.b_ffn, (size_t)H}, {w.bq, rec.b_qkv, (size_t)Nq},
+                {w.bk, rec.b_qkv + (size_t)Nq * 2, (size_t)Nkv}, {w.bv, rec.b_qkv + (size_t)(Nq + Nkv) * 2, (size_t)Nkv},
+                {w.bo, rec.b_o, (size_t)H}, {w.b_up, rec.b_up, (size_t)F}, {w.b_down, rec.b_down, (size_t)H}};
+            for (const auto &v : vecs)
+                if ((e = hipMemcpyAsync(base + v.off, v.src, v.n * 2, hipMemcpyDeviceToDevice, st))) return hip_fail(e, "copy bias");
+        } else {
+            // gate and up rows interleaved in 16-row tiles
+            if ((e = fxp::launch_weight_pack(w.w_gate, F, H, base + rec.wgu, k_steps(H), 0, 2, st))) return hip_fail(e, "pack w_gate");
+            if ((e = fxp::launch_weight_pack(w.w_up, F, H, base + rec.wgu, k_steps(H), 1, 2, st))) return hip_fail(e, "pack w_up");
+        }
         if ((e = fxp::launch_weight_pack(w.w_down, H, F, base + rec.wd, k_steps(F), 0, 1, st))) return hip_fail(e, "pack w_down");
         if ((e = hipMemcpyAsync(base + rec.g_attn, w.g_attn, (size_t)H * 2, hipMemcpyDeviceToDevice, st))) return hip_fail(e, "copy g_attn");
         if ((e = hipMemcpyAsync(base + rec.g_ffn, w.g_ffn, (size_t)H * 2, hipMemcpyDeviceToDevice, st))) return hip_fail(e, "copy g_ffn");
@@ -360,7 +385,7 @@ int fxp_stage_merge(const fxp_stage *lower, const fxp_stage *upper, fxp_stage **
     const fxp_stage_desc &a = lower->d, &b = upper->d;
     if (a.layer_end != b.layer_begin) return fail(FXP_EINVAL, "stages [%d,%d) and [%d,%d) are not adjacent", a.layer_begin, a.layer_end, b.layer_begin, b.layer_end);
     if (a.hidden != b.hidden || a.n_q_heads != b.n_q_heads || a.n_kv_heads != b.n_kv_heads || a.head_dim != b.head_dim ||
-        a.ffn != b.ffn || a.rms_eps != b.rms_eps || a.rope_base != b.rope_base || a.kv_block_size != b.kv_block_size)
+        a.ffn != b.ffn || a.arch != b.arch || a.rms_eps != b.rms_eps || a.rope_base != b.rope_base || a.kv_block_size != b.kv_block_size)
         return fail(FXP_EINVAL, "stages differ in model geometry");
     if (upper->arena != lower->arena + lower->rec.bytes * (size_t)lower->n_layers)
         return fail(FXP_EINVAL, "the upper stage's layer records do not follow the lower stage's in memory; "
@@ -406,11 +431,15 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
     hipError_t e;
 
-    auto project_skinny = [&](const char *wbase, const uint16_t *X, int N, int K, int ldx, int *S_out, uint16_t *swiglu_out = nullptr) -> hipError_t {
+    const bool opt = d.arch == FXP_ARCH_OPT;
+    // act_out: the projection applies its activation itself (no split-K): SwiGLU over gate|up tiles, or
+    // relu(sum + act_bias) for an OPT-style feed-forward
+    auto project_skinny = [&](const char *wbase, const uint16_t *X, int N, int K, int ldx, int *S_out, uint16_t *act_out = nullptr,
+                              const uint16_t *act_bias = nullptr) -> hipError_t {
         if (T > kSkinnyWideTokens) {
             // 65..128 token rows: one 128-row tile of the tiled kernel covers the batch; split-K for parallelism
             fxp::TiledArgs t;
-            t.W = (const uint16_t *)wbase; t.X = X; t.R = nullptr; t.C = nullptr; t.P = w.P;
+            t.W = (const uint16_t *)wbase; t.X = X; t.R = nullptr; t.C = nullptr; t.P = w.P; t.bias = nullptr;
             t.M = T; t.K = K; t.KS = k_steps(K); t.NT = N / 16; t.ldx = ldx; t.ldc = 0; t.epilogue = fxp::kEpiPartial;
             t.S = skinny_cfg(N, K, T).S;
             *S_out = t.S;
@@ -418,17 +447,20 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
             return fxp::launch_gemm_tiled(t, st);
         }
         fxp::SkinnyArgs a;
-        a.W = (const uint16_t *)wbase; a.X = X; a.P = w.P; a.A = nullptr;
+        a.W = (const uint16_t *)wbase; a.X = X; a.P = w.P; a.A = nullptr; a.bias = nullptr; a.act = 0;
         a.M = T; a.N = N; a.K = K; a.KS = k_steps(K); a.NT = N / 16; a.ldx = ldx; a.S = skinny_cfg(N, K, T).S; a.R = skinny_cfg(N, K, T).R; a.U = env_int("FXP_SKINNY_U", 4);
-        if (swiglu_out) { a.A = swiglu_out; a.S = 1; a.R = 2; }     // SwiGLU in the epilogue: no split, gate and up tile in one wavefront
+        if (act_out) {       // activation in the epilogue: no split; for SwiGLU the gate and the up tile sit in one wavefront
+            a.A = act_out; a.S = 1; a.R = 2;
+            if (act_bias) { a.act = 1; a.bias = act_bias; }
+        }
         *S_out = a.S;
         KernelTimer kt(kKcSkinny, st);
         return fxp::launch_gemm_skinny(a, st);
     };
     auto project_tiled = [&](const char *wbase, const uint16_t *X, int N, int K, int ldx, uint16_t *C, int ldc,
-                             const uint16_t *R, int epi) -> hipError_t {
+                             const uint16_t *R, int epi, const uint16_t *bias = nullptr) -> hipError_t {
         fxp::TiledArgs a;
-        a.W = (const uint16_t *)wbase; a.X = X; a.R = R; a.C = C; a.P = nullptr; a.S = 1;
+        a.W = (const uint16_t *)wbase; a.X = X; a.R = R; a.C = C; a.P = nullptr; a.S = 1; a.bias = bias;
         a.M = T; a.K = K; a.KS = k_steps(K); a.NT = N / 16; a.ldx = ldx; a.ldc = ldc; a.epilogue = epi;
         KernelTimer kt(kKcTiled, st);
         return fxp::launch_gemm_tiled(a, st);
@@ -438,6 +470,7 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
         fxp::RopeTableArgs rt;
         rt.cu_seqlens_q = batch->cu_seqlens_q; rt.ctx_lens = batch->ctx_lens; rt.tok_seq = w.tok_seq; rt.tok_pos = w.tok_pos; rt.blk_prefix = w.blk_prefix;
         rt.cs = w.rope_cs; rt.sn = w.rope_sn; rt.T = T; rt.num_seqs = B; rt.head_dim = D; rt.rope_base = d.rope_base;
+        rt.identity = opt ? 1 : 0;
         KernelTimer kt(kKcRopeTable, st);
         if ((e = fxp::launch_rope_table(rt, st))) return hip_fail(e, "rope table");
     }
@@ -445,6 +478,9 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
     for (int ll = 0; ll < stage->n_layers; ++ll) {
         const char *rec = stage->arena + stage->rec.bytes * (size_t)ll;
         const uint16_t *g_attn = (const uint16_t *)(rec + stage->rec.g_attn), *g_ffn = (const uint16_t *)(rec + stage->rec.g_ffn);
+        auto vec = [&](size_t off) { return opt ? (const uint16_t *)(rec + off) : nullptr; };     // OPT-style biases, null otherwise
+        const uint16_t *b_attn = vec(stage->rec.b_attn), *b_ffn = vec(stage->rec.b_ffn), *b_qkv = vec(stage->rec.b_qkv);
+        const uint16_t *b_o = vec(stage->rec.b_o), *b_up = vec(stage->rec.b_up), *b_down = vec(stage->rec.b_down);
         const bool last = ll + 1 == stage->n_layers;
         uint16_t *x_next = last ? (uint16_t *)hidden_out : w.x[ll & 1];
         float *dbg = probs ? probs + (int64_t)ll * T * d.n_q_heads * probs_stride : nullptr;
@@ -453,17 +489,17 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
         // attention norm (layers after the first get it from the previous layer's fused epilogue on the skinny path)
         if (!skinny || ll == 0) {
             KernelTimer kt(kKcRmsnorm, st);
-            if ((e = fxp::launch_rmsnorm(x_cur, g_attn, w.n, T, H, d.rms_eps, st))) return hip_fail(e, "rmsnorm");
+            if ((e = fxp::launch_rmsnorm(x_cur, g_attn, b_attn, w.n, T, H, d.rms_eps, st))) return hip_fail(e, "rmsnorm");
         }
 
         // q|k|v projection, rotary embedding, cache append
         fxp::RopeArgs ra;
-        ra.P = nullptr; ra.qkv = nullptr; ra.S = 1;
+        ra.P = nullptr; ra.qkv = nullptr; ra.S = 1; ra.bias = nullptr;
         if (skinny) {
             if ((e = project_skinny(rec + stage->rec.wqkv, w.n, Nall, H, H, &S))) return hip_fail(e, "qkv projection");
-            ra.P = w.P; ra.S = S;
+            ra.P = w.P; ra.S = S; ra.bias = b_qkv;
         } else {
-            if ((e = project_tiled(rec + stage->rec.wqkv, w.n, Nall, H, H, w.qkv, Nall, nullptr, fxp::kEpiStore))) return hip_fail(e, "qkv projection");
+            if ((e = project_tiled(rec + stage->rec.wqkv, w.n, Nall, H, H, w.qkv, Nall, nullptr, fxp::kEpiStore, b_qkv))) return hip_fail(e, "qkv projection");
             ra.qkv = w.qkv;
         }
         ra.q_out = w.q; ra.pool = (uint16_t *)pool->base;
@@ -508,6 +544,7 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
             if ((e = project_skinny(rec + stage->rec.wo, w.o, H, Nq, Nq, &S))) return hip_fail(e, "output projection");
             fxp::ResidNormArgs rn;
             rn.x = x_cur; rn.P = w.P; rn.h = w.h; rn.g = g_ffn; rn.n = w.n; rn.T = T; rn.H = H; rn.S = S; rn.eps = d.rms_eps;
+            rn.bias = b_o; rn.nb = b_ffn;
             {
                 KernelTimer kt(kKcResidNorm, st);
                 if ((e = fxp::launch_resid_norm(rn, st))) return hip_fail(e, "residual + norm");
@@ -515,31 +552,38 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
             // gate|up projection + SwiGLU
             // (up to 64 rows the projection is wide enough to fill the chip without split-K and
             // applies SwiGLU itself; above, the split partial sums go through the SwiGLU kernel)
-            const bool fused_swiglu = T <= kSkinnyWideTokens && skinny_fused_swiglu(2 * F);
-            if ((e = project_skinny(rec + stage->rec.wgu, w.n, 2 * F, H, H, &S, fused_swiglu ? w.a : nullptr))) return hip_fail(e, "gate/up projection");
-            if (!fused_swiglu) {
+            // (an OPT-style layer has one matrix here and relu(sum + bias) as activation)
+            const int Nup = opt ? F : 2 * F;
+            const bool fused_act = T <= kSkinnyWideTokens && skinny_fused_swiglu(Nup);
+            if ((e = project_skinny(rec + stage->rec.wgu, w.n, Nup, H, H, &S, fused_act ? w.a : nullptr, b_up))) return hip_fail(e, "gate/up projection");
+            if (!fused_act) {
                 fxp::SwigluArgs sg;
-                sg.P = w.P; sg.out = w.a; sg.T = T; sg.F = F; sg.S = S; sg.ld_out = F;
+                sg.P = w.P; sg.out = w.a; sg.T = T; sg.F = F; sg.S = S; sg.ld_out = F; sg.bias = b_up; sg.act = opt ? 1 : 0;
                 KernelTimer kt(kKcSwiglu, st);
                 if ((e = fxp::launch_swiglu(sg, st))) return hip_fail(e, "swiglu");
             }
             // down projection + residual, fused with the next layer's attention norm
             if ((e = project_skinny(rec + stage->rec.wd, w.a, H, F, F, &S))) return hip_fail(e, "down projection");
-            rn.x = w.h; rn.P = w.P; rn.h = x_next; rn.S = S;
+            rn.x = w.h; rn.P = w.P; rn.h = x_next; rn.S = S; rn.bias = b_down;
             rn.g = last ? nullptr : (const uint16_t *)(rec + stage->rec.bytes + stage->rec.g_attn);
+            rn.nb = (last || !opt) ? nullptr : (const uint16_t *)(rec + stage->rec.bytes + stage->rec.b_attn);
             rn.n = w.n;
             {
                 KernelTimer kt(kKcResidNorm, st);
                 if ((e = fxp::launch_resid_norm(rn, st))) return hip_fail(e, "residual + norm");
             }
         } else {
-            if ((e = project_tiled(rec + stage->rec.wo, w.o, H, Nq, Nq, w.h, H, x_cur, fxp::kEpiResidual))) return hip_fail(e, "output projection");
+            if ((e = project_tiled(rec + stage->rec.wo, w.o, H, Nq, Nq, w.h, H, x_cur, fxp::kEpiResidual, b_o))) return hip_fail(e, "output projection");
             {
                 KernelTimer kt(kKcRmsnorm, st);
-                if ((e = fxp::launch_rmsnorm(w.h, g_ffn, w.n, T, H, d.rms_eps, st))) return hip_fail(e, "rmsnorm");
+                if ((e = fxp::launch_rmsnorm(w.h, g_ffn, b_ffn, w.n, T, H, d.rms_eps, st))) return hip_fail(e, "rmsnorm");
             }
-            if ((e = project_tiled(rec + stage->rec.wgu, w.n, 2 * F, H, H, w.a, F, nullptr, fxp::kEpiSwiglu))) return hip_fail(e, "gate/up projection");
-            if ((e = project_tiled(rec + stage->rec.wd, w.a, H, F, F, x_next, H, w.h, fxp::kEpiResidual))) return hip_fail(e, "down projection");
+            if (opt) {
+                if ((e = project_tiled(rec + stage->rec.wgu, w.n, F, H, H, w.a, F, nullptr, fxp::kEpiRelu, b_up))) return hip_fail(e, "first feed-forward projection");
+            } else {
+                if ((e = project_tiled(rec + stage->rec.wgu, w.n, 2 * F, H, H, w.a, F, nullptr, fxp::kEpiSwiglu))) return hip_fail(e, "gate/up projection");
+            }
+            if ((e = project_tiled(rec + stage->rec.wd, w.a, H, F, F, x_next, H, w.h, fxp::kEpiResidual, b_down))) return hip_fail(e, "down projection");
         }
         x_cur = x_next;
     }

@@ -135,6 +135,26 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(SkinnyArgs a)
     // accumulator layout of the 16x16 MFMA: lane l, element v holds D[row 4*(l/16)+v][col l%16]
     // with rows = weight rows n and columns = token rows m: four consecutive n per lane.
     const int mrow = lane & 15;
+    if (a.A && a.act == 1) {
+        // unsplit projection with relu(sum + bias) in the epilogue
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            if (nt0 + r >= a.NT) continue;
+            const int n = (nt0 + r) * 16 + 4 * (lane >> 4);
+            const u32x2 bv = *reinterpret_cast<const u32x2 *>(a.bias + n);
+            const float bb[4] = {bf16_lo(bv.x), bf16_hi(bv.x), bf16_lo(bv.y), bf16_hi(bv.y)};
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                const int m = mt * 16 + mrow;
+                float y[4];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) y[v] = fmaxf(acc[r][mt][v] + bb[v], 0.f);
+                if (m < a.M)
+                    *reinterpret_cast<u32x2 *>(a.A + (int64_t)m * a.N + n) = u32x2{pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3])};
+            }
+        }
+        return;
+    }
     if constexpr (R % 2 == 0) {
         if (a.A) {
             // gate|up projection without split-K: tiles alternate gate rows / up rows of the same 16

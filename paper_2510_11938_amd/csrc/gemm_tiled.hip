@@ -238,6 +238,14 @@ __global__ __launch_bounds__(kTgThreads, 2) void gemm_tiled_kernel(TiledArgs a)
                 if (nt0 + r >= a.NT) continue;
                 const int n = (nt0 + r) * 16 + 4 * c;
                 float y[4] = {acc[r][mt][0], acc[r][mt][1], acc[r][mt][2], acc[r][mt][3]};
+                if (a.bias) {
+                    const u32x2 bv = *reinterpret_cast<const u32x2 *>(a.bias + n);
+                    y[0] += bf16_lo(bv.x); y[1] += bf16_hi(bv.x); y[2] += bf16_lo(bv.y); y[3] += bf16_hi(bv.y);
+                }
+                if constexpr (EPI == kEpiRelu) {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) y[v] = fmaxf(y[v], 0.f);
+                }
                 if constexpr (EPI == kEpiResidual) {
                     const u32x2 rv = *reinterpret_cast<const u32x2 *>(a.R + (int64_t)m * a.ldc + n);
                     y[0] += bf16_lo(rv.x); y[1] += bf16_hi(rv.x); y[2] += bf16_lo(rv.y); y[3] += bf16_hi(rv.y);
@@ -264,6 +272,7 @@ hipError_t launch_gemm_tiled(const TiledArgs &a, hipStream_t stream)
     case kEpiResidual: FXP_TG_LAUNCH(kEpiResidual) break;
     case kEpiSwiglu: FXP_TG_LAUNCH(kEpiSwiglu) break;
     case kEpiPartial: FXP_TG_LAUNCH(kEpiPartial) break;
+    case kEpiRelu: FXP_TG_LAUNCH(kEpiRelu) break;
     default: return hipErrorInvalidValue;
     }
 #undef FXP_TG_LAUNCH

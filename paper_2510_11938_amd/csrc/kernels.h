@@ -46,33 +46,40 @@ struct SkinnyArgs {
     const uint16_t *W;     // packed weights
     const uint16_t *X;     // token rows [M][ldx] bf16
     float *P;              // partial sums [S][M][N]
-    uint16_t *A;           // optional SwiGLU output [M][N/2] bf16 (gate|up weights, S == 1, even R): replaces P
+    uint16_t *A;           // optional activation output, replaces P (S == 1): act 0 = SwiGLU over interleaved gate|up
+                           // tiles -> [M][N/2] (even R); act 1 = relu(sum + bias) -> [M][N]
+    const uint16_t *bias;  // act 1: bias [N] bf16
+    int act;
     int M, N, K, KS, NT, ldx, S;   // KS = padded K / 32, NT = N / 16
     int R;                         // 16-row weight tiles per wavefront: 1, 2 or 4
     int U;                         // k-steps per prefetch group: 4 or 8 (8 only for R <= 2, M <= 32)
 };
 hipError_t launch_gemm_skinny(const SkinnyArgs &a, hipStream_t stream);
 
-enum { kEpiStore = 0, kEpiResidual = 1, kEpiSwiglu = 2, kEpiPartial = 3 };
+enum { kEpiStore = 0, kEpiResidual = 1, kEpiSwiglu = 2, kEpiPartial = 3, kEpiRelu = 4 };
 struct TiledArgs {
     const uint16_t *W;     // packed weights
     const uint16_t *X;     // token rows [M][ldx] bf16
     const uint16_t *R;     // residual [M][ldc] (kEpiResidual), may alias C
     uint16_t *C;           // output [M][ldc] bf16
     float *P;              // kEpiPartial: float partial sums [S][M][NT*16]
+    const uint16_t *bias;  // optional bias [NT*16] bf16, added before the residual / activation (not for kEpiPartial, kEpiSwiglu)
     int M, K, KS, NT, ldx, ldc, epilogue;
     int S;                 // kEpiPartial: split-K factor (grid.y)
 };
 hipError_t launch_gemm_tiled(const TiledArgs &a, hipStream_t stream);
 
 // ---------------------------------------------------------------- row-wise kernels
-hipError_t launch_rmsnorm(const void *x, const void *g, void *out, int T, int H, float eps, hipStream_t stream);
+// b == nullptr: RMSNorm, n = x * rsqrt(mean(x^2) + eps) * g;  else LayerNorm, n = (x - mean) * rsqrt(var + eps) * g + b
+hipError_t launch_rmsnorm(const void *x, const void *g, const void *b, void *out, int T, int H, float eps, hipStream_t stream);
 
 struct ResidNormArgs {
     const uint16_t *x;     // residual input [T][H]
     const float *P;        // projection partial sums [S][T][H]
     uint16_t *h;           // x + proj, bf16 [T][H] (may alias x)
+    const uint16_t *bias;  // bias of the projection [H], or nullptr
     const uint16_t *g;     // gain of the following norm, or nullptr
+    const uint16_t *nb;    // bias of the following norm: LayerNorm when set, RMSNorm when nullptr
     uint16_t *n;           // normed output [T][H] (when g)
     int T, H, S;
     float eps;
@@ -80,9 +87,11 @@ struct ResidNormArgs {
 hipError_t launch_resid_norm(const ResidNormArgs &a, hipStream_t stream);
 
 struct SwigluArgs {
-    const float *P;        // gate|up partial sums [S][T][2F], rows interleaved in 16-tiles
+    const float *P;        // act 0: gate|up partial sums [S][T][2F], rows interleaved in 16-tiles; act 1: [S][T][F]
     uint16_t *out;         // [T][ld_out] bf16
+    const uint16_t *bias;  // act 1: bias [F] bf16
     int T, F, S, ld_out;
+    int act;               // 0: silu(gate) * up;  1: relu(sum + bias)
 };
 hipError_t launch_swiglu(const SwigluArgs &a, hipStream_t stream);
 
@@ -93,12 +102,14 @@ struct RopeTableArgs {
     float *cs, *sn;               // [T][D/2]
     int T, num_seqs, head_dim;
     float rope_base;
+    int identity;                 // 1: no rotary embedding (cos = 1, sin = 0)
 };
 hipError_t launch_rope_table(const RopeTableArgs &a, hipStream_t stream);
 
 struct RopeArgs {
     const float *P;        // q|k|v partial sums [S][T][Nall], or nullptr
     const uint16_t *qkv;   // q|k|v bf16 [T][Nall] (when P == nullptr)
+    const uint16_t *bias;  // optional q|k|v bias [Nall] bf16, added to the partial sums (P != nullptr only)
     uint16_t *q_out;       // rotated q [T][Hq*D] bf16
     uint16_t *pool;        // stage KV pool
     const int32_t *tok_seq, *tok_pos;   // from the rope table

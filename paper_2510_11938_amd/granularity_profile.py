@@ -34,9 +34,14 @@ def measure_stage_ms(ms: synth.ModelShape, depth: int, batch: int, ctx: np.ndarr
         return (torch.randn(*shape, device=dev, generator=g) * scale).to(torch.bfloat16)
 
     H, D, F = ms.hidden, ms.head_dim, ms.ffn
-    layers = [dict(g_attn=1 + rnd(H), wq=rnd(ms.n_q_heads * D, H), wk=rnd(ms.n_kv_heads * D, H), wv=rnd(ms.n_kv_heads * D, H),
-                   wo=rnd(H, ms.n_q_heads * D), g_ffn=1 + rnd(H), w_gate=rnd(F, H), w_up=rnd(F, H), w_down=rnd(H, F))
-              for _ in range(depth)]
+    Nq, Nkv = ms.n_q_heads * D, ms.n_kv_heads * D
+    if ms.arch == binding.ARCH_OPT:
+        layers = [dict(ln1_g=1 + rnd(H), ln1_b=rnd(H), wq=rnd(Nq, H), bq=rnd(Nq), wk=rnd(Nkv, H), bk=rnd(Nkv), wv=rnd(Nkv, H),
+                       bv=rnd(Nkv), wo=rnd(H, Nq), bo=rnd(H), ln2_g=1 + rnd(H), ln2_b=rnd(H), w_fc1=rnd(F, H), b_fc1=rnd(F),
+                       w_fc2=rnd(H, F), b_fc2=rnd(H)) for _ in range(depth)]
+    else:
+        layers = [dict(g_attn=1 + rnd(H), wq=rnd(Nq, H), wk=rnd(Nkv, H), wv=rnd(Nkv, H), wo=rnd(H, Nq), g_ffn=1 + rnd(H),
+                       w_gate=rnd(F, H), w_up=rnd(F, H), w_down=rnd(H, F)) for _ in range(depth)]
     stage = binding.Stage(ms, 0, depth, layers)
     torch.cuda.synchronize()
     del layers
@@ -62,7 +67,9 @@ def measure_stage_ms(ms: synth.ModelShape, depth: int, batch: int, ctx: np.ndarr
 
 def main(argv=None) -> int:
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("--layers-total", type=int, default=32)
+    ap.add_argument("--model", default="7b", choices=["7b", "opt66b"],
+                    help="7b: Llama-style 7B shape (32 layers); opt66b: OPT-66B shape (64 layers), the model of the paper's Table 2")
+    ap.add_argument("--layers-total", type=int, default=0, help="layers of the whole model (default: the model's own)")
     ap.add_argument("--depths", default="1,2,4,8", help="layers per stage to measure")
     ap.add_argument("--batch", type=int, default=32)
     ap.add_argument("--ctx", default="512,4096", help="uniform context length range")
@@ -73,7 +80,9 @@ def main(argv=None) -> int:
     ap.add_argument("--sigma", type=float, default=1.0)
     ap.add_argument("--cvs", default="0.25,1,2,4", help="traffic CVs to score")
     args = ap.parse_args(argv)
-    ms = synth.LLAMA2_7B
+    ms = synth.OPT_66B if args.model == "opt66b" else synth.LLAMA2_7B
+    if args.layers_total <= 0:
+        args.layers_total = 64 if args.model == "opt66b" else 32
     lo, hi = (int(v) for v in args.ctx.split(","))
     ctx = synth.draw_lengths(("uniform", lo, hi), args.batch, seed=1)
     handoff_ms = (args.batch * ms.hidden * 2 / (args.link_gbps * 1e9) + args.link_latency_us * 1e-6) * 1e3
@@ -98,7 +107,7 @@ def main(argv=None) -> int:
     for cv in cvs:
         best, scores = binding.ctl_select_granularity(cands, cv, args.alpha, args.sigma)
         picks.append({"cv": cv, "selected_n_stages": cands[best].n_stages, "scores": scores})
-    print(json.dumps({"model": "7B shape", "batch": args.batch, "ctx_range": [lo, hi], "stages": rows,
+    print(json.dumps({"model": args.model, "batch": args.batch, "ctx_range": [lo, hi], "stages": rows,
                       "cv_opt": [c.cv_opt for c in cands], "alpha": args.alpha, "sigma": args.sigma, "picks": picks}))
     return 0
 

@@ -66,7 +66,8 @@ class Weights:
 
 
 def make_weights(ms: synth.ModelShape, seed: int, n_layers: int, want_f32: bool = True, want_dev: bool = True) -> Weights:
-    bits = [synth.layer_weights(ms, seed, l) for l in range(n_layers)]
+    gen = synth.opt_layer_weights if ms.arch == 1 else synth.layer_weights
+    bits = [gen(ms, seed, l) for l in range(n_layers)]
     f32 = [{k: synth.bf16_bits_to_f32(v) for k, v in lw.items()} for lw in bits] if want_f32 else []
     dev = [{k: dev_bf16(v) for k, v in lw.items()} for lw in bits] if want_dev else []
     return Weights(bits, f32, dev)
@@ -88,6 +89,11 @@ def filled_pool_bits(ms: synth.ModelShape, seed: int, n_layers: int, ctx_lens: n
     with ThreadPoolExecutor(max_workers=threads) as ex:
         list(ex.map(one, todo))
     return pool
+
+
+def oracle_forward(ms: synth.ModelShape):
+    """The oracle's stage function for the model's layer kind."""
+    return oracle.stage_forward_opt if ms.arch == 1 else oracle.stage_forward
 
 
 def pool_f32(bits: np.ndarray) -> np.ndarray:

@@ -14,7 +14,7 @@ import oracle
 from oracle import KVView
 from paper_2510_11938_amd import binding, synth
 
-from gpu_util import (check_wide_output, dev_bf16, dev_i32, filled_pool_bits, host_bits, host_f64, make_stage, make_weights,
+from gpu_util import (check_wide_output, oracle_forward, dev_bf16, dev_i32, filled_pool_bits, host_bits, host_f64, make_stage, make_weights,
                       oracle_shape, pool_f32, rel_err)
 
 pytestmark = pytest.mark.gpu
@@ -26,6 +26,9 @@ TINY = synth.TINY
 GQA64 = synth.ModelShape(hidden=512, n_q_heads=8, n_kv_heads=2, head_dim=64, ffn=1376)
 MID128 = synth.ModelShape(hidden=512, n_q_heads=4, n_kv_heads=4, head_dim=128, ffn=1024)
 GQA128 = synth.ModelShape(hidden=1024, n_q_heads=8, n_kv_heads=1, head_dim=128, ffn=1536)
+OPT_TINY = synth.TINY_OPT                                                                    # OPT-style layers (LayerNorm, biases, ReLU)
+OPT_GQA = synth.ModelShape(hidden=512, n_q_heads=8, n_kv_heads=2, head_dim=128, ffn=2048, arch=1)
+OPT_WIDE = synth.ModelShape(hidden=256, n_q_heads=4, n_kv_heads=4, head_dim=64, ffn=16400, arch=1)    # unsplit first projection with ReLU in its epilogue
 WIDE_FFN = synth.ModelShape(hidden=256, n_q_heads=4, n_kv_heads=4, head_dim=64, ffn=8208)   # gate|up wide enough for the unsplit, SwiGLU-fused projection
 
 
@@ -50,8 +53,8 @@ class Case:
         le = self.L if le is None else le
         pool = pool_f32(self.pool_bits[lb:le]) if pool is None else pool
         x = synth.bf16_bits_to_f32(self.hidden_bits).astype(np.float64) if hidden is None else hidden
-        out = oracle.stage_forward(self.osh, self.w.f32[lb:le], pool, self.cu, self.ctx, self.table, x,
-                                   probs_stride=probs_stride)
+        out = oracle_forward(self.ms)(self.osh, self.w.f32[lb:le], pool, self.cu, self.ctx, self.table, x,
+                                      probs_stride=probs_stride)
         return out, pool
 
     def gpu_cache(self, lb=0, le=None, table=None, pool_bits=None):
@@ -89,6 +92,11 @@ DECODE_CASES = [
     ("wide-ffn", WIDE_FFN, 2, [33, 200, 64, 7, 150]),             # SwiGLU in the projection epilogue, ragged last tile pair
     ("wide-ffn-40", WIDE_FFN, 1, list(range(5, 45))),
     ("batch-40", TINY, 1, list(range(5, 45))),                     # 3 row tiles, ragged
+    ("opt-tiny", OPT_TINY, 2, [37, 128, 32, 100]),
+    ("opt-gqa", OPT_GQA, 2, [300, 1025, 31, 7, 64]),
+    ("opt-wide-ffn", OPT_WIDE, 2, [33, 200, 64, 7, 150]),
+    ("opt-batch-100", OPT_TINY, 1, [17 + (i * 7) % 90 for i in range(100)]),   # 65..128 rows: split partial sums through the tiled kernel
+    ("opt-batch-150", OPT_TINY, 2, [9 + (i * 11) % 120 for i in range(150)]),  # tiled projections with bias / ReLU epilogues
     ("batch-100", TINY, 1, [17 + (i * 7) % 90 for i in range(100)]),   # 7 row tiles
     ("batch-150", TINY, 2, [9 + (i * 11) % 120 for i in range(150)]),  # above 128 rows: tiled projections feed the decode attention
 ]
@@ -110,6 +118,9 @@ PREFILL_CASES = [
     ("gqa64-prompts", GQA64, 1, [0, 5, 100], [130, 64, 17]),
     ("mid128-prompts", MID128, 2, [0, 129, 0], [200, 3, 65]),
     ("gqa128-8", GQA128, 1, [0, 40], [100, 90]),
+    ("opt-prompts", OPT_TINY, 2, [0, 0, 0, 0], [37, 128, 32, 100]),
+    ("opt-small", OPT_TINY, 2, [0, 0], [20, 45]),
+    ("opt-chunked", OPT_GQA, 1, [16, 70, 33], [48, 10, 64]),
 ]
 
 
@@ -163,10 +174,11 @@ def test_attention_probabilities_within_1e3(kind):
             t += 1
 
 
+@pytest.mark.parametrize("ms", [TINY, OPT_TINY], ids=["llama", "opt"])
 @pytest.mark.parametrize("kind", ["decode", "prefill", "prefill-skinny"])
-def test_split_stages_compose_to_unsplit_stage_bit_exact_on_gpu(kind):
+def test_split_stages_compose_to_unsplit_stage_bit_exact_on_gpu(kind, ms):
     # Eq. 2 constraints: stages are a disjoint cover, so [0,1) then [1,2) must equal [0,2) exactly
-    ms, L = TINY, 2
+    L = 2
     if kind == "decode":
         case = Case(ms, L, [37, 128, 32, 100], [1] * 4, seed=14)
     elif kind == "prefill":
