@@ -130,6 +130,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="C2", help="synthetic workload id (C2 is the headline configuration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-incremental", action="store_true",
+                    help="skip the concurrent-snapshot / delta-pass leg (keeps a kernel trace free of deliberately overlapped kernels)")
     ap.add_argument("--cpu-sample-seqs", type=int, default=0, help="sequences the oracle is timed on (0 = the whole batch)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -242,39 +244,41 @@ def main() -> int:
     # (a) the snapshot pass on a second stream while decode steps run on the first: both are
     #     HBM-bound, so each slows the other; (b) a delta pass over the last 16 tokens of every
     #     sequence, the work left after 16 decode steps went by during the snapshot.
-    side = torch.cuda.Stream()
-    reps_o = 8
-    steps_o = max(1, int(round(reps_o * move_ms / ms_per_step)))      # about the same time alone
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
-    torch.cuda.synchronize()
-    with torch.cuda.stream(side):
-        ev[0].record()
-        for _ in range(reps_o):
-            binding.kv_repartition(ms, [cache], dst, cl)
-        ev[1].record()
-    ev[2].record()
-    for _ in range(steps_o):
-        step()
-    ev[3].record()
-    torch.cuda.synchronize()
-    move_ms_o = ev[0].elapsed_time(ev[1]) / reps_o
-    step_ms_o = ev[2].elapsed_time(ev[3]) / steps_o
-    delta_from = torch.clamp(cl - 16, min=0)
-    for _ in range(3):
-        binding.kv_repartition_range(ms, [cache], dst, delta_from, cl)
-    torch.cuda.synchronize()
-    ev0.record()
-    for _ in range(20):
-        binding.kv_repartition_range(ms, [cache], dst, delta_from, cl)
-    ev1.record()
-    torch.cuda.synchronize()
-    delta_us = ev0.elapsed_time(ev1) / 20 * 1e3
-    delta_bytes = 2 * int(np.minimum(ctx, 16).sum()) * L * kv_bytes_per_token
-    incremental = {"snapshot_pass_concurrent_with_decode": {
-                       "repartition_ms": move_ms_o, "repartition_GBps": move_bytes / (move_ms_o * 1e-3) / 1e9,
-                       "decode_ms_per_step": step_ms_o, "decode_steps": steps_o, "repartitions": reps_o,
-                       "hbm_GBps_both": (move_bytes / move_ms_o + (L * weight_bytes_layer + L * attn_bytes) / step_ms_o) / 1e6},
-                   "delta_pass_last_16_tokens": {"us": delta_us, "bytes_read_plus_written": delta_bytes}}
+    incremental = None
+    if not args.no_incremental:
+        side = torch.cuda.Stream()
+        reps_o = 8
+        steps_o = max(1, int(round(reps_o * move_ms / ms_per_step)))      # about the same time alone
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            ev[0].record()
+            for _ in range(reps_o):
+                binding.kv_repartition(ms, [cache], dst, cl)
+            ev[1].record()
+        ev[2].record()
+        for _ in range(steps_o):
+            step()
+        ev[3].record()
+        torch.cuda.synchronize()
+        move_ms_o = ev[0].elapsed_time(ev[1]) / reps_o
+        step_ms_o = ev[2].elapsed_time(ev[3]) / steps_o
+        delta_from = torch.clamp(cl - 16, min=0)
+        for _ in range(3):
+            binding.kv_repartition_range(ms, [cache], dst, delta_from, cl)
+        torch.cuda.synchronize()
+        ev0.record()
+        for _ in range(20):
+            binding.kv_repartition_range(ms, [cache], dst, delta_from, cl)
+        ev1.record()
+        torch.cuda.synchronize()
+        delta_us = ev0.elapsed_time(ev1) / 20 * 1e3
+        delta_bytes = 2 * int(np.minimum(ctx, 16).sum()) * L * kv_bytes_per_token
+        incremental = {"snapshot_pass_concurrent_with_decode": {
+                           "repartition_ms": move_ms_o, "repartition_GBps": move_bytes / (move_ms_o * 1e-3) / 1e9,
+                           "decode_ms_per_step": step_ms_o, "decode_steps": steps_o, "repartitions": reps_o,
+                           "hbm_GBps_both": (move_bytes / move_ms_o + (L * weight_bytes_layer + L * attn_bytes) / step_ms_o) / 1e6},
+                       "delta_pass_last_16_tokens": {"us": delta_us, "bytes_read_plus_written": delta_bytes}}
 
     out = {
         "metric": "stage decode tokens/s (7B shape, 4 layers, B=32); KV repartition GB/s vs HBM",
