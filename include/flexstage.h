@@ -39,6 +39,10 @@ extern "C" {
 #define FXP_ENOSPC  (-2)   /* workspace, weight arena or packed buffer too small           */
 #define FXP_EHIP    (-3)   /* a HIP call or kernel launch failed                           */
 
+/* Sequences per call (batch of a forward step, sequence list of a repartition): the
+ * kernels keep per-sequence prefix sums in LDS.  More than this is FXP_EINVAL. */
+#define FXP_MAX_SEQS 4096
+
 typedef struct fxp_stage fxp_stage;           /* opaque, library-owned host object */
 
 /* A stage is a contiguous subset of the model's layers (Section 5: each stage

@@ -411,6 +411,7 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
     const fxp_stage_desc &d = stage->d;
     const int T = batch->num_tokens, B = batch->num_seqs;
     if (T < 0 || B < 0) return fail(FXP_EINVAL, "negative batch size");
+    if (B > FXP_MAX_SEQS) return fail(FXP_EINVAL, "num_seqs %d above the limit of %d", B, FXP_MAX_SEQS);
     if (T == 0 || B == 0) return FXP_OK;
     if (!hidden_in || !hidden_out || !workspace) return fail(FXP_EINVAL, "null buffer passed to fxp_stage_forward");
     if (!batch->cu_seqlens_q || !batch->ctx_lens || !batch->block_table) return fail(FXP_EINVAL, "null batch table");
@@ -669,7 +670,7 @@ static int repartition_impl(const fxp_stage_desc *desc, const fxp_kv_view *src, 
 {
     if (int rc = check_kv_geom(desc)) return rc;
     if (!src || !dst || n_src <= 0 || n_dst <= 0) return fail(FXP_EINVAL, "empty view list");
-    if (num_seqs < 0 || num_seqs > 16383) return fail(FXP_EINVAL, "num_seqs %d out of range [0,16383]", num_seqs);
+    if (num_seqs < 0 || num_seqs > FXP_MAX_SEQS) return fail(FXP_EINVAL, "num_seqs %d out of range [0,%d]", num_seqs, FXP_MAX_SEQS);
     if (int rc = check_tiling(src, n_src, "source")) return rc;
     if (int rc = check_tiling(dst, n_dst, "destination")) return rc;
     if (src[0].pool->layer_begin != dst[0].pool->layer_begin || src[n_src - 1].pool->layer_end != dst[n_dst - 1].pool->layer_end)
@@ -741,7 +742,7 @@ static int pack_or_unpack(const fxp_stage_desc *desc, const fxp_kv_view *view, i
     if (int rc = check_view(view, to_packed ? "source" : "destination", 0)) return rc;
     if (lb < view->pool->layer_begin || le > view->pool->layer_end || lb >= le)
         return fail(FXP_EINVAL, "layers [%d,%d) are not inside the pool's [%d,%d)", lb, le, view->pool->layer_begin, view->pool->layer_end);
-    if (num_seqs < 0 || num_seqs > 16383) return fail(FXP_EINVAL, "num_seqs %d out of range [0,16383]", num_seqs);
+    if (num_seqs < 0 || num_seqs > FXP_MAX_SEQS) return fail(FXP_EINVAL, "num_seqs %d out of range [0,%d]", num_seqs, FXP_MAX_SEQS);
     if (num_seqs == 0) return FXP_OK;
     if (!ctx_lens || !packed || (token_dense && !from_lens)) return fail(FXP_EINVAL, "null buffer");
     const int64_t unit = 2ll * desc->n_kv_heads * 16 * desc->head_dim * 2;

@@ -81,3 +81,16 @@ def test_split_and_merge_reject_null_handles_without_touching_the_gpu():
     lo, hi = C.c_int32(), C.c_int32()
     assert l.fxp_stage_layers(None, C.byref(lo), C.byref(hi)) == binding.FXP_EINVAL
     assert b"null" in l.fxp_last_error()
+
+
+def test_sequence_count_limit_is_checked_on_the_host():
+    """FXP_MAX_SEQS (the per-sequence prefix sums live in LDS): one more is rejected before any launch."""
+    import ctypes as C
+    l = binding.lib()
+    desc = binding.make_desc(synth.TINY, 0, 1)
+    pool = binding.KvPool(0x1000, 4, 0, 1)
+    view = binding.KvView(C.pointer(pool), 0x2000, 4)
+    pool2 = binding.KvPool(0x100000, 4, 0, 1)
+    view2 = binding.KvView(C.pointer(pool2), 0x3000, 4)
+    rc = l.fxp_kv_repartition(C.byref(desc), C.byref(view), 1, C.byref(view2), 1, 0x4000, 4097, None)
+    assert rc == binding.FXP_EINVAL and b"4096" in l.fxp_last_error()

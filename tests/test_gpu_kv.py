@@ -279,3 +279,20 @@ def test_token_dense_pack_never_writes_past_a_short_buffer():
     got = host_bits(packed)
     assert np.array_equal(got[:short], want[:short])               # what fits is right
     assert np.all(got[short:] == 0x5555)                           # nothing beyond the size given
+
+
+def test_repartition_with_the_maximum_number_of_sequences():
+    """FXP_MAX_SEQS sequences (the per-workgroup prefix scans at their largest), many of them empty."""
+    ms = geom(2, 8)
+    rng = np.random.default_rng(31)
+    lens = rng.integers(0, 40, size=4096).astype(np.int32)
+    lens[rng.integers(0, 4096, size=500)] = 0
+    hs, ds = make_views(ms, [(0, 2)], lens, seed=32)
+    hd, dd = make_views(ms, [(0, 1), (1, 2)], lens, seed=33)
+    oracle.kv_repartition(oracle_shape(ms), hs, hd, lens)
+    binding.kv_repartition(ms, ds, dd, dev_i32(lens))
+    torch.cuda.synchronize()
+    for h, g in zip(hd, dd):
+        assert np.array_equal(host_bits(g.pool), h.pool)
+    with pytest.raises(binding.FxpError):
+        binding.kv_repartition(ms, ds, dd, dev_i32(np.zeros(4097, dtype=np.int32)))

@@ -250,6 +250,16 @@ def test_stage_split_and_merge_on_handles_share_the_arena_and_change_no_arithmet
         lo.merge(make_stage(MID128, make_weights(MID128, 3, 2), 1, 2))                # other geometry
 
 
+@pytest.mark.parametrize("ms", [TINY, GQA64], ids=["mha", "gqa"])
+def test_decode_with_the_maximum_number_of_sequences(ms):
+    """FXP_MAX_SEQS one-token sequences in a step (largest block-prefix table in the attention kernels)."""
+    ctx = [(i * 37) % 50 for i in range(4096)]                                # includes empty contexts
+    case = Case(ms, 1, ctx, [1] * 4096, seed=23)
+    want, opool = case.oracle_run()
+    got, cache = case.gpu_run()
+    assert rel_err(host_f64(got), want) <= TOL_OUT
+
+
 def test_bit_exact_under_block_permutation_and_run_to_run():
     ms, L = GQA64, 2
     ctx = [700, 16, 1, 513, 90]
