@@ -2,11 +2,12 @@
 // rows, so each is one pass, 16-byte vectors, one workgroup per token row, and
 // each also performs the fixed-order reduction of the split-K partial sums when
 // it follows a skinny projection (so no separate reduce launch exists):
-//   rmsnorm            n = x * rsqrt(mean(x^2) + eps) * g
-//   qkv_rope_kvwrite   rotary embedding of q and k at the token's position,
+//   rmsnorm            n = x * rsqrt(mean(x^2) + eps) * g, or with a norm bias the
+//                      LayerNorm n = (x - mean) * rsqrt(var + eps) * g + b
+//   qkv_rope_kvwrite   (+ bias,) rotary embedding of q and k at the token's position,
 //                      q -> bf16 buffer, rotated k and raw v -> paged cache
-//   resid_norm         h = x + proj ; optionally n = rmsnorm(h) for the next block
-//   swiglu             a = silu(gate) * up
+//   resid_norm         h = x + proj (+ bias); optionally n = norm(h) for the next block
+//   swiglu             a = silu(gate) * up, or relu(sum + bias) for an OPT-style layer
 // Sums are float; every value that leaves a kernel is rounded once to bf16.
 #include "kernels.h"
 #include "common.hip.h"

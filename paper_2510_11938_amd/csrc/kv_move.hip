@@ -17,8 +17,7 @@
 // per-sequence block prefix sums itself (LDS scan over ctx_lens) and then walks
 // a grid-strided list of equal-sized 32 KiB work items: no empty workgroups for
 // short sequences, no host synchronisation, no scratch memory.  Every lane
-// moves 16-byte vectors; a workgroup has four independent 4 KiB loads in flight
-// per lane-row before the first store.
+// moves 16-byte vectors, eight loads in flight before the first store.
 #include "kernels.h"
 #include "common.hip.h"
 
