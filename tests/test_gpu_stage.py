@@ -350,3 +350,39 @@ def test_full_size_7b_decode_sampled_against_oracle():
         want = oracle.stage_forward(osh, wf, sub_pool, [0, 1], [ctx[i]], sub_table,
                                     synth.bf16_bits_to_f32(hidden_bits[i:i + 1]).astype(np.float64))
         check_wide_output(got[i:i + 1], want, f"sequence {i} ctx {ctx[i]}:")
+
+
+def test_tiny_decode_step_and_merge_against_the_stored_oracle_values():
+    """The HIP path against the fixture under tests/golden/ (written by the oracle alone): the same C1 inputs,
+    outputs within the stage tolerance of the stored values, merged cache bit-identical (sha256)."""
+    import hashlib
+    import importlib.util
+    import os
+    here = os.path.dirname(os.path.abspath(__file__))
+    spec = importlib.util.spec_from_file_location("make_golden", os.path.join(here, "golden", "make_golden.py"))
+    mk = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mk)
+    ms, ctx, w_bits, x_bits, views, (t2, n2) = mk.tiny_inputs()
+    dev_w = [{k: dev_bf16(v) for k, v in lw.items()} for lw in w_bits]
+    caches = [binding.KVCache(torch.from_numpy(views[l][0].view(np.int16)).cuda(), l, l + 1, dev_i32(views[l][1])) for l in range(2)]
+    merged = binding.KVCache(torch.full((2, n2, 2, ms.n_kv_heads, 16, ms.head_dim), 0xABCD - 65536, dtype=torch.int16, device="cuda"),
+                             0, 2, dev_i32(t2))
+    cl = dev_i32(ctx)
+    binding.kv_repartition(ms, caches, [merged], cl)
+    cu = dev_i32(np.arange(len(ctx) + 1))
+    mid = binding.Stage(ms, 0, 1, dev_w[:1]).forward(caches[0], cu, cl, dev_bf16(x_bits), 1)
+    out = host_f64(binding.Stage(ms, 1, 2, dev_w[1:]).forward(caches[1], cu, cl, mid, 1))
+    torch.cuda.synchronize()
+    rms, vals, sha = {}, [], None
+    for line in open(os.path.join(here, "golden", "c1_decode_and_merge.txt")):
+        key, *v = line.split()
+        if key == "row_rms":
+            rms[int(v[0])] = float(v[1])
+        elif key == "hidden_out":
+            vals.append((int(v[0]), int(v[1]), float(v[2])))
+        elif key == "merged_pool_sha256":
+            sha = v[0]
+    assert len(vals) == 4 * 7 and sha
+    for i, k, want in vals:
+        assert abs(out[i, k] - want) / max(abs(want), rms[i]) <= TOL_OUT
+    assert hashlib.sha256(host_bits(merged.pool).tobytes()).hexdigest() == sha
