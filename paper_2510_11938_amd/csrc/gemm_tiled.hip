@@ -9,12 +9,14 @@
 //     directly, 1 KiB contiguous per load, through a 3-deep register ring
 //     (loads issued two k-steps before use);
 //   - the token-row operand is shared by the 4 waves: it goes global -> registers
-//     -> LDS in stages of 64 k (two k-steps), fetched one stage ahead with full
+//     -> LDS in stages of 64 k (two k-steps), fetched two stages ahead with full
 //     128-byte lines per row, and is stored in MFMA operand order with a slot
 //     swizzle so that both the staging writes and the linear-by-lane operand
-//     reads are free of bank conflicts; two LDS buffers, one barrier per stage;
-//   - the 32 MFMAs of a k-step are four inline-assembly blocks that issue the
-//     LDS reads of the next operand pair ahead of the current pair's MFMAs;
+//     reads are free of bank conflicts; three LDS buffers, one barrier per stage;
+//   - the 32 MFMAs of a k-step are four inline-assembly blocks, each of which
+//     requests the operand pair of the next block before multiplying its own;
+//     the chain continues across k-steps and stages (the next stage's rows are
+//     already in LDS), so no MFMA waits for a cold LDS read;
 //   - every load is unconditional (clamped index + select): a load under a branch
 //     makes the compiler drain the whole prefetch queue at the next wait.
 // Workgroups are numbered so that the 32 that run together on one XCD (they share
@@ -33,7 +35,7 @@ namespace fxp {
 constexpr int kTgThreads = 256;
 constexpr int kTgBM = 128, kTgBN = 256;
 constexpr int kTgRn = 4, kTgRm = 8;
-constexpr int kTgStages = 2;                               // LDS stages of two k-steps (64 k) each
+constexpr int kTgStages = 3;                               // LDS buffers, each one stage of two k-steps (64 k)
 constexpr int kTgXChunks = 2 * kTgRm * 64;                 // 16-byte chunks of one stage (16 KiB)
 constexpr int kTgXPerThread = kTgXChunks / kTgThreads;     // 4
 
@@ -118,13 +120,16 @@ __global__ __launch_bounds__(kTgThreads, 2) void gemm_tiled_kernel(TiledArgs a)
 #pragma unroll
         for (int i = 0; i < kTgXPerThread; ++i) s_x[stage][xdst[i]] = x[i];
     };
-    // One k-step of the wave tile: 8 column-tile operands from LDS, 32 MFMAs.  Written as four
-    // inline-assembly blocks because the compiler's scheduler puts every LDS read directly in
-    // front of its first use and then waits for it, which leaves the matrix pipe idle for the
-    // LDS latency eight times per step.  Here the reads of the next operand pair are issued
-    // before the 8 MFMAs of the current pair, and the wait (lgkmcnt(2): everything but the two
-    // reads just issued; LDS returns in order) is satisfied long before it is reached.
-    // lds_addr = byte address in LDS of this lane's 16 bytes of column tile 0 of the stage.
+    // One k-step of the wave tile: 8 column-tile operands from LDS, 32 MFMAs, written as four
+    // inline-assembly blocks of 8 MFMAs (two column tiles) because the compiler's scheduler puts
+    // every LDS read directly in front of its first use and then waits for it, which leaves the
+    // matrix pipe idle for the LDS latency.  Every block first issues the LDS reads of the operand
+    // pair that the NEXT block multiplies and then waits only for its own pair (lgkmcnt(2):
+    // everything but the two reads just issued; LDS returns in order), which was requested one
+    // block earlier.  The chain runs across k-steps and across stages: the last block of a k-step
+    // requests the first pair of the next one (the token rows of the next stage are already in
+    // LDS, see below), so the pipe never waits for a cold LDS read after the prologue.
+    // Two operand register sets (A, B) alternate; four blocks per k-step keep their roles fixed.
 #define FXP_MFMA8(X0, X1)                                                  \
     "v_mfma_f32_16x16x32_bf16 %[a0], %[w0], %[" #X0 "], %[a0]\n"              \
     "v_mfma_f32_16x16x32_bf16 %[a1], %[w1], %[" #X0 "], %[a1]\n"              \
@@ -138,35 +143,25 @@ __global__ __launch_bounds__(kTgThreads, 2) void gemm_tiled_kernel(TiledArgs a)
     [a0] "+v"(acc[0][M]), [a1] "+v"(acc[1][M]), [a2] "+v"(acc[2][M]), [a3] "+v"(acc[3][M]),         \
     [b0] "+v"(acc[0][M + 1]), [b1] "+v"(acc[1][M + 1]), [b2] "+v"(acc[2][M + 1]), [b3] "+v"(acc[3][M + 1])
 #define FXP_WOPS [w0] "v"(w[0]), [w1] "v"(w[1]), [w2] "v"(w[2]), [w3] "v"(w[3])
-    auto compute = [&](const u32x4(&w)[kTgRn], uint32_t lds_addr) {
-        u32x4 p0, p1, q0, q1;
-        asm volatile("ds_read_b128 %[p0], %[addr]\n"
-                     "ds_read_b128 %[p1], %[addr] offset:1024\n"
-                     "ds_read_b128 %[q0], %[addr] offset:2048\n"
-                     "ds_read_b128 %[q1], %[addr] offset:3072\n"
-                     "s_waitcnt lgkmcnt(2)\n" FXP_MFMA8(p0, p1)
-                     : [p0] "=&v"(p0), [p1] "=&v"(p1), [q0] "=&v"(q0), [q1] "=&v"(q1), FXP_ACC8(0)
-                     : [addr] "v"(lds_addr), FXP_WOPS
-                     : "memory");
-        u32x4 r0, r1;
-        asm volatile("ds_read_b128 %[r0], %[addr] offset:4096\n"
-                     "ds_read_b128 %[r1], %[addr] offset:5120\n"
-                     "s_waitcnt lgkmcnt(2)\n" FXP_MFMA8(x0, x1)
-                     : [r0] "=&v"(r0), [r1] "=&v"(r1), FXP_ACC8(2)
-                     : [addr] "v"(lds_addr), FXP_WOPS, [x0] "v"(q0), [x1] "v"(q1)
-                     : "memory");
-        u32x4 t0, t1;
-        asm volatile("ds_read_b128 %[t0], %[addr] offset:6144\n"
-                     "ds_read_b128 %[t1], %[addr] offset:7168\n"
-                     "s_waitcnt lgkmcnt(2)\n" FXP_MFMA8(x0, x1)
-                     : [t0] "=&v"(t0), [t1] "=&v"(t1), FXP_ACC8(4)
-                     : [addr] "v"(lds_addr), FXP_WOPS, [x0] "v"(r0), [x1] "v"(r1)
-                     : "memory");
-        asm volatile("s_waitcnt lgkmcnt(0)\n" FXP_MFMA8(x0, x1)
-                     : FXP_ACC8(6)
-                     : FXP_WOPS, [x0] "v"(t0), [x1] "v"(t1)
-                     : "memory");
+    // request column tiles (OFF0, OFF1) at NADDR into (N0, N1); multiply column tiles M, M+1 held in (C0, C1)
+#define FXP_BLOCK(N0, N1, NADDR, OFF0, OFF1, C0, C1, M)                                              \
+    asm volatile("ds_read_b128 %[n0], %[naddr] offset:" #OFF0 "\n"                                    \
+                 "ds_read_b128 %[n1], %[naddr] offset:" #OFF1 "\n"                                    \
+                 "s_waitcnt lgkmcnt(2)\n" FXP_MFMA8(c0, c1)                                            \
+                 : [n0] "=&v"(N0), [n1] "=&v"(N1), FXP_ACC8(M)                                        \
+                 : [naddr] "v"(NADDR), FXP_WOPS, [c0] "v"(C0), [c1] "v"(C1)                           \
+                 : "memory");
+    u32x4 xa0, xa1, xb0, xb1;          // operand sets A and B
+    // lds_addr: this lane's 16 bytes of column tile 0 of the k-step (tile t is 1 KiB further per t);
+    // next_addr: the same for the k-step that follows.  On entry set A holds (or is about to
+    // receive) column tiles 0, 1 of this k-step; on exit it has been asked for those of the next.
+    auto compute = [&](const u32x4(&w)[kTgRn], uint32_t lds_addr, uint32_t next_addr) {
+        FXP_BLOCK(xb0, xb1, lds_addr, 2048, 3072, xa0, xa1, 0)
+        FXP_BLOCK(xa0, xa1, lds_addr, 4096, 5120, xb0, xb1, 2)
+        FXP_BLOCK(xb0, xb1, lds_addr, 6144, 7168, xa0, xa1, 4)
+        FXP_BLOCK(xa0, xa1, next_addr, 0, 1024, xb0, xb1, 6)
     };
+#undef FXP_BLOCK
 #undef FXP_MFMA8
 #undef FXP_ACC8
 #undef FXP_WOPS
@@ -177,34 +172,44 @@ __global__ __launch_bounds__(kTgThreads, 2) void gemm_tiled_kernel(TiledArgs a)
     constexpr uint32_t kStageBytes = kTgXChunks * 16;
 
     // Weights: ring of three k-steps (w(ks), w(ks+1) resident, w(ks+2) in flight).  Token rows:
-    // stage t+1 is fetched to registers at the start of stage t and written to the other LDS
-    // buffer at its end, one barrier per stage.  Three stages (six k-steps) per trip so that
-    // every register set keeps its name.
+    // three LDS buffers; stage t+2 is fetched to registers at the start of stage t and written to
+    // buffer (t+2) % 3 at its end.  That buffer was last read in stage t-1, so the one barrier per
+    // stage (at its end) orders those reads before these writes, and it makes the rows of stage
+    // t+1, written a stage earlier, visible before the last block of stage t asks for them.
+    // Three stages (six k-steps) per trip so that every register set and buffer keeps its name.
     u32x4 w0[kTgRn], w1[kTgRn], w2[kTgRn], xg[kTgXPerThread];
     fetch_x(xg, 0);
     fetch_w(w0, 0);
     fetch_w(w1, 1);
     store_x(xg, 0);
+    fetch_x(xg, 1);
+    store_x(xg, 1);
     __syncthreads();
-#define FXP_TG_STAGE(WA, WB, WC2, WD2, KTV)                                   \
-    fetch_x(xg, (KTV) + 1);                                                    \
+    asm volatile("ds_read_b128 %[n0], %[addr]\n"
+                 "ds_read_b128 %[n1], %[addr] offset:1024\n"
+                 : [n0] "=&v"(xa0), [n1] "=&v"(xa1) : [addr] "v"(lds_h0) : "memory");
+#define FXP_TG_STAGE(WA, WB, WC2, WD2, KTV, BUF, BUF_NEXT, BUF_STORE)          \
+    fetch_x(xg, (KTV) + 2);                                                    \
     fetch_w(WC2, 2 * (KTV) + 2);                                               \
-    compute(WA, lds_h0 + ((KTV) & 1) * kStageBytes);                           \
+    compute(WA, lds_h0 + (BUF) * kStageBytes, lds_h1 + (BUF) * kStageBytes);   \
     fetch_w(WD2, 2 * (KTV) + 3);                                               \
-    compute(WB, lds_h1 + ((KTV) & 1) * kStageBytes);                           \
-    store_x(xg, ((KTV) & 1) ^ 1);                                              \
+    compute(WB, lds_h1 + (BUF) * kStageBytes, lds_h0 + (BUF_NEXT) * kStageBytes); \
+    store_x(xg, BUF_STORE);                                                    \
     __syncthreads();
-    // k-step s lives in weight set s % 3, so the set names repeat every three stages
+    // k-step s lives in weight set s % 3 and stage t in LDS buffer t % 3, so the names repeat every three stages
     int kt = 0;
     for (; kt + 3 <= KT; kt += 3) {
-        FXP_TG_STAGE(w0, w1, w2, w0, kt)          // k-steps 6j,   6j+1; fetches w(6j+2) -> w2, w(6j+3) -> w0
-        FXP_TG_STAGE(w2, w0, w1, w2, kt + 1)      // k-steps 6j+2, 6j+3; fetches w(6j+4) -> w1, w(6j+5) -> w2
-        FXP_TG_STAGE(w1, w2, w0, w1, kt + 2)      // k-steps 6j+4, 6j+5; fetches w(6j+6) -> w0, w(6j+7) -> w1
+        FXP_TG_STAGE(w0, w1, w2, w0, kt, 0, 1, 2)          // k-steps 6j,   6j+1; fetches w(6j+2) -> w2, w(6j+3) -> w0
+        FXP_TG_STAGE(w2, w0, w1, w2, kt + 1, 1, 2, 0)      // k-steps 6j+2, 6j+3; fetches w(6j+4) -> w1, w(6j+5) -> w2
+        FXP_TG_STAGE(w1, w2, w0, w1, kt + 2, 2, 0, 1)      // k-steps 6j+4, 6j+5; fetches w(6j+6) -> w0, w(6j+7) -> w1
     }
     if (kt < KT) {
-        FXP_TG_STAGE(w0, w1, w2, w0, kt)
-        if (kt + 1 < KT) { FXP_TG_STAGE(w2, w0, w1, w2, kt + 1) }
+        FXP_TG_STAGE(w0, w1, w2, w0, kt, 0, 1, 2)
+        if (kt + 1 < KT) { FXP_TG_STAGE(w2, w0, w1, w2, kt + 1, 1, 2, 0) }
     }
+    // the last block's request for a further k-step is never used, but its registers must not be
+    // given to anything else before the data has landed
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(xa0), "+v"(xa1) : : "memory");
 #undef FXP_TG_STAGE
 
     // ---- epilogue
