@@ -130,25 +130,28 @@ __global__ __launch_bounds__(kDecThreads) void attn_decode_kernel(DecodeAttnArgs
         // it drain the (in-order) vector-memory counter, i.e. stall until the cache block in
         // flight has landed before the next one could be requested; LDS has a counter of its own.
         int c0 = 0;
-        auto load_block = [&](int b, u32x4(&k)[IPB], u32x4(&v)[IPB]) {
+        // K and V of a block are requested at different times (K before the scores of the previous
+        // block, V after them): the two 4 KiB runs of one block lie exactly Hkv*4 KiB apart in the
+        // same cache unit, and asking for both at once costs a few per cent of HBM bandwidth.
+        auto block_ptr = [&](int b) {
             const int32_t phys = __builtin_amdgcn_readfirstlane(s_tbl[b - c0]);
-            const char *kp = layer_base + (int64_t)phys * unit_bytes + (int64_t)hk * head_bytes + lane * 16;
-            const char *vp = kp + (int64_t)Hkv * head_bytes;
-#pragma unroll
-            for (int i = 0; i < IPB; ++i) {
-                k[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(kp + i * 1024));
-                v[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(vp + i * 1024));
-            }
+            return layer_base + (int64_t)phys * unit_bytes + (int64_t)hk * head_bytes + lane * 16;
         };
-        auto consume = [&](int b, const u32x4(&k)[IPB], u32x4(&v)[IPB]) {
-            const int tbase = (blk0 + b) * kBlockTokens;
-            if (tbase + kBlockTokens > n_keys) {
-                // last block of the sequence: rows past the end may hold anything (also NaN
-                // patterns); zero them so that a zero probability meets a zero value
+        auto load_k = [&](int b, u32x4(&k)[IPB]) {
+            const char *kp = block_ptr(b);
 #pragma unroll
-                for (int i = 0; i < IPB; ++i)
-                    if (tbase + i * TPI + ti >= n_keys) v[i] = u32x4{0u, 0u, 0u, 0u};
-            }
+            for (int i = 0; i < IPB; ++i) k[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(kp + i * 1024));
+        };
+        auto load_v = [&](int b, u32x4(&v)[IPB]) {
+            const char *vp = block_ptr(b) + (int64_t)Hkv * head_bytes;
+#pragma unroll
+            for (int i = 0; i < IPB; ++i) v[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(vp + i * 1024));
+        };
+        // scores of block b against the query, running maximum and sum; leaves the block's
+        // probabilities p and the rescale factor alpha for weigh()
+        float p[G][IPB], alpha[G];
+        auto scores = [&](int b, const u32x4(&k)[IPB]) {
+            const int tbase = (blk0 + b) * kBlockTokens;
 #pragma unroll
             for (int g = 0; g < G; ++g) {
                 float s[IPB];
@@ -175,24 +178,38 @@ __global__ __launch_bounds__(kDecThreads) void attn_decode_kernel(DecodeAttnArgs
 #pragma unroll
                 for (int i = 0; i < IPB; ++i) mn = fmaxf(mn, s[i]);
                 const float ms = (mn == -INFINITY) ? 0.f : mn;
-                const float alpha = fast_exp2(m[g] - ms);
+                alpha[g] = fast_exp2(m[g] - ms);
                 m[g] = mn;
-                float p[IPB], psum = 0.f;
+                float psum = 0.f;
 #pragma unroll
-                for (int i = 0; i < IPB; ++i) { p[i] = fast_exp2(s[i] - ms); psum += p[i]; }
-                l[g] = l[g] * alpha + psum;
+                for (int i = 0; i < IPB; ++i) { p[g][i] = fast_exp2(s[i] - ms); psum += p[g][i]; }
+                l[g] = l[g] * alpha[g] + psum;
+            }
+        };
+        // acc = acc * alpha + p . V of block b
+        auto weigh = [&](int b, u32x4(&v)[IPB]) {
+            const int tbase = (blk0 + b) * kBlockTokens;
+            if (tbase + kBlockTokens > n_keys) {
+                // last block of the sequence: rows past the end may hold anything (also NaN
+                // patterns); zero them so that a zero probability meets a zero value
 #pragma unroll
-                for (int e = 0; e < 8; ++e) acc[g][e] *= alpha;
+                for (int i = 0; i < IPB; ++i)
+                    if (tbase + i * TPI + ti >= n_keys) v[i] = u32x4{0u, 0u, 0u, 0u};
+            }
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[g][e] *= alpha[g];
 #pragma unroll
                 for (int i = 0; i < IPB; ++i) {
-                    acc[g][0] = fmaf(p[i], bf16_lo(v[i].x), acc[g][0]);
-                    acc[g][1] = fmaf(p[i], bf16_hi(v[i].x), acc[g][1]);
-                    acc[g][2] = fmaf(p[i], bf16_lo(v[i].y), acc[g][2]);
-                    acc[g][3] = fmaf(p[i], bf16_hi(v[i].y), acc[g][3]);
-                    acc[g][4] = fmaf(p[i], bf16_lo(v[i].z), acc[g][4]);
-                    acc[g][5] = fmaf(p[i], bf16_hi(v[i].z), acc[g][5]);
-                    acc[g][6] = fmaf(p[i], bf16_lo(v[i].w), acc[g][6]);
-                    acc[g][7] = fmaf(p[i], bf16_hi(v[i].w), acc[g][7]);
+                    acc[g][0] = fmaf(p[g][i], bf16_lo(v[i].x), acc[g][0]);
+                    acc[g][1] = fmaf(p[g][i], bf16_hi(v[i].x), acc[g][1]);
+                    acc[g][2] = fmaf(p[g][i], bf16_lo(v[i].y), acc[g][2]);
+                    acc[g][3] = fmaf(p[g][i], bf16_hi(v[i].y), acc[g][3]);
+                    acc[g][4] = fmaf(p[g][i], bf16_lo(v[i].z), acc[g][4]);
+                    acc[g][5] = fmaf(p[g][i], bf16_hi(v[i].z), acc[g][5]);
+                    acc[g][6] = fmaf(p[g][i], bf16_lo(v[i].w), acc[g][6]);
+                    acc[g][7] = fmaf(p[g][i], bf16_hi(v[i].w), acc[g][7]);
                 }
             }
         };
@@ -206,17 +223,24 @@ __global__ __launch_bounds__(kDecThreads) void attn_decode_kernel(DecodeAttnArgs
             __builtin_amdgcn_wave_barrier();
             int b = c0;
             u32x4 k0[IPB], v0[IPB], k1[IPB], v1[IPB];
-            load_block(b, k0, v0);
+            load_k(b, k0);
+            load_v(b, v0);
             while (b + 2 < ce) {
-                load_block(b + 1, k1, v1);
-                consume(b, k0, v0);
-                load_block(b + 2, k0, v0);
-                consume(b + 1, k1, v1);
+                load_k(b + 1, k1);
+                scores(b, k0);
+                load_v(b + 1, v1);
+                weigh(b, v0);
+                load_k(b + 2, k0);
+                scores(b + 1, k1);
+                load_v(b + 2, v0);
+                weigh(b + 1, v1);
                 b += 2;
             }
-            if (b + 1 < ce) load_block(b + 1, k1, v1);
-            consume(b, k0, v0);
-            if (b + 1 < ce) consume(b + 1, k1, v1);
+            if (b + 1 < ce) load_k(b + 1, k1);
+            scores(b, k0);
+            if (b + 1 < ce) load_v(b + 1, v1);
+            weigh(b, v0);
+            if (b + 1 < ce) { scores(b + 1, k1); weigh(b + 1, v1); }
         }
 
         // merge the TPI lane groups (butterfly, lower group always the first operand) and store the piece
