@@ -222,25 +222,35 @@ __global__ __launch_bounds__(kDecThreads) void attn_decode_kernel(DecodeAttnArgs
             for (int j = lane; j < ce - c0; j += 64) s_tbl[j] = trow[c0 + j];
             __builtin_amdgcn_wave_barrier();
             int b = c0;
+            // K runs two blocks ahead of the scores and is requested in the middle of an iteration, V
+            // one block ahead and at its start: the K and the V request of one block are then most of
+            // an iteration apart, with two register buffers each.
             u32x4 k0[IPB], v0[IPB], k1[IPB], v1[IPB];
             load_k(b, k0);
+            if (b + 1 < ce) load_k(b + 1, k1);
             load_v(b, v0);
-            while (b + 2 < ce) {
-                load_k(b + 1, k1);
-                scores(b, k0);
+            while (b + 3 < ce) {
                 load_v(b + 1, v1);
-                weigh(b, v0);
+                scores(b, k0);
                 load_k(b + 2, k0);
-                scores(b + 1, k1);
+                weigh(b, v0);
                 load_v(b + 2, v0);
+                scores(b + 1, k1);
+                load_k(b + 3, k1);
                 weigh(b + 1, v1);
                 b += 2;
             }
-            if (b + 1 < ce) load_k(b + 1, k1);
-            scores(b, k0);
+            // one to three blocks left: K(b), K(b+1) and V(b) have been requested
             if (b + 1 < ce) load_v(b + 1, v1);
+            scores(b, k0);
+            if (b + 2 < ce) load_k(b + 2, k0);
             weigh(b, v0);
-            if (b + 1 < ce) { scores(b + 1, k1); weigh(b + 1, v1); }
+            if (b + 1 < ce) {
+                if (b + 2 < ce) load_v(b + 2, v0);
+                scores(b + 1, k1);
+                weigh(b + 1, v1);
+                if (b + 2 < ce) { scores(b + 2, k0); weigh(b + 2, v0); }
+            }
         }
 
         // merge the TPI lane groups (butterfly, lower group always the first operand) and store the piece
