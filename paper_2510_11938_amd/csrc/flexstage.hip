@@ -9,6 +9,7 @@
 #include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
+#include <algorithm>
 #include <new>
 
 namespace {
@@ -135,11 +136,17 @@ SkinnyCfg skinny_cfg(int N, int K, int M)
     // per CU streams fastest; more, thinner workgroups lose bandwidth, as do uneven k ranges,
     // hence power-of-two splits.
     c.R = forced_r ? forced_r : ((N >= 16384 && M <= 64) ? 4 : 2);
-    // above 64 rows the tiled kernel is used: its workgroup covers 256 weight rows
-    const int wgs_n = M > kSkinnyWideTokens ? (N + 255) / 256 : (N + 64 * c.R - 1) / (64 * c.R);
+    if (M > kSkinnyWideTokens) {
+        // 65..128 rows go through the tiled kernel, whose workgroup covers 256 weight rows: one
+        // workgroup per CU of a 256-CU chip and never more (a second one on a quarter of the CUs
+        // doubles the time of the launch; measured: 320 workgroups 57 us, 240 workgroups 45 us)
+        const int wgs_n = (N + 255) / 256;
+        c.S = forced_s ? forced_s : std::max(1, std::min(std::min(8, ks / 8), 256 / wgs_n));
+        return c;
+    }
+    const int wgs_n = (N + 64 * c.R - 1) / (64 * c.R);
     int s = 1;
-    const int limit = M > kSkinnyWideTokens ? 2 * max_wgs : max_wgs;    // the tiled kernel wants two workgroups per CU
-    while (s * 2 <= 8 && s * 2 <= ks / 8 && wgs_n * s * 2 <= limit) s *= 2;
+    while (s * 2 <= 8 && s * 2 <= ks / 8 && wgs_n * s * 2 <= max_wgs) s *= 2;
     c.S = forced_s ? forced_s : s;
     return c;
 }
@@ -459,11 +466,11 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
         return fxp::launch_gemm_skinny(a, st);
     };
     auto project_tiled = [&](const char *wbase, const uint16_t *X, int N, int K, int ldx, uint16_t *C, int ldc,
-                             const uint16_t *R, int epi, const uint16_t *bias = nullptr) -> hipError_t {
+                             const uint16_t *R, int epi, const uint16_t *bias = nullptr, int kernel_class = kKcTiled) -> hipError_t {
         fxp::TiledArgs a;
         a.W = (const uint16_t *)wbase; a.X = X; a.R = R; a.C = C; a.P = nullptr; a.S = 1; a.bias = bias;
         a.M = T; a.K = K; a.KS = k_steps(K); a.NT = N / 16; a.ldx = ldx; a.ldc = ldc; a.epilogue = epi;
-        KernelTimer kt(kKcTiled, st);
+        KernelTimer kt(kernel_class, st);
         return fxp::launch_gemm_tiled(a, st);
     };
 
@@ -555,8 +562,15 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
             // applies SwiGLU itself; above, the split partial sums go through the SwiGLU kernel)
             // (an OPT-style layer has one matrix here and relu(sum + bias) as activation)
             const int Nup = opt ? F : 2 * F;
-            const bool fused_act = T <= kSkinnyWideTokens && skinny_fused_swiglu(Nup);
-            if ((e = project_skinny(rec + stage->rec.wgu, w.n, Nup, H, H, &S, fused_act ? w.a : nullptr, b_up))) return hip_fail(e, "gate/up projection");
+            const bool wide_unsplit = T > kSkinnyWideTokens && skinny_cfg(Nup, H, T).S == 1;
+            const bool fused_act = wide_unsplit || (T <= kSkinnyWideTokens && skinny_fused_swiglu(Nup));
+            if (wide_unsplit) {
+                // 65..128 rows and a matrix that fills the chip without a split: the tiled kernel's own activation epilogue
+                if ((e = project_tiled(rec + stage->rec.wgu, w.n, Nup, H, H, w.a, F, nullptr, opt ? fxp::kEpiRelu : fxp::kEpiSwiglu, b_up, kKcSkinny)))
+                    return hip_fail(e, "gate/up projection");
+            } else if ((e = project_skinny(rec + stage->rec.wgu, w.n, Nup, H, H, &S, fused_act ? w.a : nullptr, b_up))) {
+                return hip_fail(e, "gate/up projection");
+            }
             if (!fused_act) {
                 fxp::SwigluArgs sg;
                 sg.P = w.P; sg.out = w.a; sg.T = T; sg.F = F; sg.S = S; sg.ld_out = F; sg.bias = b_up; sg.act = opt ? 1 : 0;

@@ -49,7 +49,10 @@ __global__ __launch_bounds__(kTgThreads, 2) void gemm_tiled_kernel(TiledArgs a)
     // ---- tile of this workgroup (XCD-aware numbering, see the header comment)
     const int tiles_n = (a.NT * 16 + kTgBN - 1) / kTgBN, tiles_m = (a.M + kTgBM - 1) / kTgBM;
     int tile_m, tile_n;
-    {
+    if (tiles_m == 1) {          // one row of tiles (at most 128 token rows): nothing to share but the token rows
+        tile_m = 0;
+        tile_n = blockIdx.x;
+    } else {
         constexpr int kXcds = 8, kBlkN = 4, kBlkM = 8;      // 32 workgroups of one XCD = 4 x 8 tiles
         const int blocks_n = (tiles_n + kBlkN - 1) / kBlkN;
         const int id = blockIdx.x;
@@ -268,6 +271,7 @@ hipError_t launch_gemm_tiled(const TiledArgs &a, hipStream_t stream)
     // the XCD-aware numbering covers whole 4 x 8 super-blocks, rounded up to a multiple of 8 of them
     const int blocks = ((tiles_n + 3) / 4) * ((tiles_m + 7) / 8);
     dim3 grid((blocks + 7) / 8 * 8 * 32, a.epilogue == kEpiPartial ? a.S : 1);
+    if (tiles_m == 1) grid.x = tiles_n;
     const bool tail = a.K % 32 != 0;
 #define FXP_TG_LAUNCH(E)                                                                                       \
     if (tail) hipLaunchKernelGGL((gemm_tiled_kernel<E, true>), grid, dim3(kTgThreads), 0, stream, a);          \
