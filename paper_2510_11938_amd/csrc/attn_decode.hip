@@ -492,12 +492,16 @@ __global__ __launch_bounds__(kDecThreads, 2) void attn_decode_mfma_kernel(Decode
 }
 
 // Merge the pieces of each (sequence, query head) in worker order and normalise:
-// o = sum_p acc_p 2^(m_p - m) / sum_p l_p 2^(m_p - m).  One workgroup per (sequence, kv head).
+// o = sum_p acc_p 2^(m_p - m) / sum_p l_p 2^(m_p - m).  One workgroup per (sequence, query head),
+// one thread per dim.  The running maximum is carried along (as in the attention loop), so the
+// maxima, sums and accumulators of a group of pieces are independent loads issued together: one
+// memory round trip per four pieces instead of three dependent ones per piece.
 template <bool DEBUG>
 __global__ void attn_decode_combine_kernel(DecodeAttnArgs a)
 {
-    const int seq = blockIdx.x / a.n_kv_heads, hk = blockIdx.x % a.n_kv_heads;
+    constexpr int kGroup = 4;
     const int D = a.head_dim, G = a.n_q_heads / a.n_kv_heads, Hkv = a.n_kv_heads;
+    const int seq = blockIdx.x / a.n_q_heads, head = blockIdx.x % a.n_q_heads, hk = head / G, g = head % G;
     const int32_t before = a.blk_prefix[seq], total = a.blk_prefix[a.num_seqs];   // blocks (per head) before this sequence / in the batch
     const int n_keys = a.ctx_lens[seq] + 1;
     const int nb = (n_keys + kBlockTokens - 1) / kBlockTokens;
@@ -505,24 +509,35 @@ __global__ void attn_decode_combine_kernel(DecodeAttnArgs a)
     const int64_t u0 = (int64_t)before * Hkv + (int64_t)hk * nb;
     const int64_t w_first = worker_of(u0, U, W), w_last = worker_of(u0 + nb - 1, U, W);
     const int64_t pair = (int64_t)seq * Hkv + hk;
-    for (int g = 0; g < G; ++g) {
-        float mm = -INFINITY;
-        for (int64_t w = w_first; w <= w_last; ++w) mm = fmaxf(mm, a.part_ml[((w + pair) * G + g) * 2]);
-        float ll = 0.f;
-        for (int64_t w = w_first; w <= w_last; ++w)
-            ll += a.part_ml[((w + pair) * G + g) * 2 + 1] * fast_exp2(a.part_ml[((w + pair) * G + g) * 2] - mm);
-        const int64_t row = (int64_t)seq * a.n_q_heads + hk * G + g;
-        for (int d = threadIdx.x; d < D; d += blockDim.x) {
-            float av = 0.f;
-            for (int64_t w = w_first; w <= w_last; ++w)
-                av += a.part_acc[((w + pair) * G + g) * D + d] * fast_exp2(a.part_ml[((w + pair) * G + g) * 2] - mm);
-            a.out[row * D + d] = f32_to_bf16(av / ll);
+    const int d = threadIdx.x;
+    float mm = -INFINITY, ll = 0.f, av = 0.f;
+    for (int64_t w0 = w_first; w0 <= w_last; w0 += kGroup) {
+        float m[kGroup], l[kGroup], ac[kGroup];
+#pragma unroll
+        for (int j = 0; j < kGroup; ++j) {
+            const int64_t piece = (min(w0 + j, w_last) + pair) * G + g;
+            m[j] = a.part_ml[piece * 2];
+            l[j] = a.part_ml[piece * 2 + 1];
+            ac[j] = a.part_acc[piece * D + d];
         }
-        if constexpr (DEBUG) {
-            // turn the stored scaled scores (log2 domain) into probabilities
-            float *pr = a.dbg_scores + row * a.dbg_stride;
-            for (int r = threadIdx.x; r < n_keys; r += blockDim.x) pr[r] = fast_exp2(pr[r] - mm) / ll;
+#pragma unroll
+        for (int j = 0; j < kGroup; ++j) {
+            if (w0 + j <= w_last) {
+                const float mn = fmaxf(mm, m[j]);
+                const float s_old = mm == -INFINITY ? 0.f : fast_exp2(mm - mn);
+                const float s_new = m[j] == -INFINITY ? 0.f : fast_exp2(m[j] - mn);
+                ll = ll * s_old + l[j] * s_new;
+                av = av * s_old + ac[j] * s_new;
+                mm = mn;
+            }
         }
+    }
+    const int64_t row = (int64_t)seq * a.n_q_heads + head;
+    a.out[row * D + d] = f32_to_bf16(av / ll);
+    if constexpr (DEBUG) {
+        // turn the stored scaled scores (log2 domain) into probabilities
+        float *pr = a.dbg_scores + row * a.dbg_stride;
+        for (int r = threadIdx.x; r < n_keys; r += blockDim.x) pr[r] = fast_exp2(pr[r] - mm) / ll;
     }
 }
 
@@ -538,7 +553,7 @@ static hipError_t launch_dg(const DecodeAttnArgs &a, hipStream_t stream)
 
 hipError_t launch_attn_decode_combine(const DecodeAttnArgs &a, hipStream_t stream)
 {
-    const dim3 cgrid(a.num_seqs * a.n_kv_heads);
+    const dim3 cgrid(a.num_seqs * a.n_q_heads);
     if (a.dbg_scores) hipLaunchKernelGGL(attn_decode_combine_kernel<true>, cgrid, dim3(a.head_dim), 0, stream, a);
     else hipLaunchKernelGGL(attn_decode_combine_kernel<false>, cgrid, dim3(a.head_dim), 0, stream, a);
     return hipGetLastError();
