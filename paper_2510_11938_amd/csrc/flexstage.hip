@@ -146,7 +146,14 @@ SkinnyCfg skinny_cfg(int N, int K, int M)
     }
     const int wgs_n = (N + 64 * c.R - 1) / (64 * c.R);
     int s = 1;
-    while (s * 2 <= 8 && s * 2 <= ks / 8 && wgs_n * s * 2 <= max_wgs) s *= 2;
+    if (M > 32) {
+        // 33..64 rows: the token rows cost a workgroup as much L2 traffic as its weights cost HBM traffic,
+        // and more, smaller workgroups hide that better (13B shape, 64 rows: 168 -> 156 us per layer)
+        static const int wgs64 = env_int("FXP_SKINNY_MAX_WGS64", 512), cap64 = env_int("FXP_SKINNY_CAP64", 12);
+        s = std::max(1, std::min(std::min(cap64, ks / 16), wgs64 / wgs_n));
+    } else {
+        while (s * 2 <= 8 && s * 2 <= ks / 8 && wgs_n * s * 2 <= max_wgs) s *= 2;
+    }
     c.S = forced_s ? forced_s : s;
     return c;
 }
@@ -224,14 +231,16 @@ Workspace carve(const fxp_stage_desc &d, int T, int B, int max_blocks, char *bas
     w.o = (uint16_t *)take(t * Nq * 2);
     w.a = (uint16_t *)take(t * F * 2);
     w.qkv = (uint16_t *)take(T > kSkinnyMaxTokens ? t * Nall * 2 : 0);
-    const int Ms = T < kSkinnyMaxTokens ? (T > 0 ? T : 1) : kSkinnyMaxTokens;
     size_t pmax = 0;
     const int shapes[4][2] = {{Nall, H}, {H, Nq}, {2 * F, H}, {H, F}};
+    const int row_classes[3] = {32, kSkinnyWideTokens, kSkinnyMaxTokens};     // the split factor is chosen per class of row counts
     for (auto &s : shapes) {
-        // the split factor depends on the row-tile configuration chosen for M: size for the larger one
-        const int s_lo = choose_split(s[0], s[1], 16), s_hi = choose_split(s[0], s[1], kSkinnyMaxTokens);
-        const size_t b = (size_t)(s_lo > s_hi ? s_lo : s_hi) * Ms * s[0] * 4;
-        if (b > pmax) pmax = b;
+        // sized for every batch of up to T rows, so that a workspace for max_tokens serves smaller calls too
+        for (int rc : row_classes) {
+            const int m = std::min(rc, T > 0 ? T : 1);
+            const size_t b = (size_t)choose_split(s[0], s[1], m) * m * s[0] * 4;
+            if (b > pmax) pmax = b;
+        }
     }
     w.P = (float *)take(pmax);
     (void)max_blocks;
@@ -456,7 +465,11 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
         }
         fxp::SkinnyArgs a;
         a.W = (const uint16_t *)wbase; a.X = X; a.P = w.P; a.A = nullptr; a.bias = nullptr; a.act = 0;
-        a.M = T; a.N = N; a.K = K; a.KS = k_steps(K); a.NT = N / 16; a.ldx = ldx; a.S = skinny_cfg(N, K, T).S; a.R = skinny_cfg(N, K, T).R; a.U = env_int("FXP_SKINNY_U", 4);
+        a.M = T; a.N = N; a.K = K; a.KS = k_steps(K); a.NT = N / 16; a.ldx = ldx; a.S = skinny_cfg(N, K, T).S; a.R = skinny_cfg(N, K, T).R;
+        // prefetch depth (k-steps per register buffer), measured: up to 32 rows 4 is best for both forms (2: -20 %, 8: -10 %);
+        // at 33..64 rows the split form wants 2 and the unsplit form, with its long k range, 8 (13B shape: 70 -> 62 us)
+        static const int forced_u = env_int("FXP_SKINNY_U", 0);
+        a.U = forced_u ? forced_u : (T <= 32 ? 4 : (act_out ? 8 : 2));
         if (act_out) {       // activation in the epilogue: no split; for SwiGLU the gate and the up tile sit in one wavefront
             a.A = act_out; a.S = 1; a.R = 2;
             if (act_bias) { a.act = 1; a.bias = act_bias; }

@@ -200,14 +200,29 @@ static hipError_t launch_cfg(const SkinnyArgs &a, hipStream_t stream)
     return hipGetLastError();
 }
 
-template <int MT, int U>
+// a.U = k-steps per register buffer (prefetch depth), rounded down to what is built: 2, 4 or 8,
+// and 1 or 2 where four row tiles per wavefront or eight column tiles leave fewer registers
+template <int MT, int R>
+static hipError_t launch_u(const SkinnyArgs &a, hipStream_t stream)
+{
+    if constexpr (MT == 8) {
+        return R < 4 && a.U >= 2 ? launch_cfg<MT, R, 2>(a, stream) : launch_cfg<MT, R, 1>(a, stream);
+    } else if constexpr (R == 4) {
+        return MT <= 2 && a.U >= 4 ? launch_cfg<MT, R, 4>(a, stream) : launch_cfg<MT, R, 2>(a, stream);
+    } else {
+        if (a.U >= 8) return launch_cfg<MT, R, 8>(a, stream);
+        if (a.U >= 4) return launch_cfg<MT, R, 4>(a, stream);
+        return launch_cfg<MT, R, 2>(a, stream);
+    }
+}
+
+template <int MT>
 static hipError_t launch_r(const SkinnyArgs &a, hipStream_t stream)
 {
-    const bool deep = a.U >= 2 * U && MT <= 2;       // deeper prefetch only where the registers allow it
     switch (a.R) {
-    case 1: return deep ? launch_cfg<MT, 1, (MT <= 2 ? 2 * U : U)>(a, stream) : launch_cfg<MT, 1, U>(a, stream);
-    case 2: return deep ? launch_cfg<MT, 2, (MT <= 2 ? 2 * U : U)>(a, stream) : launch_cfg<MT, 2, U>(a, stream);
-    case 4: return launch_cfg<MT, 4, (MT == 8 ? 1 : U)>(a, stream);
+    case 1: return launch_u<MT, 1>(a, stream);
+    case 2: return launch_u<MT, 2>(a, stream);
+    case 4: return launch_u<MT, 4>(a, stream);
     default: return hipErrorInvalidValue;
     }
 }
@@ -215,10 +230,10 @@ static hipError_t launch_r(const SkinnyArgs &a, hipStream_t stream)
 hipError_t launch_gemm_skinny(const SkinnyArgs &a, hipStream_t stream)
 {
     const int mt = (a.M + 15) / 16;
-    if (mt <= 1) return launch_r<1, 4>(a, stream);
-    if (mt <= 2) return launch_r<2, 4>(a, stream);
-    if (mt <= 4) return launch_r<4, 2>(a, stream);
-    if (mt <= 8) return launch_r<8, 2>(a, stream);
+    if (mt <= 1) return launch_r<1>(a, stream);
+    if (mt <= 2) return launch_r<2>(a, stream);
+    if (mt <= 4) return launch_r<4>(a, stream);
+    if (mt <= 8) return launch_r<8>(a, stream);
     return hipErrorInvalidValue;
 }
 
