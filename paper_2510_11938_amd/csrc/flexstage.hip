@@ -466,10 +466,13 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
         fxp::SkinnyArgs a;
         a.W = (const uint16_t *)wbase; a.X = X; a.P = w.P; a.A = nullptr; a.bias = nullptr; a.act = 0;
         a.M = T; a.N = N; a.K = K; a.KS = k_steps(K); a.NT = N / 16; a.ldx = ldx; a.S = skinny_cfg(N, K, T).S; a.R = skinny_cfg(N, K, T).R;
-        // prefetch depth (k-steps per register buffer), measured: up to 32 rows 4 is best for both forms (2: -20 %, 8: -10 %);
-        // at 33..64 rows the split form wants 2 and the unsplit form, with its long k range, 8 (13B shape: 70 -> 62 us)
-        static const int forced_u = env_int("FXP_SKINNY_U", 0);
-        a.U = forced_u ? forced_u : (T <= 32 ? 4 : (act_out ? 8 : 2));
+        // register ring of the weight stream (NB buffers of U k-steps), measured: four buffers of two k-steps
+        // beat two of four everywhere up to 32 rows (7B shape: 96 -> 90 us per layer) and in the unsplit form
+        // with its long k range (13B shape, 64 rows: 62 -> 53 us); the short k ranges of the split form at
+        // 33..64 rows do not fill a deeper ring and keep two buffers
+        static const int forced_u = env_int("FXP_SKINNY_U", 0), forced_nb = env_int("FXP_SKINNY_NB", 0);
+        a.U = forced_u ? forced_u : 2;
+        a.NB = forced_nb ? forced_nb : ((T <= 32 || act_out) ? 4 : 2);
         if (act_out) {       // activation in the epilogue: no split; for SwiGLU the gate and the up tile sit in one wavefront
             a.A = act_out; a.S = 1; a.R = 2;
             if (act_bias) { a.act = 1; a.bias = act_bias; }

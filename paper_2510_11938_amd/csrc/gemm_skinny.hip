@@ -23,7 +23,7 @@
 
 namespace fxp {
 
-template <int MT, int R, int U>
+template <int MT, int R, int U, int NB>
 __global__ __launch_bounds__(256) void gemm_skinny_kernel(SkinnyArgs a)
 {
     constexpr int kXChunks = U * MT * 64;            // 16-byte chunks of one staged group of token rows
@@ -78,20 +78,27 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(SkinnyArgs a)
             for (int r = 0; r < R; ++r) w[u][r] = __builtin_nontemporal_load(wp[r] + (int64_t)ksc * 64);
         }
     };
+    // (the zeroing of k-steps past the range happens when the rows are stored to LDS, a group later:
+    // a select at load time needs the loaded value at once and would drain the weight prefetch with it)
+    auto x_valid = [&](int i, int g) {
+        const int ks = ks_begin + g * U + xstep[i];
+        return ks < ks_end && ks * 32 + xkc[i] + 8 <= a.K;
+    };
     auto load_x = [&](u32x4(&x)[kXPerThread], int g) {
 #pragma unroll
         for (int i = 0; i < kXPerThread; ++i) {
-            const int ks = ks_begin + g * U + xstep[i];
-            const int ksc = min(ks, ks_end - 1);
-            const bool valid = ks < ks_end && ksc * 32 + xkc[i] + 8 <= a.K;
-            const u32x4 v = ld16(xsrc[i] + (valid ? ksc * 32 : 0));
-            x[i] = valid ? v : u32x4{0u, 0u, 0u, 0u};
+            const int ksc = min(ks_begin + g * U + xstep[i], ks_end - 1);
+            x[i] = ld16(xsrc[i] + (x_valid(i, g) ? ksc * 32 : 0));
         }
     };
-    auto store_x = [&](const u32x4(&x)[kXPerThread], int buf) {
+    auto store_x = [&](const u32x4(&x)[kXPerThread], int g, int buf) {
 #pragma unroll
         for (int i = 0; i < kXPerThread; ++i)
-            if (kXChunks % 256 == 0 || i * 256 + tid < kXChunks) s_x[buf][i * 256 + tid] = x[i];
+        {
+            const uint32_t keep = x_valid(i, g) ? 0xffffffffu : 0u;      // a mask, not a select: no branch around the store
+            const u32x4 v = {x[i].x & keep, x[i].y & keep, x[i].z & keep, x[i].w & keep};
+            if (kXChunks % 256 == 0 || i * 256 + tid < kXChunks) s_x[buf][i * 256 + tid] = v;
+        }
     };
     auto mma = [&](const u32x4(&w)[U][R], int buf) {
 #pragma unroll
@@ -109,26 +116,34 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(SkinnyArgs a)
         }
     };
 
+    // Ring of NB register buffers, weights and token rows alike: the loads of the next NB-1 groups
+    // are in flight while one group is multiplied (the products of a group take a tenth of a memory
+    // round trip, so two buffers meant one round trip per group).  The token rows of a group are
+    // requested together with its weights: the vector-memory counter is in order, and a younger
+    // request for rows, waited for before its group's turn, would drain the ring.  The body is
+    // unconditional: groups past the end multiply clamped weights by zeroed token rows.
     if (ng > 0) {
-        u32x4 w0[U][R], w1[U][R], xg[kXPerThread];
-        load_x(xg, 0);
-        load_w(w0, 0);
-        store_x(xg, 0);
-        load_x(xg, 1);
+        u32x4 w[NB][U][R], xg[NB][kXPerThread];
+#pragma unroll
+        for (int b = 0; b < NB - 1; ++b) {
+            load_w(w[b], b);
+            load_x(xg[b], b);
+        }
+        store_x(xg[0], 0, 0);
         __syncthreads();
-        for (int g = 0; g < ng; g += 2) {
-            // even group: weights of g in w0, token rows of g in s_x[0], rows of g+1 in xg
-            load_w(w1, g + 1);
-            mma(w0, 0);
-            store_x(xg, 1);
-            load_x(xg, g + 2);
-            __syncthreads();
-            if (g + 1 >= ng) break;
-            load_w(w0, g + 2);
-            mma(w1, 1);
-            store_x(xg, 0);
-            load_x(xg, g + 3);
-            __syncthreads();
+        for (int g0 = 0; g0 < ng; g0 += NB) {
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                // weights of group g0+b in w[b], its token rows in s_x[b%2], the rows of the next group in xg[b+1]
+                load_w(w[(b + NB - 1) % NB], g0 + b + NB - 1);
+                load_x(xg[(b + NB - 1) % NB], g0 + b + NB - 1);
+                // keep the requests in front of the group: sunk below the products they would be
+                // younger than what the group waits for
+                __builtin_amdgcn_sched_barrier(0);
+                mma(w[b], b & 1);
+                store_x(xg[(b + 1) % NB], g0 + b + 1, (b + 1) & 1);
+                __syncthreads();
+            }
         }
     }
 
@@ -196,7 +211,10 @@ template <int MT, int R, int U>
 static hipError_t launch_cfg(const SkinnyArgs &a, hipStream_t stream)
 {
     dim3 grid((a.NT + 4 * R - 1) / (4 * R), a.S);
-    hipLaunchKernelGGL((gemm_skinny_kernel<MT, R, U>), grid, dim3(256), 0, stream, a);
+    constexpr bool kRing4 = MT * R <= 8 && U * R <= 8, kRing8 = MT * R <= 8 && U * R <= 4;    // register budget for four / eight buffers
+    if (kRing8 && a.NB >= 8) hipLaunchKernelGGL((gemm_skinny_kernel<MT, R, U, (kRing8 ? 8 : 2)>), grid, dim3(256), 0, stream, a);
+    else if (kRing4 && a.NB >= 4) hipLaunchKernelGGL((gemm_skinny_kernel<MT, R, U, (kRing4 ? 4 : 2)>), grid, dim3(256), 0, stream, a);
+    else hipLaunchKernelGGL((gemm_skinny_kernel<MT, R, U, 2>), grid, dim3(256), 0, stream, a);
     return hipGetLastError();
 }
 
@@ -212,7 +230,8 @@ static hipError_t launch_u(const SkinnyArgs &a, hipStream_t stream)
     } else {
         if (a.U >= 8) return launch_cfg<MT, R, 8>(a, stream);
         if (a.U >= 4) return launch_cfg<MT, R, 4>(a, stream);
-        return launch_cfg<MT, R, 2>(a, stream);
+        if (a.U >= 2) return launch_cfg<MT, R, 2>(a, stream);
+        return launch_cfg<MT, R, 1>(a, stream);
     }
 }
 

@@ -52,7 +52,8 @@ struct SkinnyArgs {
     int act;
     int M, N, K, KS, NT, ldx, S;   // KS = padded K / 32, NT = N / 16
     int R;                         // 16-row weight tiles per wavefront: 1, 2 or 4
-    int U;                         // k-steps per prefetch group: 4 or 8 (8 only for R <= 2, M <= 32)
+    int U;                         // k-steps per register buffer: 1, 2, 4 or 8 (rounded down to what the shape allows)
+    int NB;                        // register buffers in the ring: 2 or 4 (4 only where the registers allow it)
 };
 hipError_t launch_gemm_skinny(const SkinnyArgs &a, hipStream_t stream);
 
