@@ -65,6 +65,43 @@ def measure_stage_ms(ms: synth.ModelShape, depth: int, batch: int, ctx: np.ndarr
     return e0.elapsed_time(e1) / steps
 
 
+def layer_tensor_shapes(ms: synth.ModelShape) -> dict:
+    H, D, F = ms.hidden, ms.head_dim, ms.ffn
+    Nq, Nkv = ms.n_q_heads * D, ms.n_kv_heads * D
+    if ms.arch == binding.ARCH_OPT:
+        return dict(ln1_g=(H,), ln1_b=(H,), wq=(Nq, H), bq=(Nq,), wk=(Nkv, H), bk=(Nkv,), wv=(Nkv, H), bv=(Nkv,), wo=(H, Nq), bo=(H,),
+                    ln2_g=(H,), ln2_b=(H,), w_fc1=(F, H), b_fc1=(F,), w_fc2=(H, F), b_fc2=(H,))
+    return dict(g_attn=(H,), wq=(Nq, H), wk=(Nkv, H), wv=(Nkv, H), wo=(H, Nq), g_ffn=(H,), w_gate=(F, H), w_up=(F, H), w_down=(H, F))
+
+
+def measure_load_ms(ms: synth.ModelShape, depth: int) -> dict:
+    """The load column of Table 2 as far as one GPU can show it: a stage's parameters go from pinned
+    host memory to the GPU (one layer's worth of pinned buffers, copied once per layer: the contents do
+    not matter for the time) and fxp_stage_create re-tiles them into the stage's arena."""
+    dev = torch.device("cuda:0")
+    shapes = layer_tensor_shapes(ms)
+    host = {k: torch.zeros(shp, dtype=torch.bfloat16).pin_memory() for k, shp in shapes.items()}
+    layer_bytes = sum(t.numel() * 2 for t in host.values())
+    torch.cuda.synchronize()
+    e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    e[0].record()
+    layers = [{k: t.to(dev, non_blocking=True) for k, t in host.items()} for _ in range(depth)]
+    e[1].record()
+    stage = binding.Stage(ms, 0, depth, layers)
+    e[2].record()
+    torch.cuda.synchronize()
+    stage.close()
+    return {"bytes": layer_bytes * depth, "h2d_ms": e[0].elapsed_time(e[1]), "retile_ms": e[1].elapsed_time(e[2])}
+
+
+def max_batch(ms: synth.ModelShape, depth: int, ctx_len: int, hbm_bytes: float) -> int:
+    """Sequences of ctx_len cached tokens whose KV blocks fit next to the stage's weights (raw + re-tiled are not
+    both kept: the arena alone stays) in hbm_bytes."""
+    weights = ms.params_per_layer * 2 * depth
+    per_seq = -(-(ctx_len + 1) // 16) * ms.block_elems * 2 * depth
+    return int(max(0.0, hbm_bytes - weights) // per_seq)
+
+
 def main(argv=None) -> int:
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     ap.add_argument("--model", default="7b", choices=["7b", "opt66b"],
@@ -79,6 +116,8 @@ def main(argv=None) -> int:
     ap.add_argument("--alpha", type=float, default=0.5)
     ap.add_argument("--sigma", type=float, default=1.0)
     ap.add_argument("--cvs", default="0.25,1,2,4", help="traffic CVs to score")
+    ap.add_argument("--load", action="store_true", help="also time host-pinned -> GPU parameter load and re-tiling per stage")
+    ap.add_argument("--hbm-gb", type=float, default=288.0, help="device memory for the max-batch column")
     args = ap.parse_args(argv)
     ms = synth.OPT_66B if args.model == "opt66b" else synth.LLAMA2_7B
     if args.layers_total <= 0:
@@ -94,9 +133,14 @@ def main(argv=None) -> int:
         thr = args.batch / ((t + handoff_ms) * 1e-3)
         lat = n_stages * (t + handoff_ms)
         rows.append({"layers_per_stage": depth, "n_stages": n_stages, "compute_ms": t, "handoff_ms": handoff_ms,
-                     "throughput_tokens_s": thr, "latency_ms": lat})
+                     "throughput_tokens_s": thr, "latency_ms": lat, "max_batch_at_ctx_hi": max_batch(ms, depth, hi, args.hbm_gb * 1e9)})
         print(f"depth {depth:2d}: {n_stages:2d} stages, compute {t:7.3f} ms, hand-off {handoff_ms:6.3f} ms, "
               f"T = {thr:9.0f} tokens/s, L = {lat:7.2f} ms", file=sys.stderr, flush=True)
+        if args.load:
+            rows[-1]["load"] = measure_load_ms(ms, depth)
+            print(f"          load {rows[-1]['load']['bytes'] / 1e9:6.2f} GB: host -> GPU {rows[-1]['load']['h2d_ms']:8.1f} ms, "
+                  f"re-tile {rows[-1]['load']['retile_ms']:7.1f} ms; max batch at ctx {hi}: {rows[-1]['max_batch_at_ctx_hi']}",
+                  file=sys.stderr, flush=True)
         # nu_k: finer granularities suit burstier traffic; spread the candidates over the CV range scored
         cands.append(binding.Granularity(n_stages, args.batch, thr, lat, 0.0))
     cvs = [float(v) for v in args.cvs.split(",")]
