@@ -272,7 +272,7 @@ hipError_t launch_gemm_tiled(const TiledArgs &a, hipStream_t stream)
     const int blocks = ((tiles_n + 3) / 4) * ((tiles_m + 7) / 8);
     dim3 grid((blocks + 7) / 8 * 8 * 32, a.epilogue == kEpiPartial ? a.S : 1);
     if (tiles_m == 1) grid.x = tiles_n;
-    const bool tail = a.K % 32 != 0;
+    const bool tail = a.K % 64 != 0;                  // a stage is 64 wide: the token rows end inside the last one
 #define FXP_TG_LAUNCH(E)                                                                                       \
     if (tail) hipLaunchKernelGGL((gemm_tiled_kernel<E, true>), grid, dim3(kTgThreads), 0, stream, a);          \
     else hipLaunchKernelGGL((gemm_tiled_kernel<E, false>), grid, dim3(kTgThreads), 0, stream, a);

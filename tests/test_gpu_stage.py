@@ -30,6 +30,7 @@ OPT_TINY = synth.TINY_OPT                                                       
 OPT_GQA = synth.ModelShape(hidden=512, n_q_heads=8, n_kv_heads=2, head_dim=128, ffn=2048, arch=1)
 OPT_WIDE = synth.ModelShape(hidden=256, n_q_heads=4, n_kv_heads=4, head_dim=64, ffn=16400, arch=1)    # unsplit first projection with ReLU in its epilogue
 WIDE_FFN = synth.ModelShape(hidden=256, n_q_heads=4, n_kv_heads=4, head_dim=64, ffn=8208)   # gate|up wide enough for the unsplit, SwiGLU-fused projection
+ODD_K = synth.ModelShape(hidden=160, n_q_heads=2, n_kv_heads=2, head_dim=64, ffn=224)        # contraction lengths of 32 mod 64 (and heads narrower than hidden)
 
 
 class Case:
@@ -92,6 +93,7 @@ DECODE_CASES = [
     ("wide-ffn", WIDE_FFN, 2, [33, 200, 64, 7, 150]),             # SwiGLU in the projection epilogue, ragged last tile pair
     ("wide-ffn-40", WIDE_FFN, 1, list(range(5, 45))),
     ("batch-40", TINY, 1, list(range(5, 45))),                     # 3 row tiles, ragged
+    ("odd-k-batch-100", ODD_K, 1, [17 + (i * 7) % 90 for i in range(100)]),
     ("opt-tiny", OPT_TINY, 2, [37, 128, 32, 100]),
     ("opt-gqa", OPT_GQA, 2, [300, 1025, 31, 7, 64]),
     ("opt-wide-ffn", OPT_WIDE, 2, [33, 200, 64, 7, 150]),
@@ -118,6 +120,7 @@ PREFILL_CASES = [
     ("gqa64-prompts", GQA64, 1, [0, 5, 100], [130, 64, 17]),
     ("mid128-prompts", MID128, 2, [0, 129, 0], [200, 3, 65]),
     ("gqa128-8", GQA128, 1, [0, 40], [100, 90]),
+    ("odd-k-prompts", ODD_K, 2, [0, 0, 7], [150, 33, 60]),                  # hidden and ffn are 32 mod 64: the last 64-wide stage is half empty
     ("opt-prompts", OPT_TINY, 2, [0, 0, 0, 0], [37, 128, 32, 100]),
     ("opt-small", OPT_TINY, 2, [0, 0], [20, 45]),
     ("opt-chunked", OPT_GQA, 1, [16, 70, 33], [48, 10, 64]),
