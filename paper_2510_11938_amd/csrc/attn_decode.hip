@@ -492,8 +492,8 @@ __global__ __launch_bounds__(kDecThreads, 2) void attn_decode_mfma_kernel(Decode
 }
 
 // Merge the pieces of each (sequence, query head) in worker order and normalise:
-// o = sum_p acc_p 2^(m_p - m) / sum_p l_p 2^(m_p - m).  One workgroup per (sequence, query head),
-// one thread per dim.  The running maximum is carried along (as in the attention loop), so the
+// o = sum_p acc_p 2^(m_p - m) / sum_p l_p 2^(m_p - m).  One thread per dim of a (sequence, query head),
+// 512 / D heads per workgroup.  The running maximum is carried along (as in the attention loop), so the
 // maxima, sums and accumulators of a group of pieces are independent loads issued together: one
 // memory round trip per four pieces instead of three dependent ones per piece.
 template <bool DEBUG>
@@ -501,7 +501,9 @@ __global__ void attn_decode_combine_kernel(DecodeAttnArgs a)
 {
     constexpr int kGroup = 4;
     const int D = a.head_dim, G = a.n_q_heads / a.n_kv_heads, Hkv = a.n_kv_heads;
-    const int seq = blockIdx.x / a.n_q_heads, head = blockIdx.x % a.n_q_heads, hk = head / G, g = head % G;
+    const int row_id = blockIdx.x * (blockDim.x / D) + threadIdx.x / D;      // (sequence, query head), several per workgroup
+    if (row_id >= a.num_seqs * a.n_q_heads) return;
+    const int seq = row_id / a.n_q_heads, head = row_id % a.n_q_heads, hk = head / G, g = head % G;
     const int32_t before = a.blk_prefix[seq], total = a.blk_prefix[a.num_seqs];   // blocks (per head) before this sequence / in the batch
     const int n_keys = a.ctx_lens[seq] + 1;
     const int nb = (n_keys + kBlockTokens - 1) / kBlockTokens;
@@ -509,7 +511,7 @@ __global__ void attn_decode_combine_kernel(DecodeAttnArgs a)
     const int64_t u0 = (int64_t)before * Hkv + (int64_t)hk * nb;
     const int64_t w_first = worker_of(u0, U, W), w_last = worker_of(u0 + nb - 1, U, W);
     const int64_t pair = (int64_t)seq * Hkv + hk;
-    const int d = threadIdx.x;
+    const int d = threadIdx.x % D;
     float mm = -INFINITY, ll = 0.f, av = 0.f;
     for (int64_t w0 = w_first; w0 <= w_last; w0 += kGroup) {
         float m[kGroup], l[kGroup], ac[kGroup];
@@ -537,7 +539,7 @@ __global__ void attn_decode_combine_kernel(DecodeAttnArgs a)
     if constexpr (DEBUG) {
         // turn the stored scaled scores (log2 domain) into probabilities
         float *pr = a.dbg_scores + row * a.dbg_stride;
-        for (int r = threadIdx.x; r < n_keys; r += blockDim.x) pr[r] = fast_exp2(pr[r] - mm) / ll;
+        for (int r = d; r < n_keys; r += D) pr[r] = fast_exp2(pr[r] - mm) / ll;
     }
 }
 
@@ -553,9 +555,10 @@ static hipError_t launch_dg(const DecodeAttnArgs &a, hipStream_t stream)
 
 hipError_t launch_attn_decode_combine(const DecodeAttnArgs &a, hipStream_t stream)
 {
-    const dim3 cgrid(a.num_seqs * a.n_q_heads);
-    if (a.dbg_scores) hipLaunchKernelGGL(attn_decode_combine_kernel<true>, cgrid, dim3(a.head_dim), 0, stream, a);
-    else hipLaunchKernelGGL(attn_decode_combine_kernel<false>, cgrid, dim3(a.head_dim), 0, stream, a);
+    const int threads = 512, per_wg = threads / a.head_dim;      // query heads per workgroup: thousands of one-head workgroups take longer to launch than to run
+    const dim3 cgrid((a.num_seqs * a.n_q_heads + per_wg - 1) / per_wg);
+    if (a.dbg_scores) hipLaunchKernelGGL(attn_decode_combine_kernel<true>, cgrid, dim3(threads), 0, stream, a);
+    else hipLaunchKernelGGL(attn_decode_combine_kernel<false>, cgrid, dim3(threads), 0, stream, a);
     return hipGetLastError();
 }
 
