@@ -11,6 +11,11 @@
 //            worker streams the same number of blocks (+-1) whatever the length
 //            mix, and the whole grid starts and ends together.  The cut depends
 //            on the lengths only, never on the physical placement of blocks;
+//            (with head_group = Gs > 1 a worker is Gs neighbouring wavefronts of a
+//            workgroup and a unit one block of Gs adjacent kv heads: the wavefronts
+//            walk the same blocks at the same time, one head each, so the K runs
+//            they ask for are one contiguous Gs*4 KiB stretch of the cache, which
+//            HBM serves a few per cent faster than unrelated 4 KiB runs)
 //   piece  = the part of one (sequence, kv head) inside a worker's range; the
 //            worker leaves one partial softmax state (max, sum, acc[D]) per piece
 //            and a second kernel merges the pieces of each head in worker order.
@@ -26,6 +31,7 @@
 #include "kernels.h"
 #include "common.hip.h"
 #include <math.h>
+#include <stdlib.h>
 
 namespace fxp {
 
@@ -75,10 +81,12 @@ __global__ __launch_bounds__(kDecThreads) void attn_decode_kernel(DecodeAttnArgs
     int32_t *s_tbl = s_tbl_all[threadIdx.x >> 6];
 
     const int lane = threadIdx.x & 63;
-    const int Hkv = a.n_kv_heads;
-    const int64_t U = (int64_t)s_prefix[a.num_seqs] * Hkv;
-    const int64_t W = min((int64_t)gridDim.x * kDecWaves, U);       // never more workers than units: no empty ranges
-    const int64_t wk = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * kDecWaves + (threadIdx.x >> 6)));
+    const int Hkv = a.n_kv_heads, Gs = a.head_group, Hg = Hkv / Gs;
+    const int64_t U = (int64_t)s_prefix[a.num_seqs] * Hg;
+    const int64_t W = min((int64_t)gridDim.x * kDecWaves / Gs, U);  // never more workers than units: no empty ranges
+    const int wave_id = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * kDecWaves + (threadIdx.x >> 6)));
+    const int64_t wk = wave_id / Gs;                                 // worker: Gs neighbouring wavefronts, one head each
+    const int hi_w = wave_id % Gs;
     if (wk >= W) return;
     int64_t u = worker_begin(wk, U, W);
     const int64_t u_end = worker_begin(wk + 1, U, W);
@@ -89,20 +97,21 @@ __global__ __launch_bounds__(kDecThreads) void attn_decode_kernel(DecodeAttnArgs
     const int64_t unit_bytes = 2 * (int64_t)Hkv * head_bytes;
     const char *layer_base = reinterpret_cast<const char *>(a.pool) + (int64_t)a.layer_local * a.num_blocks * unit_bytes;
 
-    // sequence that owns unit u: prefix[seq]*Hkv <= u < prefix[seq+1]*Hkv
+    // sequence that owns unit u: prefix[seq]*Hg <= u < prefix[seq+1]*Hg
     int seq;
     {
         int lo = 0, hi = a.num_seqs;
-        while (hi - lo > 1) { const int mid = (lo + hi) >> 1; if ((int64_t)s_prefix[mid] * Hkv <= u) lo = mid; else hi = mid; }
+        while (hi - lo > 1) { const int mid = (lo + hi) >> 1; if ((int64_t)s_prefix[mid] * Hg <= u) lo = mid; else hi = mid; }
         seq = lo;
     }
 
     while (u < u_end) {
-        while ((int64_t)s_prefix[seq + 1] * Hkv <= u) ++seq;
+        while ((int64_t)s_prefix[seq + 1] * Hg <= u) ++seq;
         seq = __builtin_amdgcn_readfirstlane(seq);                       // wave-uniform: keep the piece's bookkeeping in scalar registers
         const int nb_seq = __builtin_amdgcn_readfirstlane(s_prefix[seq + 1] - s_prefix[seq]);
-        const int64_t r = u - (int64_t)__builtin_amdgcn_readfirstlane(s_prefix[seq]) * Hkv;
-        const int hk = (int)(r / nb_seq), blk0 = (int)(r % nb_seq);
+        const int64_t r = u - (int64_t)__builtin_amdgcn_readfirstlane(s_prefix[seq]) * Hg;
+        const int hg = (int)(r / nb_seq), blk0 = (int)(r % nb_seq);
+        const int hk = hg * Gs + hi_w;
         const int nblk = (int)min((int64_t)(nb_seq - blk0), u_end - u);  // blocks of this piece
         const int n_keys = a.ctx_lens[seq] + 1;                          // cached tokens + the one appended this step
         const int32_t *trow = a.block_table + (int64_t)seq * a.max_blocks_per_seq + blk0;
@@ -254,8 +263,8 @@ __global__ __launch_bounds__(kDecThreads) void attn_decode_kernel(DecodeAttnArgs
         }
 
         // merge the TPI lane groups (butterfly, lower group always the first operand) and store the piece
-        const int64_t pair = (int64_t)seq * Hkv + hk;
-        const int64_t slot = wk + pair;                  // unique: consecutive pieces differ in worker or in pair
+        // unique: consecutive pieces of a head differ in worker or in (sequence, head group), and never go back in either
+        const int64_t slot = (wk + (int64_t)seq * Hg + hg) * Gs + hi_w;
 #pragma unroll
         for (int g = 0; g < G; ++g) {
 #pragma unroll
@@ -320,9 +329,12 @@ __global__ __launch_bounds__(kDecThreads, 2) void attn_decode_mfma_kernel(Decode
     const int col = lane & 15, c = lane >> 4;
     const int Hkv = a.n_kv_heads, G = a.n_q_heads / Hkv;
     char *s_v = reinterpret_cast<char *>(s_dyn) + ((a.num_seqs + 1) * 4 + 255) / 256 * 256 + wave * (2 * kVBlock);
-    const int64_t U = (int64_t)s_prefix[a.num_seqs] * Hkv;
-    const int64_t W = min((int64_t)gridDim.x * kDecWaves, U);
-    const int64_t wk = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * kDecWaves + wave));
+    const int Gs = a.head_group, Hg = Hkv / Gs;
+    const int64_t U = (int64_t)s_prefix[a.num_seqs] * Hg;
+    const int64_t W = min((int64_t)gridDim.x * kDecWaves / Gs, U);
+    const int wave_id = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * kDecWaves + wave));
+    const int64_t wk = wave_id / Gs;                                 // worker: Gs neighbouring wavefronts, one kv head each
+    const int hi_w = wave_id % Gs;
     if (wk >= W) return;
     int64_t u = worker_begin(wk, U, W);
     const int64_t u_end = worker_begin(wk + 1, U, W);
@@ -335,7 +347,7 @@ __global__ __launch_bounds__(kDecThreads, 2) void attn_decode_mfma_kernel(Decode
     int seq;
     {
         int lo = 0, hi = a.num_seqs;
-        while (hi - lo > 1) { const int mid = (lo + hi) >> 1; if ((int64_t)s_prefix[mid] * Hkv <= u) lo = mid; else hi = mid; }
+        while (hi - lo > 1) { const int mid = (lo + hi) >> 1; if ((int64_t)s_prefix[mid] * Hg <= u) lo = mid; else hi = mid; }
         seq = lo;
     }
     // LDS addresses of this lane: where it stores V (row-major, 16 bytes per lane per load) and
@@ -344,11 +356,12 @@ __global__ __launch_bounds__(kDecThreads, 2) void attn_decode_mfma_kernel(Decode
     const int v_tr = (4 * c + (col >> 2)) * kVPitch + (col & 3) * 8;               // + dt*32 + block*kVBlock
 
     while (u < u_end) {
-        while ((int64_t)s_prefix[seq + 1] * Hkv <= u) ++seq;
+        while ((int64_t)s_prefix[seq + 1] * Hg <= u) ++seq;
         seq = __builtin_amdgcn_readfirstlane(seq);
         const int nb_seq = __builtin_amdgcn_readfirstlane(s_prefix[seq + 1] - s_prefix[seq]);
-        const int64_t r = u - (int64_t)__builtin_amdgcn_readfirstlane(s_prefix[seq]) * Hkv;
-        const int hk = (int)(r / nb_seq), blk0 = (int)(r % nb_seq);
+        const int64_t r = u - (int64_t)__builtin_amdgcn_readfirstlane(s_prefix[seq]) * Hg;
+        const int hg = (int)(r / nb_seq), blk0 = (int)(r % nb_seq);
+        const int hk = hg * Gs + hi_w;
         const int nblk = (int)min((int64_t)(nb_seq - blk0), u_end - u);
         const int n_keys = a.ctx_lens[seq] + 1;
         const int32_t *trow = a.block_table + (int64_t)seq * a.max_blocks_per_seq + blk0;
@@ -481,7 +494,7 @@ __global__ __launch_bounds__(kDecThreads, 2) void attn_decode_mfma_kernel(Decode
         l_tot += __shfl_xor(l_tot, 16, 64);
         l_tot += __shfl_xor(l_tot, 32, 64);
         if (col < G) {
-            const int64_t slot = wk + (int64_t)seq * Hkv + hk;
+            const int64_t slot = (wk + (int64_t)seq * Hg + hg) * Gs + hi_w;
             float *pa = a.part_acc + (slot * G + col) * D + 4 * c;
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt) *reinterpret_cast<f32x4_t *>(pa + dt * 16) = o[dt];
@@ -507,17 +520,18 @@ __global__ void attn_decode_combine_kernel(DecodeAttnArgs a)
     const int32_t before = a.blk_prefix[seq], total = a.blk_prefix[a.num_seqs];   // blocks (per head) before this sequence / in the batch
     const int n_keys = a.ctx_lens[seq] + 1;
     const int nb = (n_keys + kBlockTokens - 1) / kBlockTokens;
-    const int64_t U = (int64_t)total * Hkv, W = min((int64_t)a.n_workers, U);
-    const int64_t u0 = (int64_t)before * Hkv + (int64_t)hk * nb;
+    const int Gs = a.head_group, Hg = Hkv / Gs, hg = hk / Gs, hi_w = hk % Gs;
+    const int64_t U = (int64_t)total * Hg, W = min((int64_t)a.n_workers / Gs, U);
+    const int64_t u0 = (int64_t)before * Hg + (int64_t)hg * nb;
     const int64_t w_first = worker_of(u0, U, W), w_last = worker_of(u0 + nb - 1, U, W);
-    const int64_t pair = (int64_t)seq * Hkv + hk;
+    const int64_t pair = (int64_t)seq * Hg + hg;
     const int d = threadIdx.x % D;
     float mm = -INFINITY, ll = 0.f, av = 0.f;
     for (int64_t w0 = w_first; w0 <= w_last; w0 += kGroup) {
         float m[kGroup], l[kGroup], ac[kGroup];
 #pragma unroll
         for (int j = 0; j < kGroup; ++j) {
-            const int64_t piece = (min(w0 + j, w_last) + pair) * G + g;
+            const int64_t piece = ((min(w0 + j, w_last) + pair) * Gs + hi_w) * G + g;
             m[j] = a.part_ml[piece * 2];
             l[j] = a.part_ml[piece * 2 + 1];
             ac[j] = a.part_acc[piece * D + d];
@@ -560,6 +574,13 @@ hipError_t launch_attn_decode_combine(const DecodeAttnArgs &a, hipStream_t strea
     if (a.dbg_scores) hipLaunchKernelGGL(attn_decode_combine_kernel<true>, cgrid, dim3(threads), 0, stream, a);
     else hipLaunchKernelGGL(attn_decode_combine_kernel<false>, cgrid, dim3(threads), 0, stream, a);
     return hipGetLastError();
+}
+
+int decode_head_group(int n_kv_heads)
+{
+    static const int forced = getenv("FXP_DECODE_HEAD_GROUP") ? atoi(getenv("FXP_DECODE_HEAD_GROUP")) : 0;
+    if (forced > 0 && kDecWaves % forced == 0 && n_kv_heads % forced == 0) return forced;
+    return n_kv_heads % 4 == 0 ? 4 : (n_kv_heads % 2 == 0 ? 2 : 1);
 }
 
 bool decode_attn_supported(int head_dim, int group)

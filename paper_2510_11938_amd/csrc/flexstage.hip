@@ -543,7 +543,7 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
             aa.part_acc = w.part_acc; aa.part_ml = w.part_ml; aa.out = w.o; aa.dbg_scores = dbg; aa.dbg_stride = probs_stride;
             aa.num_blocks = pool->num_blocks; aa.num_seqs = B; aa.max_blocks_per_seq = batch->max_blocks_per_seq;
             aa.n_workers = w.n_workers; aa.layer_local = ll; aa.n_q_heads = d.n_q_heads; aa.n_kv_heads = d.n_kv_heads;
-            aa.head_dim = D; aa.scale_log2e = scale_log2e;
+            aa.head_dim = D; aa.scale_log2e = scale_log2e; aa.head_group = fxp::decode_head_group(d.n_kv_heads);
             {
                 KernelTimer kt(kKcAttnDecode, st);
                 if ((e = fxp::launch_attn_decode(aa, st))) return hip_fail(e, "decode attention");

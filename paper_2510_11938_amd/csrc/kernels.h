@@ -138,8 +138,10 @@ struct DecodeAttnArgs {
     int64_t num_blocks;
     int num_seqs, max_blocks_per_seq, n_workers, layer_local;   // n_workers: multiple of 4
     int n_q_heads, n_kv_heads, head_dim;
+    int head_group;        // kv heads (= wavefronts) per worker: 4, 2 or 1, a divisor of n_kv_heads
     float scale_log2e;     // log2(e) / sqrt(D)
 };
+int decode_head_group(int n_kv_heads);
 bool decode_attn_supported(int head_dim, int group);
 hipError_t launch_attn_decode(const DecodeAttnArgs &a, hipStream_t stream);          // per-split partial results
 hipError_t launch_attn_decode_combine(const DecodeAttnArgs &a, hipStream_t stream);  // merge of the splits
