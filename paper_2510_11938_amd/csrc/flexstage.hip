@@ -32,7 +32,7 @@ int hip_fail(hipError_t e, const char *what)
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline int k_steps(int K) { return (K + 63) / 64 * 2; }                   // 32-wide steps, K padded to 64
-inline size_t packed_bytes(int N, int K) { return (size_t)(N / 16) * k_steps(K) * 1024; }
+inline size_t packed_bytes(int N, int K) { return (size_t)((N / 16 + fxp::kPackGroup - 1) / fxp::kPackGroup * fxp::kPackGroup) * k_steps(K) * 1024; }   // whole groups of tiles
 
 constexpr int kSkinnyMaxTokens = 128;     // up to here the projections run weight-streaming with split-K
 constexpr int kSkinnyWideTokens = 64;     // above this the split-K work goes to the tiled kernel's 128-row tile

@@ -41,7 +41,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(SkinnyArgs a)
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int nt = min(nt0 + r, a.NT - 1);        // tiles past the end are clamped and never stored
-        wp[r] = reinterpret_cast<const u32x4 *>(a.W) + (int64_t)nt * a.KS * 64 + lane;
+        wp[r] = reinterpret_cast<const u32x4 *>(a.W) + packed_operand(nt, 0, a.KS) + lane;
     }
 
     // Staging of the token rows: chunk q of a group is the 16 bytes that lane q%64 feeds to the
@@ -75,7 +75,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(SkinnyArgs a)
         for (int u = 0; u < U; ++u) {
             const int ksc = min(ks_begin + g * U + u, ks_end - 1);
 #pragma unroll
-            for (int r = 0; r < R; ++r) w[u][r] = __builtin_nontemporal_load(wp[r] + (int64_t)ksc * 64);
+            for (int r = 0; r < R; ++r) w[u][r] = __builtin_nontemporal_load(wp[r] + (int64_t)ksc * kPackStepStride);
         }
     };
     // (the zeroing of k-steps past the range happens when the rows are stored to LDS, a group later:

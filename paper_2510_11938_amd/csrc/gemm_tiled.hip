@@ -70,7 +70,7 @@ __global__ __launch_bounds__(kTgThreads, 2) void gemm_tiled_kernel(TiledArgs a)
     const u32x4 *wp[kTgRn];
 #pragma unroll
     for (int r = 0; r < kTgRn; ++r)
-        wp[r] = reinterpret_cast<const u32x4 *>(a.W) + (int64_t)min(nt0 + r, a.NT - 1) * KS * 64 + lane;
+        wp[r] = reinterpret_cast<const u32x4 *>(a.W) + packed_operand(min(nt0 + r, a.NT - 1), 0, KS) + lane;
 
     // Staging map.  Global side: chunk q = i*256 + tid is 16 bytes of token row q/8, k-chunk q%8
     // of the 64-wide stage, so 8 consecutive lanes fetch one full 128-byte line (a wave
@@ -104,7 +104,7 @@ __global__ __launch_bounds__(kTgThreads, 2) void gemm_tiled_kernel(TiledArgs a)
     auto fetch_w = [&](u32x4(&w)[kTgRn], int ks) {
         const int ksc = 2 * kt0 + min(ks, 2 * KT - 1);
 #pragma unroll
-        for (int r = 0; r < kTgRn; ++r) w[r] = wp[r][(int64_t)ksc * 64];
+        for (int r = 0; r < kTgRn; ++r) w[r] = wp[r][(int64_t)ksc * kPackStepStride];
     };
     auto fetch_x = [&](u32x4(&x)[kTgXPerThread], int kt) {
         const int ktc = kt0 + min(kt, KT - 1);

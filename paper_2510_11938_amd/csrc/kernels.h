@@ -37,7 +37,17 @@ hipError_t launch_kv_move(const KvMoveArgs &args, int grid, hipStream_t stream);
 int kv_move_chunk_bytes();     // bytes of one work item
 
 // ---------------------------------------------------------------- weights
-// W[N][K] row-major bf16 -> packed[n_tile][k_step][lane][8] (k zero-padded to k_steps*32).
+// W[N][K] row-major bf16 -> packed[n_tile / 8][k_step][n_tile % 8][lane][8] (k zero-padded to k_steps*32):
+// one MFMA row operand (16 rows x 32 k) is 1 KiB, and the eight 16-row tiles that the wavefronts of a
+// workgroup multiply in the same k-step lie next to each other, so what a workgroup asks for at one
+// time is one contiguous stretch (HBM serves that a few per cent faster than scattered 1-2 KiB runs).
+constexpr int kPackGroup = 8;
+// index, in 16-byte chunks, of lane 0 of the operand (tile nt, k-step ks) of a matrix with KS k-steps
+__host__ __device__ inline int64_t packed_operand(int nt, int ks, int KS)
+{
+    return (((int64_t)(nt / kPackGroup) * KS + ks) * kPackGroup + nt % kPackGroup) * 64;
+}
+constexpr int kPackStepStride = kPackGroup * 64;      // chunks between consecutive k-steps of one tile
 hipError_t launch_weight_pack(const void *src, int N, int K, void *dst, int k_steps,
                               int tile_offset, int tile_stride, hipStream_t stream);
 

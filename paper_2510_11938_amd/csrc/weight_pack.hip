@@ -4,10 +4,11 @@
 // weight matrix as the row operand of v_mfma_f32_16x16x32_bf16.  That operand
 // wants, per lane l of the wavefront, the 8 consecutive k values
 // k0 + 8*(l/16) .. +7 of row n0 + l%16.  Stored in that order,
-//     packed[n_tile][k_step][lane][8],   n_tile = n/16, k_step = k/32,
-// one operand is one contiguous 1 KiB read (16 bytes per lane) and a 16-row
-// slab of W is one contiguous stream: the layout weight streaming wants when
-// the token count is small and the projection is bound by HBM.
+//     packed[n_tile / 8][k_step][n_tile % 8][lane][8],   n_tile = n/16, k_step = k/32,
+// one operand is one contiguous 1 KiB read (16 bytes per lane) and a 128-row
+// slab of W is one contiguous stream in the order a workgroup consumes it: the
+// layout weight streaming wants when the token count is small and the
+// projection is bound by HBM.
 //
 // K is zero-padded to a multiple of 64.  Rows can be placed at a tile offset
 // with a tile stride, which is how Wq|Wk|Wv are concatenated (stride 1) and how
@@ -33,7 +34,7 @@ __global__ __launch_bounds__(256) void weight_pack_kernel(const uint16_t *__rest
         u32x4 v = {0u, 0u, 0u, 0u};
         if (k + 8 <= K) v = ld16(src + (int64_t)n * K + k);
         const int64_t ntd = (int64_t)tile_offset + (int64_t)nts * tile_stride;
-        st16(dst + ((ntd * k_steps + ks) * 64 + lane) * 8, v);
+        st16(dst + (packed_operand((int)ntd, ks, k_steps) + lane) * 8, v);
     }
 }
 

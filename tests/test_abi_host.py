@@ -35,8 +35,9 @@ def test_arena_and_packed_sizes_are_host_computations():
     # per layer: every matrix re-tiled with k padded to 64, plus the two gains
     per_layer = 2 * (ms.qkv_out * 4096 + 4096 * 4096 + 2 * 11008 * 4096 + 4096 * 11008) + 2 * 4096 * 2
     assert lib.fxp_stage_weight_arena_bytes(C.byref(d)) == 4 * per_layer
-    tiny = binding.make_desc(synth.TINY, 0, 1)          # ffn 688 is padded to 704 as the k of the down projection
-    assert lib.fxp_stage_weight_arena_bytes(C.byref(tiny)) == 2 * (768 * 256 + 256 * 256 + 1376 * 256 + 256 * 704) + 2 * 512
+    # ffn 688 is padded to 704 as the k of the down projection; the 1376 gate|up rows take whole groups of 8 x 16 rows (1408)
+    tiny = binding.make_desc(synth.TINY, 0, 1)
+    assert lib.fxp_stage_weight_arena_bytes(C.byref(tiny)) == 2 * (768 * 256 + 256 * 256 + 1408 * 256 + 256 * 704) + 2 * 512
     lens = np.array([1, 16, 17, 0, 4096], dtype=np.int32)
     assert binding.kv_packed_bytes(ms, 2, 4, lens) == (1 + 1 + 2 + 0 + 256) * 2 * (2 * 32 * 16 * 128 * 2)
 
