@@ -215,10 +215,17 @@ hipError_t launch_swiglu(const SwigluArgs &a, hipStream_t stream)
 // evaluated in double (it reaches thousands of radians; float would lose the low
 // bits before the range reduction).  Positions are the same for every layer of
 // the stage, so this runs once per forward call.
-constexpr int kRopeTableThreads = 128;
+constexpr int kRopeTableThreads = kRowThreads;
 
 __global__ __launch_bounds__(kRopeTableThreads) void rope_table_kernel(RopeTableArgs a)
 {
+    if ((int)blockIdx.x >= a.T) {
+        // workgroups past the tokens: the first layer's attention norm, one row each
+        __shared__ float red[kRowThreads / 64];
+        const int64_t row = (int64_t)(blockIdx.x - a.T) * a.norm_H;
+        norm_row<kRowThreads>(a.norm_x + row, a.norm_g, a.norm_b, a.norm_out + row, a.norm_H, a.norm_eps, -1.f, red);
+        return;
+    }
     __shared__ int s_seq, s_pos;
     const int t = blockIdx.x, half = a.head_dim / 2;
     if (threadIdx.x == 0) {
@@ -262,7 +269,7 @@ __global__ __launch_bounds__(kRopeTableThreads) void rope_table_kernel(RopeTable
 
 hipError_t launch_rope_table(const RopeTableArgs &a, hipStream_t stream)
 {
-    hipLaunchKernelGGL(rope_table_kernel, dim3(a.T), dim3(kRopeTableThreads), 0, stream, a);
+    hipLaunchKernelGGL(rope_table_kernel, dim3(a.norm_x ? 2 * a.T : a.T), dim3(kRopeTableThreads), 0, stream, a);
     return hipGetLastError();
 }
 

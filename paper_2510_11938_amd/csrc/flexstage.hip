@@ -495,6 +495,10 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
         rt.cu_seqlens_q = batch->cu_seqlens_q; rt.ctx_lens = batch->ctx_lens; rt.tok_seq = w.tok_seq; rt.tok_pos = w.tok_pos; rt.blk_prefix = w.blk_prefix;
         rt.cs = w.rope_cs; rt.sn = w.rope_sn; rt.T = T; rt.num_seqs = B; rt.head_dim = D; rt.rope_base = d.rope_base;
         rt.identity = opt ? 1 : 0;
+        // the attention norm of the stage's first layer goes with it
+        rt.norm_x = (const uint16_t *)hidden_in; rt.norm_g = (const uint16_t *)(stage->arena + stage->rec.g_attn);
+        rt.norm_b = opt ? (const uint16_t *)(stage->arena + stage->rec.b_attn) : nullptr;
+        rt.norm_out = w.n; rt.norm_H = H; rt.norm_eps = d.rms_eps;
         KernelTimer kt(kKcRopeTable, st);
         if ((e = fxp::launch_rope_table(rt, st))) return hip_fail(e, "rope table");
     }
@@ -510,8 +514,9 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
         float *dbg = probs ? probs + (int64_t)ll * T * d.n_q_heads * probs_stride : nullptr;
         int S = 1;
 
-        // attention norm (layers after the first get it from the previous layer's fused epilogue on the skinny path)
-        if (!skinny || ll == 0) {
+        // attention norm (the first layer's came with the rope table; later layers get it from the previous layer's
+        // fused epilogue on the skinny path)
+        if (!skinny && ll > 0) {
             KernelTimer kt(kKcRmsnorm, st);
             if ((e = fxp::launch_rmsnorm(x_cur, g_attn, b_attn, w.n, T, H, d.rms_eps, st))) return hip_fail(e, "rmsnorm");
         }

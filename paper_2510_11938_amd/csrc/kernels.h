@@ -114,6 +114,11 @@ struct RopeTableArgs {
     int T, num_seqs, head_dim;
     float rope_base;
     int identity;                 // 1: no rotary embedding (cos = 1, sin = 0)
+    // the first layer's attention norm rides in the same launch (one launch less per step); skipped when norm_x is null
+    const uint16_t *norm_x, *norm_g, *norm_b;   // rows [T][norm_H], gain, optional LayerNorm bias
+    uint16_t *norm_out;
+    int norm_H;
+    float norm_eps;
 };
 hipError_t launch_rope_table(const RopeTableArgs &a, hipStream_t stream);
 
