@@ -30,6 +30,8 @@ OPT_TINY = synth.TINY_OPT                                                       
 OPT_GQA = synth.ModelShape(hidden=512, n_q_heads=8, n_kv_heads=2, head_dim=128, ffn=2048, arch=1)
 OPT_WIDE = synth.ModelShape(hidden=256, n_q_heads=4, n_kv_heads=4, head_dim=64, ffn=16400, arch=1)    # unsplit first projection with ReLU in its epilogue
 WIDE_FFN = synth.ModelShape(hidden=256, n_q_heads=4, n_kv_heads=4, head_dim=64, ffn=8208)   # gate|up wide enough for the unsplit, SwiGLU-fused projection
+KV6 = synth.ModelShape(hidden=384, n_q_heads=6, n_kv_heads=6, head_dim=64, ffn=512)            # kv heads in groups of two per decode worker
+GQA_KV3 = synth.ModelShape(hidden=384, n_q_heads=6, n_kv_heads=3, head_dim=64, ffn=512)        # an odd number of kv heads: one per worker
 ODD_K = synth.ModelShape(hidden=160, n_q_heads=2, n_kv_heads=2, head_dim=64, ffn=224)        # contraction lengths of 32 mod 64 (and heads narrower than hidden)
 
 
@@ -92,6 +94,8 @@ DECODE_CASES = [
     ("gqa128-8", GQA128, 1, [300, 1025, 31]),
     ("wide-ffn", WIDE_FFN, 2, [33, 200, 64, 7, 150]),             # SwiGLU in the projection epilogue, ragged last tile pair
     ("wide-ffn-40", WIDE_FFN, 1, list(range(5, 45))),
+    ("kv6", KV6, 1, [900, 33, 2049, 16, 15, 700]),
+    ("gqa-kv3", GQA_KV3, 1, [900, 33, 2049, 16, 15, 700]),
     ("batch-40", TINY, 1, list(range(5, 45))),                     # 3 row tiles, ragged
     ("odd-k-batch-100", ODD_K, 1, [17 + (i * 7) % 90 for i in range(100)]),
     ("opt-tiny", OPT_TINY, 2, [37, 128, 32, 100]),
