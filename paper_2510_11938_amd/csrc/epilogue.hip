@@ -134,17 +134,16 @@ hipError_t launch_rmsnorm(const void *x, const void *g, const void *b, void *out
 }
 
 // ---------------------------------------------------------------- residual (+ norm)
-// (512 threads: at hidden 4096 every thread owns one 8-wide chunk, so all partial-sum loads of
-// a row are in flight at once)
-constexpr int kNormThreads = 512;
-
-__global__ __launch_bounds__(kNormThreads) void resid_norm_kernel(ResidNormArgs a)
+// (512 threads at hidden 4096, 1024 above: every thread owns one 8-wide chunk, so all partial-sum
+// loads of a row are in flight at once)
+template <int THREADS>
+__global__ __launch_bounds__(THREADS) void resid_norm_kernel(ResidNormArgs a)
 {
-    __shared__ float red[kNormThreads / 64];
+    __shared__ float red[THREADS / 64];
     const int t = blockIdx.x;
     const int64_t row = (int64_t)t * a.H;
     float ss = 0.f;
-    for (int c = threadIdx.x; c < a.H / 8; c += kNormThreads) {
+    for (int c = threadIdx.x; c < a.H / 8; c += THREADS) {
         float f[8], p[8];
         unpack8(ld16(a.x + row + c * 8), f);
         partial8(a.P, a.S, (int64_t)a.T * a.H, row + c * 8, p);
@@ -164,13 +163,14 @@ __global__ __launch_bounds__(kNormThreads) void resid_norm_kernel(ResidNormArgs 
     }
     if (!a.g) return;
     // (every thread reads back only the chunks it wrote itself)
-    if (a.nb) norm_row<kNormThreads>(a.h + row, a.g, a.nb, a.n + row, a.H, a.eps, -1.f, red);
-    else norm_row<kNormThreads>(a.h + row, a.g, nullptr, a.n + row, a.H, a.eps, block_sum<kNormThreads>(ss, red), red);
+    if (a.nb) norm_row<THREADS>(a.h + row, a.g, a.nb, a.n + row, a.H, a.eps, -1.f, red);
+    else norm_row<THREADS>(a.h + row, a.g, nullptr, a.n + row, a.H, a.eps, block_sum<THREADS>(ss, red), red);
 }
 
 hipError_t launch_resid_norm(const ResidNormArgs &a, hipStream_t stream)
 {
-    hipLaunchKernelGGL(resid_norm_kernel, dim3(a.T), dim3(kNormThreads), 0, stream, a);
+    if (a.H / 8 > 512) hipLaunchKernelGGL(resid_norm_kernel<1024>, dim3(a.T), dim3(1024), 0, stream, a);
+    else hipLaunchKernelGGL(resid_norm_kernel<512>, dim3(a.T), dim3(512), 0, stream, a);
     return hipGetLastError();
 }
 
