@@ -12,8 +12,9 @@
 //     once per workgroup through LDS in operand order (the 4 wavefronts of a
 //     workgroup share the k range) and re-used across the R tiles: fetching them
 //     per wavefront cost as much L2 bandwidth as the weights themselves;
-//   - two register buffers of U k-steps each keep 2*U*R KiB of weights in flight
-//     per wavefront while the other buffer is consumed;
+//   - a ring of NB register buffers of U k-steps each (weights and the token rows
+//     of the same group) keeps (NB-1)*U*R KiB of weights in flight per wavefront
+//     while one buffer is consumed;
 //   - split-K across workgroups fills all 256 CUs; partial sums go to a float
 //     buffer and are reduced in fixed order by the fused epilogue kernels, so
 //     the result is deterministic (no atomics).  The gate|up projection is wide
