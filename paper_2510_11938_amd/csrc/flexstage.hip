@@ -137,11 +137,12 @@ SkinnyCfg skinny_cfg(int N, int K, int M)
     // hence power-of-two splits.
     c.R = forced_r ? forced_r : ((N >= 16384 && M <= 64) ? 4 : 2);
     if (M > kSkinnyWideTokens) {
-        // 65..128 rows go through the tiled kernel, whose workgroup covers 256 weight rows: one
-        // workgroup per CU of a 256-CU chip and never more (a second one on a quarter of the CUs
-        // doubles the time of the launch; measured: 320 workgroups 57 us, 240 workgroups 45 us)
-        const int wgs_n = (N + 255) / 256;
-        c.S = forced_s ? forced_s : std::max(1, std::min(std::min(8, ks / 8), 256 / wgs_n));
+        // above 64 rows the tiled kernel is used, whose workgroup covers 256 weight rows x 128 token rows: one
+        // workgroup per CU of a 256-CU chip and never more (a second one on a quarter of the CUs doubles the
+        // time of the launch; measured: 320 workgroups 57 us, 240 workgroups 45 us).  With several hundred
+        // token rows a narrow matrix still has few tiles (hidden 4096: 16 x rows/128) and is split as well.
+        const int wgs = ((N + 255) / 256) * ((M + 127) / 128);
+        c.S = forced_s ? forced_s : std::max(1, std::min(std::min(8, ks / 8), 256 / wgs));
         return c;
     }
     const int wgs_n = (N + 64 * c.R - 1) / (64 * c.R);
@@ -233,13 +234,19 @@ Workspace carve(const fxp_stage_desc &d, int T, int B, int max_blocks, char *bas
     w.qkv = (uint16_t *)take(T > kSkinnyMaxTokens ? t * Nall * 2 : 0);
     size_t pmax = 0;
     const int shapes[4][2] = {{Nall, H}, {H, Nq}, {2 * F, H}, {H, F}};
-    const int row_classes[3] = {32, kSkinnyWideTokens, kSkinnyMaxTokens};     // the split factor is chosen per class of row counts
     for (auto &s : shapes) {
-        // sized for every batch of up to T rows, so that a workspace for max_tokens serves smaller calls too
-        for (int rc : row_classes) {
-            const int m = std::min(rc, T > 0 ? T : 1);
+        // sized for every batch of up to T rows, so that a workspace for max_tokens serves smaller calls too: the split
+        // factor is chosen per class of row counts (<= 32, <= 64, then per 128-row tile until the matrix alone fills the chip)
+        auto need = [&](int m) {
+            m = std::min(m, T > 0 ? T : 1);
             const size_t b = (size_t)choose_split(s[0], s[1], m) * m * s[0] * 4;
             if (b > pmax) pmax = b;
+        };
+        need(32);
+        need(kSkinnyWideTokens);
+        for (int tm = 1; tm <= 256; ++tm) {
+            need(tm * 128);
+            if (tm * 128 >= T || choose_split(s[0], s[1], tm * 128) == 1) break;
         }
     }
     w.P = (float *)take(pmax);
@@ -503,6 +510,7 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
         if ((e = fxp::launch_rope_table(rt, st))) return hip_fail(e, "rope table");
     }
     const uint16_t *x_cur = (const uint16_t *)hidden_in;
+    bool n_ready = true;        // w.n holds the attention norm of the layer's input (the first layer's came with the rope table)
     for (int ll = 0; ll < stage->n_layers; ++ll) {
         const char *rec = stage->arena + stage->rec.bytes * (size_t)ll;
         const uint16_t *g_attn = (const uint16_t *)(rec + stage->rec.g_attn), *g_ffn = (const uint16_t *)(rec + stage->rec.g_ffn);
@@ -514,9 +522,18 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
         float *dbg = probs ? probs + (int64_t)ll * T * d.n_q_heads * probs_stride : nullptr;
         int S = 1;
 
-        // attention norm (the first layer's came with the rope table; later layers get it from the previous layer's
-        // fused epilogue on the skinny path)
-        if (!skinny && ll > 0) {
+        // Each projection either fills the chip by itself and finishes in its own epilogue (bf16 store, residual,
+        // activation), or is split along k and leaves float partial sums that the row kernel behind it reduces
+        // (together with rotary embedding / residual / norm / activation): always up to 128 rows, and above that
+        // for matrices with too few tiles (a 4096-wide output has 16 x rows/128 of them).
+        const int Nup = opt ? F : 2 * F;
+        const bool part_qkv = skinny || skinny_cfg(Nall, H, T).S > 1;
+        const bool part_o = skinny || skinny_cfg(H, Nq, T).S > 1;
+        const bool part_down = skinny || skinny_cfg(H, F, T).S > 1;
+
+        // attention norm (the first layer's came with the rope table; later ones come from the previous layer's
+        // residual kernel when its down projection was split)
+        if (!n_ready) {
             KernelTimer kt(kKcRmsnorm, st);
             if ((e = fxp::launch_rmsnorm(x_cur, g_attn, b_attn, w.n, T, H, d.rms_eps, st))) return hip_fail(e, "rmsnorm");
         }
@@ -524,7 +541,7 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
         // q|k|v projection, rotary embedding, cache append
         fxp::RopeArgs ra;
         ra.P = nullptr; ra.qkv = nullptr; ra.S = 1; ra.bias = nullptr;
-        if (skinny) {
+        if (part_qkv) {
             if ((e = project_skinny(rec + stage->rec.wqkv, w.n, Nall, H, H, &S))) return hip_fail(e, "qkv projection");
             ra.P = w.P; ra.S = S; ra.bias = b_qkv;
         } else {
@@ -568,26 +585,29 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
             if ((e = fxp::launch_attn_prefill(pa, st))) return hip_fail(e, "prefill attention");
         }
 
-        if (skinny) {
-            // output projection + residual, fused with the feed-forward norm
+        // output projection + residual, then the feed-forward norm
+        fxp::ResidNormArgs rn;
+        rn.T = T; rn.H = H; rn.eps = d.rms_eps; rn.P = w.P;
+        if (part_o) {
             if ((e = project_skinny(rec + stage->rec.wo, w.o, H, Nq, Nq, &S))) return hip_fail(e, "output projection");
-            fxp::ResidNormArgs rn;
-            rn.x = x_cur; rn.P = w.P; rn.h = w.h; rn.g = g_ffn; rn.n = w.n; rn.T = T; rn.H = H; rn.S = S; rn.eps = d.rms_eps;
-            rn.bias = b_o; rn.nb = b_ffn;
-            {
-                KernelTimer kt(kKcResidNorm, st);
-                if ((e = fxp::launch_resid_norm(rn, st))) return hip_fail(e, "residual + norm");
-            }
-            // gate|up projection + SwiGLU
-            // (up to 64 rows the projection is wide enough to fill the chip without split-K and
-            // applies SwiGLU itself; above, the split partial sums go through the SwiGLU kernel)
-            // (an OPT-style layer has one matrix here and relu(sum + bias) as activation)
-            const int Nup = opt ? F : 2 * F;
-            const bool wide_unsplit = T > kSkinnyWideTokens && skinny_cfg(Nup, H, T).S == 1;
-            const bool fused_act = wide_unsplit || (T <= kSkinnyWideTokens && skinny_fused_swiglu(Nup));
-            if (wide_unsplit) {
-                // 65..128 rows and a matrix that fills the chip without a split: the tiled kernel's own activation epilogue
-                if ((e = project_tiled(rec + stage->rec.wgu, w.n, Nup, H, H, w.a, F, nullptr, opt ? fxp::kEpiRelu : fxp::kEpiSwiglu, b_up, kKcSkinny)))
+            rn.x = x_cur; rn.h = w.h; rn.g = g_ffn; rn.n = w.n; rn.S = S; rn.bias = b_o; rn.nb = b_ffn;
+            KernelTimer kt(kKcResidNorm, st);
+            if ((e = fxp::launch_resid_norm(rn, st))) return hip_fail(e, "residual + norm");
+        } else {
+            if ((e = project_tiled(rec + stage->rec.wo, w.o, H, Nq, Nq, w.h, H, x_cur, fxp::kEpiResidual, b_o))) return hip_fail(e, "output projection");
+            KernelTimer kt(kKcRmsnorm, st);
+            if ((e = fxp::launch_rmsnorm(w.h, g_ffn, b_ffn, w.n, T, H, d.rms_eps, st))) return hip_fail(e, "rmsnorm");
+        }
+
+        // gate|up projection + SwiGLU (an OPT-style layer has one matrix here and relu(sum + bias) as activation).
+        // Up to 64 rows the weight-streaming kernel applies the activation itself when the matrix fills the chip
+        // unsplit; above, the tiled kernel does when it is unsplit; split partial sums go through the activation kernel.
+        {
+            const bool tiled_unsplit = T > kSkinnyWideTokens && skinny_cfg(Nup, H, T).S == 1;
+            const bool fused_act = tiled_unsplit || (T <= kSkinnyWideTokens && skinny_fused_swiglu(Nup));
+            if (tiled_unsplit) {
+                if ((e = project_tiled(rec + stage->rec.wgu, w.n, Nup, H, H, w.a, F, nullptr, opt ? fxp::kEpiRelu : fxp::kEpiSwiglu, b_up,
+                                       skinny ? kKcSkinny : kKcTiled)))
                     return hip_fail(e, "gate/up projection");
             } else if ((e = project_skinny(rec + stage->rec.wgu, w.n, Nup, H, H, &S, fused_act ? w.a : nullptr, b_up))) {
                 return hip_fail(e, "gate/up projection");
@@ -598,28 +618,20 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
                 KernelTimer kt(kKcSwiglu, st);
                 if ((e = fxp::launch_swiglu(sg, st))) return hip_fail(e, "swiglu");
             }
-            // down projection + residual, fused with the next layer's attention norm
+        }
+
+        // down projection + residual; split: fused with the next layer's attention norm
+        if (part_down) {
             if ((e = project_skinny(rec + stage->rec.wd, w.a, H, F, F, &S))) return hip_fail(e, "down projection");
-            rn.x = w.h; rn.P = w.P; rn.h = x_next; rn.S = S; rn.bias = b_down;
+            rn.x = w.h; rn.h = x_next; rn.S = S; rn.bias = b_down; rn.n = w.n;
             rn.g = last ? nullptr : (const uint16_t *)(rec + stage->rec.bytes + stage->rec.g_attn);
             rn.nb = (last || !opt) ? nullptr : (const uint16_t *)(rec + stage->rec.bytes + stage->rec.b_attn);
-            rn.n = w.n;
-            {
-                KernelTimer kt(kKcResidNorm, st);
-                if ((e = fxp::launch_resid_norm(rn, st))) return hip_fail(e, "residual + norm");
-            }
+            KernelTimer kt(kKcResidNorm, st);
+            if ((e = fxp::launch_resid_norm(rn, st))) return hip_fail(e, "residual + norm");
+            n_ready = true;
         } else {
-            if ((e = project_tiled(rec + stage->rec.wo, w.o, H, Nq, Nq, w.h, H, x_cur, fxp::kEpiResidual, b_o))) return hip_fail(e, "output projection");
-            {
-                KernelTimer kt(kKcRmsnorm, st);
-                if ((e = fxp::launch_rmsnorm(w.h, g_ffn, b_ffn, w.n, T, H, d.rms_eps, st))) return hip_fail(e, "rmsnorm");
-            }
-            if (opt) {
-                if ((e = project_tiled(rec + stage->rec.wgu, w.n, F, H, H, w.a, F, nullptr, fxp::kEpiRelu, b_up))) return hip_fail(e, "first feed-forward projection");
-            } else {
-                if ((e = project_tiled(rec + stage->rec.wgu, w.n, 2 * F, H, H, w.a, F, nullptr, fxp::kEpiSwiglu))) return hip_fail(e, "gate/up projection");
-            }
             if ((e = project_tiled(rec + stage->rec.wd, w.a, H, F, F, x_next, H, w.h, fxp::kEpiResidual, b_down))) return hip_fail(e, "down projection");
+            n_ready = false;
         }
         x_cur = x_next;
     }
