@@ -71,3 +71,31 @@ def test_13b_shape_decode_batch_64_then_resplit_sampled_against_oracle():
                 want[:, -1, :, :, tail:, :] = 0
             assert torch.equal(dv.pool[:, db], want), f"stage {s} sequence {i}"
         assert bool((dv.pool[:, ~owned] == 0x2222).all())
+
+
+def test_7b_shape_prefill_chunk_of_514_tokens_sampled_against_oracle():
+    # hidden 4096, 32 x 128 heads, ffn 11008; three prompts of 300 + 150 + 64 tokens in one call, 1 layer: between 128 and
+    # 1024 rows the narrow projections (o, down) are split along k and finished by the row kernels, the wide ones are not
+    ms = synth.WORKLOADS["C3"].shape
+    seed, lens = 21, np.array([300, 150, 64], dtype=np.int32)
+    T = int(lens.sum())
+    table, nblk = synth.block_table(lens, 16, seed)
+    w = make_weights(ms, seed, 1, want_f32=False)
+    hidden_bits = synth.hidden_states(T, ms.hidden, seed)
+    stage = make_stage(ms, w, 0, 1)
+    pool = torch.zeros((1, nblk, 2, ms.n_kv_heads, 16, ms.head_dim), dtype=torch.int16, device="cuda")
+    cache = binding.KVCache(pool, 0, 1, dev_i32(table))
+    cu = synth.cu_seqlens(lens)
+    y = stage.forward(cache, dev_i32(cu), dev_i32(np.zeros(3)), dev_bf16(hidden_bits), int(lens.max()))
+    torch.cuda.synchronize()
+    got = host_f64(y)
+    assert np.isfinite(got).all()
+    osh = oracle_shape(ms)
+    wf = [{k: synth.bf16_bits_to_f32(v) for k, v in lw.items()} for lw in w.bits]
+    for i in (2, 1):                                        # prompts are independent: the oracle recomputes two of them alone
+        nb = (int(lens[i]) + 15) // 16
+        sub_pool = np.zeros((1, nb, 2, ms.n_kv_heads, 16, ms.head_dim), dtype=np.float32)
+        rows = slice(int(cu[i]), int(cu[i + 1]))
+        want = oracle.stage_forward(osh, wf, sub_pool, [0, int(lens[i])], [0], np.arange(nb, dtype=np.int32)[None, :],
+                                    synth.bf16_bits_to_f32(hidden_bits[rows]).astype(np.float64))
+        check_wide_output(got[rows], want, f"prompt {i} ({lens[i]} tokens):")
