@@ -53,6 +53,14 @@ __device__ __forceinline__ void merge_state(float &m, float &l, float (&acc)[NV]
     m = mn;
 }
 
+// Workers that share the U units: never more than units (no empty ranges).  With very few sequences
+// every head would leave a piece per worker, and merging dozens of pieces costs more than the shorter
+// streams save: then at most eight workers per (sequence, head group) on average, unless that leaves a
+// worker more than 16 blocks (1 sequence of 1024 tokens: attention + merge 28 -> 21 us).
+__device__ __forceinline__ int64_t worker_count(int64_t available, int64_t U, int64_t seq_groups)
+{
+    return min(min(available, U), max(8 * seq_groups, U / 16));
+}
 // first unit of worker w when U units are cut into W ranges
 __device__ __forceinline__ int64_t worker_begin(int64_t w, int64_t U, int64_t W) { return w * U / W; }
 // worker that owns unit u
@@ -83,7 +91,7 @@ __global__ __launch_bounds__(kDecThreads) void attn_decode_kernel(DecodeAttnArgs
     const int lane = threadIdx.x & 63;
     const int Hkv = a.n_kv_heads, Gs = a.head_group, Hg = Hkv / Gs;
     const int64_t U = (int64_t)s_prefix[a.num_seqs] * Hg;
-    const int64_t W = min((int64_t)gridDim.x * kDecWaves / Gs, U);  // never more workers than units: no empty ranges
+    const int64_t W = worker_count((int64_t)gridDim.x * kDecWaves / Gs, U, (int64_t)a.num_seqs * Hg);
     const int wave_id = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * kDecWaves + (threadIdx.x >> 6)));
     const int64_t wk = wave_id / Gs;                                 // worker: Gs neighbouring wavefronts, one head each
     const int hi_w = wave_id % Gs;
@@ -331,7 +339,7 @@ __global__ __launch_bounds__(kDecThreads, 2) void attn_decode_mfma_kernel(Decode
     char *s_v = reinterpret_cast<char *>(s_dyn) + ((a.num_seqs + 1) * 4 + 255) / 256 * 256 + wave * (2 * kVBlock);
     const int Gs = a.head_group, Hg = Hkv / Gs;
     const int64_t U = (int64_t)s_prefix[a.num_seqs] * Hg;
-    const int64_t W = min((int64_t)gridDim.x * kDecWaves / Gs, U);
+    const int64_t W = worker_count((int64_t)gridDim.x * kDecWaves / Gs, U, (int64_t)a.num_seqs * Hg);
     const int wave_id = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * kDecWaves + wave));
     const int64_t wk = wave_id / Gs;                                 // worker: Gs neighbouring wavefronts, one kv head each
     const int hi_w = wave_id % Gs;
@@ -521,7 +529,7 @@ __global__ void attn_decode_combine_kernel(DecodeAttnArgs a)
     const int n_keys = a.ctx_lens[seq] + 1;
     const int nb = (n_keys + kBlockTokens - 1) / kBlockTokens;
     const int Gs = a.head_group, Hg = Hkv / Gs, hg = hk / Gs, hi_w = hk % Gs;
-    const int64_t U = (int64_t)total * Hg, W = min((int64_t)a.n_workers / Gs, U);
+    const int64_t U = (int64_t)total * Hg, W = worker_count((int64_t)a.n_workers / Gs, U, (int64_t)a.num_seqs * Hg);
     const int64_t u0 = (int64_t)before * Hg + (int64_t)hg * nb;
     const int64_t w_first = worker_of(u0, U, W), w_last = worker_of(u0 + nb - 1, U, W);
     const int64_t pair = (int64_t)seq * Hg + hg;

@@ -28,7 +28,7 @@ def pieces(ctx, Hkv, Gs, n_workers):
     prefix = np.concatenate([[0], np.cumsum(nb)])
     Hg = Hkv // Gs
     U = int(prefix[-1]) * Hg
-    W = min(n_workers // Gs, U)
+    W = min(n_workers // Gs, U, max(8 * len(ctx) * Hg, U // 16))   # few sequences: at most eight workers per head group, or 16 blocks each
     out = []
     for w in range(W):
         u, u_end = worker_begin(w, U, W), worker_begin(w + 1, U, W)
