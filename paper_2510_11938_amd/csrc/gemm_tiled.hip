@@ -52,8 +52,8 @@ __global__ __launch_bounds__(kTgThreads, 2) void gemm_tiled_kernel(TiledArgs a)
     if (tiles_m == 1) {          // one row of tiles (at most 128 token rows): nothing to share but the token rows
         tile_m = 0;
         tile_n = blockIdx.x;
-    } else if (tiles_m < 8) {
-        // a few rows of tiles: XCD x takes the weight tiles n = x mod 8 and walks the token tiles of each in turn,
+    } else if (tiles_m < 16) {
+        // up to 15 rows of tiles: XCD x takes the weight tiles n = x mod 8 and walks the token tiles of each in turn,
         // so the workgroups that share weight rows follow each other on one L2
         const int xcd = blockIdx.x % 8, seq = blockIdx.x / 8;
         tile_m = seq % tiles_m;
@@ -278,7 +278,7 @@ hipError_t launch_gemm_tiled(const TiledArgs &a, hipStream_t stream)
     const int blocks = ((tiles_n + 3) / 4) * ((tiles_m + 7) / 8);
     dim3 grid((blocks + 7) / 8 * 8 * 32, a.epilogue == kEpiPartial ? a.S : 1);
     if (tiles_m == 1) grid.x = tiles_n;
-    else if (tiles_m < 8) grid.x = (tiles_n + 7) / 8 * 8 * tiles_m;
+    else if (tiles_m < 16) grid.x = (tiles_n + 7) / 8 * 8 * tiles_m;
     const bool tail = a.K % 64 != 0;                  // a stage is 64 wide: the token rows end inside the last one
 #define FXP_TG_LAUNCH(E)                                                                                       \
     if (tail) hipLaunchKernelGGL((gemm_tiled_kernel<E, true>), grid, dim3(kTgThreads), 0, stream, a);          \
