@@ -25,6 +25,7 @@
 // zero probability never meets an uninitialised (possibly NaN) value.
 #include "kernels.h"
 #include "common.hip.h"
+#include <stdlib.h>
 #include <math.h>
 
 namespace fxp {
@@ -34,7 +35,7 @@ constexpr int kPfQPerWave = 16;
 constexpr int kPfQTile = 64;        // query rows per workgroup
 constexpr int kPfKvTile = 64;       // keys per LDS tile (4 cache blocks)
 
-template <int D, bool DEBUG>
+template <int D, bool DEBUG, bool FLAT>
 __global__ __launch_bounds__(kPfThreads) void attn_prefill_kernel(PrefillAttnArgs a)
 {
     constexpr int KS = D / 32;                    // k-steps of the QK product
@@ -45,10 +46,34 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_kernel(PrefillAttnArg
     __shared__ __attribute__((aligned(16))) char s_k[kPfKvTile * kKPitch];
     __shared__ __attribute__((aligned(16))) char s_v[kPfKvTile * kVPitch];
 
-    const int qt = blockIdx.x, h = blockIdx.y, seq = blockIdx.z;
-    const int t0 = a.cu_seqlens_q[seq];
-    const int q_len = a.cu_seqlens_q[seq + 1] - t0;
-    if (qt * kPfQTile >= q_len) return;
+    // Workgroups are launched in index order and a causal tile's work grows with its position in the sequence:
+    // heads vary fastest and the tiles are taken from the last one down, so the long tiles start first and the
+    // short ones fill the tail of the launch.
+    int seq, t0, q_len, qt;
+    const int h = blockIdx.x;
+    if constexpr (FLAT) {
+        // Query tiles of all sequences as one line: sequence i owns the slots from cu[i] / 64 + i on (cu = first
+        // token of the sequence).  The ranges cannot overlap (the next one starts at least ceil(len / 64) further)
+        // and the line is num_tokens / 64 + num_seqs long, so a batch of one long and many short prompts launches
+        // about as many workgroups as it has tiles, not longest-prompt tiles times sequences.
+        extern __shared__ int32_t s_cu[];             // [num_seqs + 1]
+        for (int i = threadIdx.x; i <= a.num_seqs; i += kPfThreads) s_cu[i] = a.cu_seqlens_q[i];
+        __syncthreads();
+        seq = 0;
+        int hi = a.num_seqs;
+        const int slot = (int)(gridDim.y - 1 - blockIdx.y);
+        while (hi - seq > 1) { const int mid = (seq + hi) >> 1; if (s_cu[mid] / kPfQTile + mid <= slot) seq = mid; else hi = mid; }
+        t0 = s_cu[seq];
+        q_len = s_cu[seq + 1] - t0;
+        qt = slot - (t0 / kPfQTile + seq);
+        if (qt * kPfQTile >= q_len) return;
+    } else {
+        seq = blockIdx.z;
+        t0 = a.cu_seqlens_q[seq];
+        q_len = a.cu_seqlens_q[seq + 1] - t0;
+        qt = (q_len + kPfQTile - 1) / kPfQTile - 1 - (int)blockIdx.y;
+        if (qt < 0) return;
+    }
     const int ctx = a.ctx_lens[seq];
     const int n_keys = ctx + q_len;
     const int hk = h / (a.n_q_heads / a.n_kv_heads);
@@ -239,13 +264,21 @@ __global__ void attn_probs_normalize_kernel(float *scores, const float *ml, int6
 template <int D>
 static hipError_t launch_d(const PrefillAttnArgs &a, hipStream_t stream)
 {
-    dim3 grid((a.max_q_len + kPfQTile - 1) / kPfQTile, a.n_q_heads, a.num_seqs);
+    // one line of tiles when the rectangle (tiles of the longest prompt x sequences) would be more than eight times as
+    // large (an empty workgroup costs a few nanoseconds, which only matters when there are very many of them)
+    const int rect_x = (a.max_q_len + kPfQTile - 1) / kPfQTile, flat_x = a.num_tokens / kPfQTile + a.num_seqs;
+    static const int forced = getenv("FXP_PREFILL_FLAT_GRID") ? atoi(getenv("FXP_PREFILL_FLAT_GRID")) : -1;
+    const bool flat = forced >= 0 ? forced != 0 : (int64_t)rect_x * a.num_seqs > 8 * (int64_t)flat_x;
+    const dim3 grid = flat ? dim3(a.n_q_heads, flat_x) : dim3(a.n_q_heads, rect_x, a.num_seqs);
+    const size_t lds = flat ? (size_t)(a.num_seqs + 1) * sizeof(int32_t) : 0;
     if (a.dbg_scores) {
-        hipLaunchKernelGGL((attn_prefill_kernel<D, true>), grid, dim3(kPfThreads), 0, stream, a);
+        if (flat) hipLaunchKernelGGL((attn_prefill_kernel<D, true, true>), grid, dim3(kPfThreads), lds, stream, a);
+        else hipLaunchKernelGGL((attn_prefill_kernel<D, true, false>), grid, dim3(kPfThreads), lds, stream, a);
         hipLaunchKernelGGL(attn_probs_normalize_kernel, dim3(a.num_tokens * a.n_q_heads), dim3(64), 0, stream,
                            a.dbg_scores, a.dbg_ml, a.dbg_stride);
     } else {
-        hipLaunchKernelGGL((attn_prefill_kernel<D, false>), grid, dim3(kPfThreads), 0, stream, a);
+        if (flat) hipLaunchKernelGGL((attn_prefill_kernel<D, false, true>), grid, dim3(kPfThreads), lds, stream, a);
+        else hipLaunchKernelGGL((attn_prefill_kernel<D, false, false>), grid, dim3(kPfThreads), lds, stream, a);
     }
     return hipGetLastError();
 }

@@ -125,6 +125,9 @@ PREFILL_CASES = [
     ("mid128-prompts", MID128, 2, [0, 129, 0], [200, 3, 65]),
     ("gqa128-8", GQA128, 1, [0, 40], [100, 90]),
     ("odd-k-prompts", ODD_K, 2, [0, 0, 7], [150, 33, 60]),                  # hidden and ffn are 32 mod 64: the last 64-wide stage is half empty
+    ("skewed-prompts", TINY, 1, [0] * 8, [300, 5, 9, 1, 17, 2, 33, 4]),      # one long prompt among short ones
+    ("very-skewed", TINY, 1, [0] * 60, [640] + [1 + i % 3 for i in range(59)]),   # ... so many that the query tiles are launched as one line
+    ("skewed-chunked", GQA64, 1, [16, 0, 70, 3, 0, 0, 40, 1], [260, 1, 2, 64, 65, 3, 1, 7]),
     ("opt-prompts", OPT_TINY, 2, [0, 0, 0, 0], [37, 128, 32, 100]),
     ("opt-small", OPT_TINY, 2, [0, 0], [20, 45]),
     ("opt-chunked", OPT_GQA, 1, [16, 70, 33], [48, 10, 64]),
