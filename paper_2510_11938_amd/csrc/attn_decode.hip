@@ -122,13 +122,14 @@ __global__ __launch_bounds__(kDecThreads) void attn_decode_kernel(DecodeAttnArgs
         const int hk = hg * Gs + hi_w;
         const int nblk = (int)min((int64_t)(nb_seq - blk0), u_end - u);  // blocks of this piece
         const int n_keys = a.ctx_lens[seq] + 1;                          // cached tokens + the one appended this step
+        const int tok_row = a.cu_seqlens_q[seq];                         // the sequence's token row (= seq in a pure decode step)
         const int32_t *trow = a.block_table + (int64_t)seq * a.max_blocks_per_seq + blk0;
 
         // query, pre-scaled by log2(e)/sqrt(D) so that probabilities are exp2(s - m)
         float q[G][8];
 #pragma unroll
         for (int g = 0; g < G; ++g) {
-            const u32x4 v = ld16(a.q + ((int64_t)seq * a.n_q_heads + hk * G + g) * D + dc * 8);
+            const u32x4 v = ld16(a.q + ((int64_t)tok_row * a.n_q_heads + hk * G + g) * D + dc * 8);
             q[g][0] = bf16_lo(v.x) * a.scale_log2e; q[g][1] = bf16_hi(v.x) * a.scale_log2e;
             q[g][2] = bf16_lo(v.y) * a.scale_log2e; q[g][3] = bf16_hi(v.y) * a.scale_log2e;
             q[g][4] = bf16_lo(v.z) * a.scale_log2e; q[g][5] = bf16_hi(v.z) * a.scale_log2e;
@@ -188,7 +189,7 @@ __global__ __launch_bounds__(kDecThreads) void attn_decode_kernel(DecodeAttnArgs
                     s[i] = tok < n_keys ? d : -INFINITY;
                     if constexpr (DEBUG) {
                         if (dc == 0 && tok < n_keys)
-                            a.dbg_scores[((int64_t)seq * a.n_q_heads + hk * G + g) * a.dbg_stride + tok] = d;
+                            a.dbg_scores[((int64_t)tok_row * a.n_q_heads + hk * G + g) * a.dbg_stride + tok] = d;
                     }
                 }
                 float mn = m[g];
@@ -372,12 +373,13 @@ __global__ __launch_bounds__(kDecThreads, 2) void attn_decode_mfma_kernel(Decode
         const int hk = hg * Gs + hi_w;
         const int nblk = (int)min((int64_t)(nb_seq - blk0), u_end - u);
         const int n_keys = a.ctx_lens[seq] + 1;
+        const int tok_row = a.cu_seqlens_q[seq];
         const int32_t *trow = a.block_table + (int64_t)seq * a.max_blocks_per_seq + blk0;
 
         // column operand: query head col of the group (zero beyond G), dims 32*s + 8*c .. +7
         u32x4 qop[KS];
         {
-            const uint16_t *qp = a.q + ((int64_t)seq * a.n_q_heads + hk * G + min(col, G - 1)) * D + c * 8;
+            const uint16_t *qp = a.q + ((int64_t)tok_row * a.n_q_heads + hk * G + min(col, G - 1)) * D + c * 8;
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
                 const u32x4 v = ld16(qp + ks * 32);
@@ -439,7 +441,7 @@ __global__ __launch_bounds__(kDecThreads, 2) void attn_decode_mfma_kernel(Decode
                     const bool ok = present && tok < n_keys;
                     sc[h][v] = ok ? sv : -INFINITY;
                     if constexpr (DEBUG) {
-                        if (ok && col < G) a.dbg_scores[((int64_t)seq * a.n_q_heads + hk * G + col) * a.dbg_stride + tok] = sv;
+                        if (ok && col < G) a.dbg_scores[((int64_t)tok_row * a.n_q_heads + hk * G + col) * a.dbg_stride + tok] = sv;
                     }
                 }
             }
@@ -525,6 +527,8 @@ __global__ void attn_decode_combine_kernel(DecodeAttnArgs a)
     const int row_id = blockIdx.x * (blockDim.x / D) + threadIdx.x / D;      // (sequence, query head), several per workgroup
     if (row_id >= a.num_seqs * a.n_q_heads) return;
     const int seq = row_id / a.n_q_heads, head = row_id % a.n_q_heads, hk = head / G, g = head % G;
+    const int tok_row = a.cu_seqlens_q[seq];
+    if (a.cu_seqlens_q[seq + 1] - tok_row != 1) return;      // a prompt chunk in a mixed call: the prefill kernel's
     const int32_t before = a.blk_prefix[seq], total = a.blk_prefix[a.num_seqs];   // blocks (per head) before this sequence / in the batch
     const int n_keys = a.ctx_lens[seq] + 1;
     const int nb = (n_keys + kBlockTokens - 1) / kBlockTokens;
@@ -556,7 +560,7 @@ __global__ void attn_decode_combine_kernel(DecodeAttnArgs a)
             }
         }
     }
-    const int64_t row = (int64_t)seq * a.n_q_heads + head;
+    const int64_t row = (int64_t)tok_row * a.n_q_heads + head;
     a.out[row * D + d] = f32_to_bf16(av / ll);
     if constexpr (DEBUG) {
         // turn the stored scaled scores (log2 domain) into probabilities

@@ -74,6 +74,7 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_kernel(PrefillAttnArg
         qt = (q_len + kPfQTile - 1) / kPfQTile - 1 - (int)blockIdx.y;
         if (qt < 0) return;
     }
+    if (a.skip_single && q_len == 1) return;
     const int ctx = a.ctx_lens[seq];
     const int n_keys = ctx + q_len;
     const int hk = h / (a.n_q_heads / a.n_kv_heads);

@@ -252,7 +252,12 @@ __global__ __launch_bounds__(kRopeTableThreads) void rope_table_kernel(RopeTable
         const int per = (n + nt - 1) / nt;
         const int lo = min(tid * per, n), hi = min(lo + per, n);
         int32_t local = 0;
-        for (int i = lo; i < hi; ++i) local += (a.ctx_lens[i] + 1 + kBlockTokens - 1) / kBlockTokens;
+        // (only the sequences with one new token are the decode kernels' business: in a call that mixes prompt chunks
+        // and decode rows the chunks count as zero blocks and go to the prefill kernel)
+        auto blocks_of = [&](int i) {
+            return a.cu_seqlens_q[i + 1] - a.cu_seqlens_q[i] == 1 ? (a.ctx_lens[i] + 1 + kBlockTokens - 1) / kBlockTokens : 0;
+        };
+        for (int i = lo; i < hi; ++i) local += blocks_of(i);
         s_scan[tid] = local;
         __syncthreads();
         for (int o = 1; o < nt; o <<= 1) {
@@ -262,7 +267,7 @@ __global__ __launch_bounds__(kRopeTableThreads) void rope_table_kernel(RopeTable
             __syncthreads();
         }
         int32_t run = s_scan[tid] - local;
-        for (int i = lo; i < hi; ++i) { a.blk_prefix[i] = run; run += (a.ctx_lens[i] + 1 + kBlockTokens - 1) / kBlockTokens; }
+        for (int i = lo; i < hi; ++i) { a.blk_prefix[i] = run; run += blocks_of(i); }
         if (tid == nt - 1) a.blk_prefix[n] = s_scan[nt - 1];
     }
 }

@@ -453,6 +453,8 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
     const int H = d.hidden, D = d.head_dim, Nq = d.n_q_heads * D, Nall = (d.n_q_heads + 2 * d.n_kv_heads) * D, F = d.ffn;
     const bool skinny = T <= kSkinnyMaxTokens;
     const bool decode = batch->max_q_len == 1 && T == B;
+    // lengths live on the device: a ragged call with several sequences may mix prompt chunks and single-token rows
+    const bool mixed = !decode && !probs && B >= 2 && batch->max_q_len > 1 && (int64_t)T < (int64_t)B * batch->max_q_len;
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
     hipError_t e;
 
@@ -558,11 +560,12 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
             if ((e = fxp::launch_qkv_rope_kvwrite(ra, st))) return hip_fail(e, "rope + kv append");
         }
 
-        // attention
-        if (decode) {
+        // attention: sequences with one new token by the decode kernels, longer chunks by the prefill kernel (a call that
+        // may hold both -- ragged, more than one sequence -- launches both; each leaves the other's sequences alone)
+        if (decode || mixed) {
             fxp::DecodeAttnArgs aa;
             aa.q = w.q; aa.pool = (const uint16_t *)pool->base; aa.ctx_lens = batch->ctx_lens; aa.block_table = batch->block_table;
-            aa.blk_prefix = w.blk_prefix;
+            aa.cu_seqlens_q = batch->cu_seqlens_q; aa.blk_prefix = w.blk_prefix;
             aa.part_acc = w.part_acc; aa.part_ml = w.part_ml; aa.out = w.o; aa.dbg_scores = dbg; aa.dbg_stride = probs_stride;
             aa.num_blocks = pool->num_blocks; aa.num_seqs = B; aa.max_blocks_per_seq = batch->max_blocks_per_seq;
             aa.n_workers = w.n_workers; aa.layer_local = ll; aa.n_q_heads = d.n_q_heads; aa.n_kv_heads = d.n_kv_heads;
@@ -575,8 +578,10 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
                 KernelTimer kt(kKcAttnCombine, st);
                 if ((e = fxp::launch_attn_decode_combine(aa, st))) return hip_fail(e, "decode attention combine");
             }
-        } else {
+        }
+        if (!decode) {
             fxp::PrefillAttnArgs pa;
+            pa.skip_single = mixed ? 1 : 0;
             pa.q = w.q; pa.pool = (const uint16_t *)pool->base; pa.cu_seqlens_q = batch->cu_seqlens_q; pa.ctx_lens = batch->ctx_lens;
             pa.block_table = batch->block_table; pa.out = w.o; pa.dbg_scores = dbg; pa.dbg_ml = w.dbg_ml; pa.dbg_stride = probs_stride;
             pa.num_blocks = pool->num_blocks; pa.num_seqs = B; pa.num_tokens = T; pa.max_q_len = batch->max_q_len;

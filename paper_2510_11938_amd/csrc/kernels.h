@@ -144,7 +144,8 @@ struct DecodeAttnArgs {
     const uint16_t *q;     // [num_seqs][Hq][D] bf16 (rotated)
     const uint16_t *pool;
     const int32_t *ctx_lens, *block_table;
-    const int32_t *blk_prefix;   // [num_seqs + 1] from the rope-table kernel
+    const int32_t *cu_seqlens_q; // [num_seqs + 1]: a sequence with exactly one new token is a decode row, at token row cu[seq]
+    const int32_t *blk_prefix;   // [num_seqs + 1] from the rope-table kernel (decode rows only)
     float *part_acc;       // [n_workers + num_seqs*Hkv][G][D]   one row group per piece
     float *part_ml;        // [n_workers + num_seqs*Hkv][G][2]
     uint16_t *out;         // [num_seqs][Hq*D] bf16
@@ -172,6 +173,7 @@ struct PrefillAttnArgs {
     int64_t num_blocks;
     int num_seqs, num_tokens, max_q_len, max_blocks_per_seq, layer_local;
     int n_q_heads, n_kv_heads, head_dim;
+    int skip_single;       // 1: sequences with one new token are left to the decode kernels
     float scale_log2e;
 };
 hipError_t launch_attn_prefill(const PrefillAttnArgs &a, hipStream_t stream);

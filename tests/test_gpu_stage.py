@@ -125,6 +125,8 @@ PREFILL_CASES = [
     ("mid128-prompts", MID128, 2, [0, 129, 0], [200, 3, 65]),
     ("gqa128-8", GQA128, 1, [0, 40], [100, 90]),
     ("odd-k-prompts", ODD_K, 2, [0, 0, 7], [150, 33, 60]),                  # hidden and ffn are 32 mod 64: the last 64-wide stage is half empty
+    ("mixed-chunk-and-decode", TINY, 2, [0, 700, 33, 128, 5, 16], [130, 1, 1, 1, 20, 1]),   # single-token rows go to the decode kernels
+    ("mixed-gqa", GQA64, 1, [40, 1100, 0, 15, 513], [70, 1, 1, 1, 1]),
     ("skewed-prompts", TINY, 1, [0] * 8, [300, 5, 9, 1, 17, 2, 33, 4]),      # one long prompt among short ones
     ("very-skewed", TINY, 1, [0] * 60, [640] + [1 + i % 3 for i in range(59)]),   # ... so many that the query tiles are launched as one line
     ("skewed-chunked", GQA64, 1, [16, 0, 70, 3, 0, 0, 40, 1], [260, 1, 2, 64, 65, 3, 1, 7]),
