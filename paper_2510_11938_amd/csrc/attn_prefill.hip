@@ -27,6 +27,7 @@
 #include "common.hip.h"
 #include <stdlib.h>
 #include <math.h>
+#include <algorithm>
 
 namespace fxp {
 
@@ -34,6 +35,17 @@ constexpr int kPfThreads = 256;
 constexpr int kPfQPerWave = 16;
 constexpr int kPfQTile = 64;        // query rows per workgroup
 constexpr int kPfKvTile = 64;       // keys per LDS tile (4 cache blocks)
+constexpr int kPfMinPieceTiles = 8; // a query tile's keys are cut into pieces of at least this many LDS tiles
+constexpr int kPfMaxPieces = 8;
+constexpr int kPfResidentWgs = 768; // workgroups of this kernel that the chip holds at a time (3 per compute unit)
+
+// Pieces that the keys of one query tile are cut into when the launch has too few query tiles to fill the chip (a short
+// chunk behind a long cached prefix): as many as the launch allows, each at least kPfMinPieceTiles tiles long.
+// The attention kernel and the merge kernel both derive it from the same lengths.
+__device__ inline int kv_pieces(int n_tiles, int kv_split)
+{
+    return min(kv_split, max(1, n_tiles / kPfMinPieceTiles));
+}
 
 template <int D, bool DEBUG, bool FLAT>
 __global__ __launch_bounds__(kPfThreads) void attn_prefill_kernel(PrefillAttnArgs a)
@@ -51,6 +63,7 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_kernel(PrefillAttnArg
     // short ones fill the tail of the launch.
     int seq, t0, q_len, qt;
     const int h = blockIdx.x;
+    const int piece = (int)blockIdx.y % a.kv_split, by = (int)blockIdx.y / a.kv_split, ny = (int)gridDim.y / a.kv_split;
     if constexpr (FLAT) {
         // Query tiles of all sequences as one line: sequence i owns the slots from cu[i] / 64 + i on (cu = first
         // token of the sequence).  The ranges cannot overlap (the next one starts at least ceil(len / 64) further)
@@ -61,7 +74,7 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_kernel(PrefillAttnArg
         __syncthreads();
         seq = 0;
         int hi = a.num_seqs;
-        const int slot = (int)(gridDim.y - 1 - blockIdx.y);
+        const int slot = ny - 1 - by;
         while (hi - seq > 1) { const int mid = (seq + hi) >> 1; if (s_cu[mid] / kPfQTile + mid <= slot) seq = mid; else hi = mid; }
         t0 = s_cu[seq];
         q_len = s_cu[seq + 1] - t0;
@@ -71,7 +84,7 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_kernel(PrefillAttnArg
         seq = blockIdx.z;
         t0 = a.cu_seqlens_q[seq];
         q_len = a.cu_seqlens_q[seq + 1] - t0;
-        qt = (q_len + kPfQTile - 1) / kPfQTile - 1 - (int)blockIdx.y;
+        qt = (q_len + kPfQTile - 1) / kPfQTile - 1 - by;
         if (qt < 0) return;
     }
     if (a.skip_single && q_len == 1) return;
@@ -88,6 +101,9 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_kernel(PrefillAttnArg
     const int wave_last_pos = ctx + min(j0 + kPfQPerWave - 1, q_len - 1);
     const int wg_last_pos = ctx + min(qt * kPfQTile + kPfQTile - 1, q_len - 1);
     const int n_tiles = wg_last_pos / kPfKvTile + 1;
+    const int n_pieces = kv_pieces(n_tiles, a.kv_split);
+    if (piece >= n_pieces) return;
+    const int tile_begin = (int)((int64_t)piece * n_tiles / n_pieces), tile_end = (int)((int64_t)(piece + 1) * n_tiles / n_pieces);
 
     // Q as column operand: lane holds Q[jq][32*ks + 8*c .. +7]
     u32x4 qreg[KS];
@@ -135,9 +151,9 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_kernel(PrefillAttnArg
             vreg[i] = ok ? vvec : u32x4{0u, 0u, 0u, 0u};
         }
     };
-    fetch_tile(0);
+    fetch_tile(tile_begin);
 
-    for (int tile = 0; tile < n_tiles; ++tile) {
+    for (int tile = tile_begin; tile < tile_end; ++tile) {
         const int kv0 = tile * kPfKvTile;
         // ---- stage K and V (both row-major, padded pitches) of keys kv0 .. kv0+63
         __syncthreads();
@@ -148,7 +164,7 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_kernel(PrefillAttnArg
             *reinterpret_cast<u32x4 *>(s_v + r * kVPitch + dc0 * 16) = vreg[i];
         }
         __syncthreads();
-        if (tile + 1 < n_tiles) fetch_tile(tile + 1);
+        if (tile + 1 < tile_end) fetch_tile(tile + 1);
         if (kv0 > wave_last_pos) continue;          // whole tile is in this wave's future (wave-uniform)
 
         // ---- S^T = K . Q^T for the 4 sub-tiles of 16 keys
@@ -237,6 +253,16 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_kernel(PrefillAttnArg
     l_run += __shfl_xor(l_run, 16, 64);
     l_run += __shfl_xor(l_run, 32, 64);
     if (!q_ok) return;
+    if (n_pieces > 1) {
+        // one piece of several: unnormalised sums, running maximum and denominator go to the merge kernel.  A wave whose
+        // rows see none of this piece's keys (possible in the last piece only) hands over m = -inf, l = 0, o = 0.
+        const int64_t row = ((int64_t)piece * a.num_tokens + t0 + jq) * a.n_q_heads + h;
+        float *pa = a.part_acc + row * D + 4 * c;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) *reinterpret_cast<f32x4_t *>(pa + dt * 16) = o[dt];
+        if (c == 0) { a.part_ml[row * 2] = m_run; a.part_ml[row * 2 + 1] = l_run; }
+        return;
+    }
     const float inv = 1.f / l_run;
     uint16_t *op = a.out + ((int64_t)(t0 + jq) * a.n_q_heads + h) * D + 4 * c;
 #pragma unroll
@@ -252,6 +278,38 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_kernel(PrefillAttnArg
     }
 }
 
+// Merge of the pieces of the query tiles whose keys were cut: out = sum_z 2^(m_z - M) o_z / sum_z 2^(m_z - M) l_z.
+// One thread per four output dims; rows whose tile ran as one piece were finished by the attention kernel.
+template <int D>
+__global__ __launch_bounds__(kPfThreads) void attn_prefill_merge_kernel(PrefillAttnArgs a)
+{
+    constexpr int kLanesPerRow = D / 4, kRowsPerWg = kPfThreads / kLanesPerRow;
+    const int64_t row = (int64_t)blockIdx.x * kRowsPerWg + threadIdx.x / kLanesPerRow;
+    if (row >= (int64_t)a.num_tokens * a.n_q_heads) return;
+    const int t = (int)(row / a.n_q_heads), i = threadIdx.x % kLanesPerRow;
+    const int seq = a.tok_seq[t];
+    const int t0 = a.cu_seqlens_q[seq], q_len = a.cu_seqlens_q[seq + 1] - t0;
+    if (a.skip_single && q_len == 1) return;
+    const int qt = (t - t0) / kPfQTile;
+    const int wg_last_pos = a.ctx_lens[seq] + min(qt * kPfQTile + kPfQTile - 1, q_len - 1);
+    const int n_pieces = kv_pieces(wg_last_pos / kPfKvTile + 1, a.kv_split);
+    if (n_pieces == 1) return;
+    const int64_t piece_stride = (int64_t)a.num_tokens * a.n_q_heads;
+    float m = -INFINITY;
+    for (int z = 0; z < n_pieces; ++z) m = fmaxf(m, a.part_ml[(row + z * piece_stride) * 2]);
+    f32x4_t num = {0.f, 0.f, 0.f, 0.f};
+    float den = 0.f;
+    for (int z = 0; z < n_pieces; ++z) {
+        const int64_t r = row + z * piece_stride;
+        const float wgt = __builtin_amdgcn_exp2f(a.part_ml[r * 2] - m);     // piece 0 always holds key 0, so m is finite
+        den += wgt * a.part_ml[r * 2 + 1];
+        num += wgt * *reinterpret_cast<const f32x4_t *>(a.part_acc + r * D + 4 * i);
+    }
+    const float inv = 1.f / den;
+    const u32x2 w = {pack_bf16x2(num[0] * inv, num[1] * inv), pack_bf16x2(num[2] * inv, num[3] * inv)};
+    *reinterpret_cast<u32x2 *>(a.out + row * D + 4 * i) = w;
+}
+
 // debug only: scores (log2 domain) -> probabilities, one workgroup per (token, head)
 __global__ void attn_probs_normalize_kernel(float *scores, const float *ml, int64_t stride)
 {
@@ -262,15 +320,34 @@ __global__ void attn_probs_normalize_kernel(float *scores, const float *ml, int6
         scores[row * stride + r] = __builtin_amdgcn_exp2f(scores[row * stride + r] - m) / l;
 }
 
-template <int D>
-static hipError_t launch_d(const PrefillAttnArgs &a, hipStream_t stream)
+size_t prefill_piece_rows(int n_q_heads, int max_tokens)
 {
+    // rows of [piece][token][head]: pieces * heads * tiles <= kPfResidentWgs with 64 tokens per tile, and pieces <= kPfMaxPieces
+    return std::min<size_t>((size_t)kPfResidentWgs * kPfQTile, (size_t)kPfMaxPieces * (size_t)std::max(max_tokens, 1) * n_q_heads);
+}
+int prefill_kv_split(int n_q_heads, int num_tokens, int num_seqs, int max_blocks_per_seq)
+{
+    static const int forced = getenv("FXP_PREFILL_KV_SPLIT") ? atoi(getenv("FXP_PREFILL_KV_SPLIT")) : 0;
+    const int64_t rows = (int64_t)std::max(num_tokens, 1) * n_q_heads;
+    const int64_t fits = (int64_t)prefill_piece_rows(n_q_heads, num_tokens) / rows;      // pieces the workspace has rows for
+    if (forced > 0) return (int)std::max<int64_t>(1, std::min<int64_t>(std::min(forced, kPfMaxPieces), fits));
+    // no sequence can hold two pieces' worth of keys: nothing to cut
+    if ((int64_t)max_blocks_per_seq * kBlockTokens < 2 * kPfMinPieceTiles * kPfKvTile) return 1;
+    const int64_t wgs = (int64_t)n_q_heads * (num_tokens / kPfQTile + num_seqs);      // upper bound of the live workgroups
+    return (int)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(kPfMaxPieces, kPfResidentWgs / wgs), fits));
+}
+
+template <int D>
+static hipError_t launch_d(const PrefillAttnArgs &a_in, hipStream_t stream)
+{
+    PrefillAttnArgs a = a_in;
+    if (a.dbg_scores || !a.part_acc || a.kv_split < 1) a.kv_split = 1;      // the probability dump runs every tile as one piece
     // one line of tiles when the rectangle (tiles of the longest prompt x sequences) would be more than eight times as
     // large (an empty workgroup costs a few nanoseconds, which only matters when there are very many of them)
     const int rect_x = (a.max_q_len + kPfQTile - 1) / kPfQTile, flat_x = a.num_tokens / kPfQTile + a.num_seqs;
     static const int forced = getenv("FXP_PREFILL_FLAT_GRID") ? atoi(getenv("FXP_PREFILL_FLAT_GRID")) : -1;
     const bool flat = forced >= 0 ? forced != 0 : (int64_t)rect_x * a.num_seqs > 8 * (int64_t)flat_x;
-    const dim3 grid = flat ? dim3(a.n_q_heads, flat_x) : dim3(a.n_q_heads, rect_x, a.num_seqs);
+    const dim3 grid = flat ? dim3(a.n_q_heads, flat_x * a.kv_split) : dim3(a.n_q_heads, rect_x * a.kv_split, a.num_seqs);
     const size_t lds = flat ? (size_t)(a.num_seqs + 1) * sizeof(int32_t) : 0;
     if (a.dbg_scores) {
         if (flat) hipLaunchKernelGGL((attn_prefill_kernel<D, true, true>), grid, dim3(kPfThreads), lds, stream, a);
@@ -280,6 +357,11 @@ static hipError_t launch_d(const PrefillAttnArgs &a, hipStream_t stream)
     } else {
         if (flat) hipLaunchKernelGGL((attn_prefill_kernel<D, false, true>), grid, dim3(kPfThreads), lds, stream, a);
         else hipLaunchKernelGGL((attn_prefill_kernel<D, false, false>), grid, dim3(kPfThreads), lds, stream, a);
+        if (a.kv_split > 1) {
+            constexpr int kRowsPerWg = kPfThreads / (D / 4);
+            const int64_t rows = (int64_t)a.num_tokens * a.n_q_heads;
+            hipLaunchKernelGGL((attn_prefill_merge_kernel<D>), dim3((unsigned)((rows + kRowsPerWg - 1) / kRowsPerWg)), dim3(kPfThreads), 0, stream, a);
+        }
     }
     return hipGetLastError();
 }

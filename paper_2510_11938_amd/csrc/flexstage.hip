@@ -211,7 +211,7 @@ namespace {
 
 struct Workspace {
     uint16_t *x[2], *n, *q, *qkv, *o, *h, *a;
-    float *P, *part_acc, *part_ml, *dbg_ml, *rope_cs, *rope_sn;
+    float *P, *part_acc, *part_ml, *pf_acc, *pf_ml, *dbg_ml, *rope_cs, *rope_sn;
     int32_t *tok_seq, *tok_pos;
     int32_t *blk_prefix;    // decode attention: cache blocks (per head) before each sequence, [B + 1]
     int n_workers;
@@ -256,6 +256,9 @@ Workspace carve(const fxp_stage_desc &d, int T, int B, int max_blocks, char *bas
     const size_t rows = ((size_t)w.n_workers + (size_t)(B > 0 ? B : 1) * d.n_kv_heads) * (d.n_q_heads / d.n_kv_heads);
     w.part_acc = (float *)take(rows * d.head_dim * 4);
     w.part_ml = (float *)take(rows * 2 * 4);
+    const size_t pf_rows = fxp::prefill_piece_rows(d.n_q_heads, T);
+    w.pf_acc = (float *)take(pf_rows * d.head_dim * 4);
+    w.pf_ml = (float *)take(pf_rows * 2 * 4);
     w.dbg_ml = (float *)take(t * d.n_q_heads * 3 * 4);
     w.rope_cs = (float *)take(t * (d.head_dim / 2) * 4);
     w.rope_sn = (float *)take(t * (d.head_dim / 2) * 4);
@@ -587,6 +590,8 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
             pa.num_blocks = pool->num_blocks; pa.num_seqs = B; pa.num_tokens = T; pa.max_q_len = batch->max_q_len;
             pa.max_blocks_per_seq = batch->max_blocks_per_seq; pa.layer_local = ll; pa.n_q_heads = d.n_q_heads;
             pa.n_kv_heads = d.n_kv_heads; pa.head_dim = D; pa.scale_log2e = scale_log2e;
+            pa.tok_seq = w.tok_seq; pa.part_acc = w.pf_acc; pa.part_ml = w.pf_ml;
+            pa.kv_split = fxp::prefill_kv_split(d.n_q_heads, T, B, batch->max_blocks_per_seq);
             KernelTimer kt(kKcAttnPrefill, st);
             if ((e = fxp::launch_attn_prefill(pa, st))) return hip_fail(e, "prefill attention");
         }

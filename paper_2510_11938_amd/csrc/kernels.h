@@ -175,7 +175,14 @@ struct PrefillAttnArgs {
     int n_q_heads, n_kv_heads, head_dim;
     int skip_single;       // 1: sequences with one new token are left to the decode kernels
     float scale_log2e;
+    // a launch with few query tiles cuts the keys of each tile into up to kv_split pieces (prefill_kv_split) and merges them
+    const int32_t *tok_seq;      // [T] sequence of each token (from the rope table)
+    float *part_acc;             // [kv_split][T][Hq][D] unnormalised sums of the pieces; nullptr: never cut
+    float *part_ml;              // [kv_split][T][Hq][2] running maximum (log2 domain) and denominator
+    int kv_split;
 };
+int prefill_kv_split(int n_q_heads, int num_tokens, int num_seqs, int max_blocks_per_seq);
+size_t prefill_piece_rows(int n_q_heads, int max_tokens);     // rows of part_acc / part_ml for calls of up to max_tokens
 hipError_t launch_attn_prefill(const PrefillAttnArgs &a, hipStream_t stream);
 
 }  // namespace fxp

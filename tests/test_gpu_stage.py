@@ -130,6 +130,11 @@ PREFILL_CASES = [
     ("skewed-prompts", TINY, 1, [0] * 8, [300, 5, 9, 1, 17, 2, 33, 4]),      # one long prompt among short ones
     ("very-skewed", TINY, 1, [0] * 60, [640] + [1 + i % 3 for i in range(59)]),   # ... so many that the query tiles are launched as one line
     ("skewed-chunked", GQA64, 1, [16, 0, 70, 3, 0, 0, 40, 1], [260, 1, 2, 64, 65, 3, 1, 7]),
+    # few query tiles behind long cached prefixes: the keys of a tile are cut into pieces that are merged afterwards
+    ("chunk-behind-long-prefix", TINY, 2, [1500], [70]),
+    ("chunks-behind-prefixes", GQA64, 1, [2100, 0, 600, 1030], [100, 130, 64, 3]),
+    ("mixed-long-prefix", TINY, 1, [3000, 900, 2047], [33, 1, 1]),
+    ("gqa128-long-prefix", GQA128, 1, [1100, 40], [80, 5]),
     ("opt-prompts", OPT_TINY, 2, [0, 0, 0, 0], [37, 128, 32, 100]),
     ("opt-small", OPT_TINY, 2, [0, 0], [20, 45]),
     ("opt-chunked", OPT_GQA, 1, [16, 70, 33], [48, 10, 64]),
