@@ -15,6 +15,10 @@ UNITS = ["flexstage", "kv_move", "weight_pack", "gemm_skinny", "gemm_tiled", "ep
          "granularity"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+# Per-unit additions.  attn_prefill: matrix-core results stay in ordinary vector registers; with the default choice the
+# compiler kept the output accumulators in vector registers between tiles and copied all 32 of them to accumulation
+# registers and back around the products of every tile (64 moves per tile and wavefront in a loop bound by vector ALU work).
+UNIT_FLAGS = {"attn_prefill": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 
 
 def _stale(target: str, deps) -> bool:
@@ -32,7 +36,7 @@ def build(force: bool = False, verbose: bool = False) -> str:
     def compile_one(u: str) -> str:
         src, obj = os.path.join(CSRC, u + ".hip"), os.path.join(OBJ, u + ".o")
         if force or _stale(obj, [src] + headers):
-            r = subprocess.run(["hipcc", *FLAGS, "-c", src, "-o", obj], capture_output=True, text=True)
+            r = subprocess.run(["hipcc", *FLAGS, *UNIT_FLAGS.get(u, []), "-c", src, "-o", obj], capture_output=True, text=True)
             err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
             if r.returncode != 0:
                 raise RuntimeError(f"hipcc failed on {u}.hip:\n{err}")

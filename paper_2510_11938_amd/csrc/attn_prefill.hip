@@ -124,31 +124,42 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_kernel(PrefillAttnArg
     constexpr int kChunksPerRow = D / 8;
     constexpr int kChunksPerThread = kPfKvTile * kChunksPerRow / kPfThreads;
 
-    // The K and V rows of the next tile travel from the cache to registers while the current
-    // tile is being multiplied: the table look-up and the cache read are two dependent memory
-    // round trips that would otherwise sit between every two tiles.
-    // Thread tid owns chunk dc of rows r0 + i * kRowsPerPass of a tile; kRowsPerPass is a multiple
-    // of the cache block, so its slot inside a block and its byte offset inside a unit never change
-    // and only the block-table entry differs from load to load.
+    // The K and V rows of the next tile travel from the cache to registers while the current tile is being multiplied.
+    // Nothing between the request and the LDS store of the following iteration may need the loaded values (the memory
+    // counter is in order: one early use would wait for everything requested before it), so rows past the sequence end
+    // are dealt with at the store (V, last tile only: a zero probability must not meet an uninitialised NaN; a K row
+    // past the end only produces scores that the causal mask replaces), and the block-table entries are not looked up
+    // per tile: each lane keeps one entry of a 64-block (16-tile) stretch of the table, the next stretch is requested
+    // sixteen tiles before it is needed, and a tile's entries are read out of those registers by lane index.
+    // Thread tid owns chunk dc0 of rows r0 + i * kRowsPerPass of a tile; kRowsPerPass is a multiple of the cache
+    // block, so its slot inside a block and its byte offset inside a unit never change, and the block a row lies in
+    // is the same for all lanes of a wavefront.
     constexpr int kRowsPerPass = kPfThreads / kChunksPerRow;
+    constexpr int kBlocksPerPass = kRowsPerPass / kBlockTokens, kBlocksPerTile = kPfKvTile / kBlockTokens;
+    constexpr int kTilesPerStretch = 64 / kBlocksPerTile;
     static_assert(kRowsPerPass % kBlockTokens == 0, "a pass of the staging loop covers whole cache blocks");
+    static_assert((64 / kChunksPerRow) <= kBlockTokens && kBlockTokens % (64 / kChunksPerRow) == 0, "the rows of a wavefront lie in one cache block");
     const int r0 = tid / kChunksPerRow, dc0 = tid % kChunksPerRow;
+    const int wave_blk = __builtin_amdgcn_readfirstlane(r0 / kBlockTokens);      // block (within a pass) of this wavefront's rows
     const uint16_t *lane_base = layer_base + (int64_t)hk * head_elems + (int64_t)(r0 % kBlockTokens) * D + dc0 * 8;
     const int64_t v_off = (int64_t)a.n_kv_heads * head_elems;
     const int last_blk = (n_keys - 1) / kBlockTokens;
+    const int last_tile = (n_keys - 1) / kPfKvTile;
+    int32_t stretch_cur = table[min(tile_begin * kBlocksPerTile + lane, last_blk)];
+    int32_t stretch_next = table[min((tile_begin + kTilesPerStretch) * kBlocksPerTile + lane, last_blk)];
     u32x4 kreg[kChunksPerThread], vreg[kChunksPerThread];
     auto fetch_tile = [&](int tile) {
-        const int kv0 = tile * kPfKvTile;
+        const int in_stretch = (tile - tile_begin) % kTilesPerStretch;
+        if (in_stretch == 0 && tile != tile_begin) {
+            stretch_cur = stretch_next;
+            stretch_next = table[min((tile + kTilesPerStretch) * kBlocksPerTile + lane, last_blk)];
+        }
 #pragma unroll
         for (int i = 0; i < kChunksPerThread; ++i) {
-            const int r = r0 + i * kRowsPerPass;
-            const int32_t phys = table[min((kv0 + r) / kBlockTokens, last_blk)];   // unconditional loads, rows past the end zeroed below
+            const int32_t phys = __builtin_amdgcn_readlane(stretch_cur, in_stretch * kBlocksPerTile + i * kBlocksPerPass + wave_blk);
             const uint16_t *kp = lane_base + (int64_t)phys * unit_elems;
-            const u32x4 kvec = ld16(kp);
-            const u32x4 vvec = ld16(kp + v_off);
-            const bool ok = kv0 + r < n_keys;
-            kreg[i] = ok ? kvec : u32x4{0u, 0u, 0u, 0u};
-            vreg[i] = ok ? vvec : u32x4{0u, 0u, 0u, 0u};
+            kreg[i] = ld16(kp);
+            vreg[i] = ld16(kp + v_off);
         }
     };
     fetch_tile(tile_begin);
@@ -157,6 +168,11 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_kernel(PrefillAttnArg
         const int kv0 = tile * kPfKvTile;
         // ---- stage K and V (both row-major, padded pitches) of keys kv0 .. kv0+63
         __syncthreads();
+        if (tile == last_tile) {
+#pragma unroll
+            for (int i = 0; i < kChunksPerThread; ++i)
+                if (kv0 + r0 + i * kRowsPerPass >= n_keys) vreg[i] = u32x4{0u, 0u, 0u, 0u};
+        }
 #pragma unroll
         for (int i = 0; i < kChunksPerThread; ++i) {
             const int r = r0 + i * kRowsPerPass;
@@ -165,6 +181,7 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_kernel(PrefillAttnArg
         }
         __syncthreads();
         if (tile + 1 < tile_end) fetch_tile(tile + 1);
+        __builtin_amdgcn_sched_barrier(0);          // the requests go out before the products, not after them
         if (kv0 > wave_last_pos) continue;          // whole tile is in this wave's future (wave-uniform)
 
         // ---- S^T = K . Q^T for the 4 sub-tiles of 16 keys
