@@ -18,8 +18,10 @@
 //                                         V^T comes from the row-major V tile in
 //                                         LDS through the transpose load
 //                                         (ds_read_b64_tr_b16).
-// A workgroup is 4 waves x 16 query rows of one (sequence, query head); the
-// 64-key K and V tiles are staged once in LDS and shared by the 4 waves.
+// A workgroup is 4 waves x 16 or 32 query rows (one or two column blocks per
+// wave) of one (sequence, query head); the 64-key K and V tiles are staged once
+// in LDS and shared by the 4 waves.  With two column blocks every K and V
+// operand read from LDS feeds two MFMAs and a tile is staged once per 128 rows.
 // Probabilities enter the second product rounded to bf16; everything else is
 // float.  Rows of V past the sequence end are zeroed while staging so that a
 // zero probability never meets an uninitialised (possibly NaN) value.
@@ -32,12 +34,11 @@
 namespace fxp {
 
 constexpr int kPfThreads = 256;
-constexpr int kPfQPerWave = 16;
-constexpr int kPfQTile = 64;        // query rows per workgroup
 constexpr int kPfKvTile = 64;       // keys per LDS tile (4 cache blocks)
 constexpr int kPfMinPieceTiles = 8; // a query tile's keys are cut into pieces of at least this many LDS tiles
 constexpr int kPfMaxPieces = 8;
-constexpr int kPfResidentWgs = 768; // workgroups of this kernel that the chip holds at a time (3 per compute unit)
+// workgroups of this kernel that the chip holds at a time: 3 per compute unit with 64 query rows, 2 with 128
+constexpr int prefill_resident_wgs(int q_tile) { return q_tile == 64 ? 768 : 512; }
 
 // Pieces that the keys of one query tile are cut into when the launch has too few query tiles to fill the chip (a short
 // chunk behind a long cached prefix): as many as the launch allows, each at least kPfMinPieceTiles tiles long.
@@ -47,9 +48,11 @@ __device__ inline int kv_pieces(int n_tiles, int kv_split)
     return min(kv_split, max(1, n_tiles / kPfMinPieceTiles));
 }
 
-template <int D, bool DEBUG, bool FLAT>
+template <int D, int QB, bool DEBUG, bool FLAT>
 __global__ __launch_bounds__(kPfThreads) void attn_prefill_kernel(PrefillAttnArgs a)
 {
+    constexpr int QW = 16 * QB;                   // query rows per wave
+    constexpr int QT = 4 * QW;                    // query rows per workgroup
     constexpr int KS = D / 32;                    // k-steps of the QK product
     constexpr int DT = D / 16;                    // 16-dim tiles of the output
     constexpr int kKPitch = D * 2 + 16;           // bytes per K row in LDS (conflict-free 16-byte reads)
@@ -65,9 +68,9 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_kernel(PrefillAttnArg
     const int h = blockIdx.x;
     const int piece = (int)blockIdx.y % a.kv_split, by = (int)blockIdx.y / a.kv_split, ny = (int)gridDim.y / a.kv_split;
     if constexpr (FLAT) {
-        // Query tiles of all sequences as one line: sequence i owns the slots from cu[i] / 64 + i on (cu = first
-        // token of the sequence).  The ranges cannot overlap (the next one starts at least ceil(len / 64) further)
-        // and the line is num_tokens / 64 + num_seqs long, so a batch of one long and many short prompts launches
+        // Query tiles of all sequences as one line: sequence i owns the slots from cu[i] / QT + i on (cu = first
+        // token of the sequence).  The ranges cannot overlap (the next one starts at least ceil(len / QT) further)
+        // and the line is num_tokens / QT + num_seqs long, so a batch of one long and many short prompts launches
         // about as many workgroups as it has tiles, not longest-prompt tiles times sequences.
         extern __shared__ int32_t s_cu[];             // [num_seqs + 1]
         for (int i = threadIdx.x; i <= a.num_seqs; i += kPfThreads) s_cu[i] = a.cu_seqlens_q[i];
@@ -75,16 +78,16 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_kernel(PrefillAttnArg
         seq = 0;
         int hi = a.num_seqs;
         const int slot = ny - 1 - by;
-        while (hi - seq > 1) { const int mid = (seq + hi) >> 1; if (s_cu[mid] / kPfQTile + mid <= slot) seq = mid; else hi = mid; }
+        while (hi - seq > 1) { const int mid = (seq + hi) >> 1; if (s_cu[mid] / QT + mid <= slot) seq = mid; else hi = mid; }
         t0 = s_cu[seq];
         q_len = s_cu[seq + 1] - t0;
-        qt = slot - (t0 / kPfQTile + seq);
-        if (qt * kPfQTile >= q_len) return;
+        qt = slot - (t0 / QT + seq);
+        if (qt * QT >= q_len) return;
     } else {
         seq = blockIdx.z;
         t0 = a.cu_seqlens_q[seq];
         q_len = a.cu_seqlens_q[seq + 1] - t0;
-        qt = (q_len + kPfQTile - 1) / kPfQTile - 1 - by;
+        qt = (q_len + QT - 1) / QT - 1 - by;
         if (qt < 0) return;
     }
     if (a.skip_single && q_len == 1) return;
@@ -94,28 +97,34 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_kernel(PrefillAttnArg
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int col = lane & 15, c = lane >> 4;
 
-    const int j0 = qt * kPfQTile + wave * kPfQPerWave;        // first query row of this wave
-    const int jq = j0 + col;                                   // this lane's query column
-    const int q_pos = ctx + jq;
-    const bool q_ok = jq < q_len;
-    const int wave_last_pos = ctx + min(j0 + kPfQPerWave - 1, q_len - 1);
-    const int wg_last_pos = ctx + min(qt * kPfQTile + kPfQTile - 1, q_len - 1);
+    const int j0 = qt * QT + wave * QW;                        // first query row of this wave
+    int jq[QB], q_pos[QB];                                     // this lane's query column in each column block
+#pragma unroll
+    for (int b = 0; b < QB; ++b) { jq[b] = j0 + 16 * b + col; q_pos[b] = ctx + jq[b]; }
+    const int wave_last_pos = ctx + min(j0 + QW - 1, q_len - 1);
+    const int wg_last_pos = ctx + min(qt * QT + QT - 1, q_len - 1);
     const int n_tiles = wg_last_pos / kPfKvTile + 1;
     const int n_pieces = kv_pieces(n_tiles, a.kv_split);
     if (piece >= n_pieces) return;
     const int tile_begin = (int)((int64_t)piece * n_tiles / n_pieces), tile_end = (int)((int64_t)(piece + 1) * n_tiles / n_pieces);
 
     // Q as column operand: lane holds Q[jq][32*ks + 8*c .. +7]
-    u32x4 qreg[KS];
-    {
-        const uint16_t *qp = a.q + ((int64_t)(t0 + min(jq, q_len - 1)) * a.n_q_heads + h) * D + c * 8;
+    u32x4 qreg[QB][KS];
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) qreg[ks] = ld16(qp + ks * 32);
+    for (int b = 0; b < QB; ++b) {
+        const uint16_t *qp = a.q + ((int64_t)(t0 + min(jq[b], q_len - 1)) * a.n_q_heads + h) * D + c * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) qreg[b][ks] = ld16(qp + ks * 32);
     }
-    f32x4_t o[DT];
+    f32x4_t o[QB][DT];
+    float m_run[QB], l_run[QB];
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt) o[dt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    float m_run = -INFINITY, l_run = 0.f;
+    for (int b = 0; b < QB; ++b) {
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) o[b][dt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        m_run[b] = -INFINITY;
+        l_run[b] = 0.f;
+    }
 
     const int64_t head_elems = (int64_t)kBlockTokens * D;
     const int64_t unit_elems = 2 * (int64_t)a.n_kv_heads * head_elems;
@@ -184,72 +193,79 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_kernel(PrefillAttnArg
         __builtin_amdgcn_sched_barrier(0);          // the requests go out before the products, not after them
         if (kv0 > wave_last_pos) continue;          // whole tile is in this wave's future (wave-uniform)
 
-        // ---- S^T = K . Q^T for the 4 sub-tiles of 16 keys
+        // ---- S^T = K . Q^T for the 4 sub-tiles of 16 keys; a K operand read from LDS serves every column block
         // (below the diagonal every key of the tile is visible to every query row of the wave:
         // no mask arithmetic there)
         const bool full_tile = !DEBUG && kv0 + kPfKvTile - 1 <= ctx + j0;
-        float s[4][4];
-        f32x4_t acc[4];
+        f32x4_t acc[QB][4];
 #pragma unroll
         for (int st = 0; st < 4; ++st) {
-            acc[st] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int b = 0; b < QB; ++b) acc[b][st] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
                 const u32x4 kop = *reinterpret_cast<const u32x4 *>(s_k + (st * 16 + col) * kKPitch + ks * 64 + c * 16);
-                acc[st] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kop),
-                                                                  __builtin_bit_cast(bf16x8_t, qreg[ks]), acc[st], 0, 0, 0);
+#pragma unroll
+                for (int b = 0; b < QB; ++b)
+                    acc[b][st] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kop),
+                                                                         __builtin_bit_cast(bf16x8_t, qreg[b][ks]), acc[b][st], 0, 0, 0);
             }
         }
-        if (full_tile) {
+        u32x4 pop[QB][2];                             // P^T column operands for sub-tile pairs (0,1) and (2,3)
+#pragma unroll
+        for (int b = 0; b < QB; ++b) {
+            float s[4][4];
+            if (full_tile) {
+#pragma unroll
+                for (int st = 0; st < 4; ++st)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) s[st][v] = acc[b][st][v] * a.scale_log2e;
+            } else {
+#pragma unroll
+                for (int st = 0; st < 4; ++st)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int kv = kv0 + st * 16 + 4 * c + v;
+                        const float sv = acc[b][st][v] * a.scale_log2e;
+                        s[st][v] = (kv <= q_pos[b]) ? sv : -INFINITY;
+                        if constexpr (DEBUG) {
+                            if (jq[b] < q_len && kv <= q_pos[b])
+                                a.dbg_scores[((int64_t)(t0 + jq[b]) * a.n_q_heads + h) * a.dbg_stride + kv] = sv;
+                        }
+                    }
+            }
+            // ---- online softmax per query column (lanes col, col+16, col+32, col+48)
+            float mx = m_run[b];
 #pragma unroll
             for (int st = 0; st < 4; ++st)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) s[st][v] = acc[st][v] * a.scale_log2e;
-        } else {
+                for (int v = 0; v < 4; ++v) mx = fmaxf(mx, s[st][v]);
+            mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float ms = (mx == -INFINITY) ? 0.f : mx;
+            const float alpha = __builtin_amdgcn_exp2f(m_run[b] - ms);
+            m_run[b] = mx;
+            float psum = 0.f;
 #pragma unroll
-            for (int st = 0; st < 4; ++st)
+            for (int u = 0; u < 2; ++u) {
+                float p[8];
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    const int kv = kv0 + st * 16 + 4 * c + v;
-                    const float sv = acc[st][v] * a.scale_log2e;
-                    s[st][v] = (kv <= q_pos) ? sv : -INFINITY;
-                    if constexpr (DEBUG) {
-                        if (q_ok && kv <= q_pos)
-                            a.dbg_scores[((int64_t)(t0 + jq) * a.n_q_heads + h) * a.dbg_stride + kv] = sv;
-                    }
+                    p[v] = __builtin_amdgcn_exp2f(s[2 * u][v] - ms);
+                    p[4 + v] = __builtin_amdgcn_exp2f(s[2 * u + 1][v] - ms);
                 }
-        }
-        // ---- online softmax per query column (lanes col, col+16, col+32, col+48)
-        float mx = m_run;
 #pragma unroll
-        for (int st = 0; st < 4; ++st)
-#pragma unroll
-            for (int v = 0; v < 4; ++v) mx = fmaxf(mx, s[st][v]);
-        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float ms = (mx == -INFINITY) ? 0.f : mx;
-        const float alpha = __builtin_amdgcn_exp2f(m_run - ms);
-        m_run = mx;
-        float psum = 0.f;
-        u32x4 pop[2];                                 // P^T column operands for sub-tile pairs (0,1) and (2,3)
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            float p[8];
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                p[v] = __builtin_amdgcn_exp2f(s[2 * u][v] - ms);
-                p[4 + v] = __builtin_amdgcn_exp2f(s[2 * u + 1][v] - ms);
+                for (int e = 0; e < 8; ++e) psum += p[e];
+                pop[b][u] = u32x4{pack_bf16x2(p[0], p[1]), pack_bf16x2(p[2], p[3]), pack_bf16x2(p[4], p[5]), pack_bf16x2(p[6], p[7])};
             }
+            l_run[b] = l_run[b] * alpha + psum;       // per lane; the four lanes of a column are added once at the end
+            // the accumulator rescale only when some row's maximum moved
+            if (__builtin_amdgcn_ballot_w64(alpha != 1.f)) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) psum += p[e];
-            pop[u] = u32x4{pack_bf16x2(p[0], p[1]), pack_bf16x2(p[2], p[3]), pack_bf16x2(p[4], p[5]), pack_bf16x2(p[6], p[7])};
+                for (int dt = 0; dt < DT; ++dt) o[b][dt] *= alpha;
+            }
         }
-        l_run = l_run * alpha + psum;                 // per lane; the four lanes of a column are added once at the end
-        // ---- O^T = O^T * alpha + V^T . P^T  (the rescale only when some row's maximum moved)
-        if (__builtin_amdgcn_ballot_w64(alpha != 1.f)) {
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt) o[dt] *= alpha;
-        }
+        // ---- O^T += V^T . P^T; a V^T operand read from LDS serves every column block
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
 #pragma unroll
@@ -261,36 +277,42 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_kernel(PrefillAttnArg
                 const u32x2 lo = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s *)(vsrc)));
                 const u32x2 hi = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s *)(vsrc + 16 * kVPitch)));
                 const u32x4 vop = {lo.x, lo.y, hi.x, hi.y};
-                o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, vop),
-                                                                __builtin_bit_cast(bf16x8_t, pop[u]), o[dt], 0, 0, 0);
+#pragma unroll
+                for (int b = 0; b < QB; ++b)
+                    o[b][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, vop),
+                                                                       __builtin_bit_cast(bf16x8_t, pop[b][u]), o[b][dt], 0, 0, 0);
             }
         }
     }
 
-    l_run += __shfl_xor(l_run, 16, 64);
-    l_run += __shfl_xor(l_run, 32, 64);
-    if (!q_ok) return;
-    if (n_pieces > 1) {
-        // one piece of several: unnormalised sums, running maximum and denominator go to the merge kernel.  A wave whose
-        // rows see none of this piece's keys (possible in the last piece only) hands over m = -inf, l = 0, o = 0.
-        const int64_t row = ((int64_t)piece * a.num_tokens + t0 + jq) * a.n_q_heads + h;
-        float *pa = a.part_acc + row * D + 4 * c;
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) *reinterpret_cast<f32x4_t *>(pa + dt * 16) = o[dt];
-        if (c == 0) { a.part_ml[row * 2] = m_run; a.part_ml[row * 2 + 1] = l_run; }
-        return;
-    }
-    const float inv = 1.f / l_run;
-    uint16_t *op = a.out + ((int64_t)(t0 + jq) * a.n_q_heads + h) * D + 4 * c;
+    for (int b = 0; b < QB; ++b) {
+        float l = l_run[b];
+        l += __shfl_xor(l, 16, 64);
+        l += __shfl_xor(l, 32, 64);
+        if (jq[b] >= q_len) continue;
+        if (n_pieces > 1) {
+            // one piece of several: unnormalised sums, running maximum and denominator go to the merge kernel.  A wave whose
+            // rows see none of this piece's keys hands over m = -inf, l = 0, o = 0.
+            const int64_t row = ((int64_t)piece * a.num_tokens + t0 + jq[b]) * a.n_q_heads + h;
+            float *pa = a.part_acc + row * D + 4 * c;
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt) {
-        const u32x2 w = {pack_bf16x2(o[dt][0] * inv, o[dt][1] * inv), pack_bf16x2(o[dt][2] * inv, o[dt][3] * inv)};
-        *reinterpret_cast<u32x2 *>(op + dt * 16) = w;
-    }
-    if constexpr (DEBUG) {
-        if (c == 0) {
-            float *ml = a.dbg_ml + ((int64_t)(t0 + jq) * a.n_q_heads + h) * 3;
-            ml[0] = m_run; ml[1] = l_run; ml[2] = __int_as_float(q_pos + 1);
+            for (int dt = 0; dt < DT; ++dt) *reinterpret_cast<f32x4_t *>(pa + dt * 16) = o[b][dt];
+            if (c == 0) { a.part_ml[row * 2] = m_run[b]; a.part_ml[row * 2 + 1] = l; }
+            continue;
+        }
+        const float inv = 1.f / l;
+        uint16_t *op = a.out + ((int64_t)(t0 + jq[b]) * a.n_q_heads + h) * D + 4 * c;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+            const u32x2 w = {pack_bf16x2(o[b][dt][0] * inv, o[b][dt][1] * inv), pack_bf16x2(o[b][dt][2] * inv, o[b][dt][3] * inv)};
+            *reinterpret_cast<u32x2 *>(op + dt * 16) = w;
+        }
+        if constexpr (DEBUG) {
+            if (c == 0) {
+                float *ml = a.dbg_ml + ((int64_t)(t0 + jq[b]) * a.n_q_heads + h) * 3;
+                ml[0] = m_run[b]; ml[1] = l; ml[2] = __int_as_float(q_pos[b] + 1);
+            }
         }
     }
 }
@@ -307,8 +329,8 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_merge_kernel(PrefillA
     const int seq = a.tok_seq[t];
     const int t0 = a.cu_seqlens_q[seq], q_len = a.cu_seqlens_q[seq + 1] - t0;
     if (a.skip_single && q_len == 1) return;
-    const int qt = (t - t0) / kPfQTile;
-    const int wg_last_pos = a.ctx_lens[seq] + min(qt * kPfQTile + kPfQTile - 1, q_len - 1);
+    const int qt = (t - t0) / a.q_tile;
+    const int wg_last_pos = a.ctx_lens[seq] + min(qt * a.q_tile + a.q_tile - 1, q_len - 1);
     const int n_pieces = kv_pieces(wg_last_pos / kPfKvTile + 1, a.kv_split);
     if (n_pieces == 1) return;
     const int64_t piece_stride = (int64_t)a.num_tokens * a.n_q_heads;
@@ -337,12 +359,26 @@ __global__ void attn_probs_normalize_kernel(float *scores, const float *ml, int6
         scores[row * stride + r] = __builtin_amdgcn_exp2f(scores[row * stride + r] - m) / l;
 }
 
+// Query rows per workgroup: 128 (two column blocks per wave) when the prompts are long enough to fill such tiles and
+// there are enough of them for every compute unit -- counting the pieces their keys may be cut into when the block
+// table is wide enough for a long cached prefix -- else 64.
+int prefill_q_tile(int n_q_heads, int num_tokens, int num_seqs, int max_blocks_per_seq)
+{
+    static const int forced = getenv("FXP_PREFILL_Q_TILE") ? atoi(getenv("FXP_PREFILL_Q_TILE")) : 0;
+    if (forced == 64 || forced == 128) return forced;
+    if (num_tokens < 128 * (int64_t)std::max(num_seqs, 1)) return 64;
+    const int64_t tiles = (int64_t)n_q_heads * (num_tokens / 128);
+    if (tiles >= 256) return 128;
+    const bool wide = (int64_t)max_blocks_per_seq * kBlockTokens >= 2 * kPfMinPieceTiles * kPfKvTile;
+    return wide && tiles * kPfMaxPieces >= prefill_resident_wgs(128) ? 128 : 64;
+}
 size_t prefill_piece_rows(int n_q_heads, int max_tokens)
 {
-    // rows of [piece][token][head]: pieces * heads * tiles <= kPfResidentWgs with 64 tokens per tile, and pieces <= kPfMaxPieces
-    return std::min<size_t>((size_t)kPfResidentWgs * kPfQTile, (size_t)kPfMaxPieces * (size_t)std::max(max_tokens, 1) * n_q_heads);
+    // rows of [piece][token][head]: pieces * heads * tiles <= the resident workgroups, q_tile tokens per tile, pieces <= kPfMaxPieces
+    const size_t by_wgs = std::max((size_t)prefill_resident_wgs(64) * 64, (size_t)prefill_resident_wgs(128) * 128);
+    return std::min<size_t>(by_wgs, (size_t)kPfMaxPieces * (size_t)std::max(max_tokens, 1) * n_q_heads);
 }
-int prefill_kv_split(int n_q_heads, int num_tokens, int num_seqs, int max_blocks_per_seq)
+int prefill_kv_split(int n_q_heads, int num_tokens, int num_seqs, int max_blocks_per_seq, int q_tile)
 {
     static const int forced = getenv("FXP_PREFILL_KV_SPLIT") ? atoi(getenv("FXP_PREFILL_KV_SPLIT")) : 0;
     const int64_t rows = (int64_t)std::max(num_tokens, 1) * n_q_heads;
@@ -350,37 +386,48 @@ int prefill_kv_split(int n_q_heads, int num_tokens, int num_seqs, int max_blocks
     if (forced > 0) return (int)std::max<int64_t>(1, std::min<int64_t>(std::min(forced, kPfMaxPieces), fits));
     // no sequence can hold two pieces' worth of keys: nothing to cut
     if ((int64_t)max_blocks_per_seq * kBlockTokens < 2 * kPfMinPieceTiles * kPfKvTile) return 1;
-    const int64_t wgs = (int64_t)n_q_heads * (num_tokens / kPfQTile + num_seqs);      // upper bound of the live workgroups
-    return (int)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(kPfMaxPieces, kPfResidentWgs / wgs), fits));
+    const int64_t wgs = (int64_t)n_q_heads * (num_tokens / q_tile + num_seqs);      // upper bound of the live workgroups
+    return (int)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(kPfMaxPieces, prefill_resident_wgs(q_tile) / wgs), fits));
+}
+
+template <int D, int QB>
+static hipError_t launch_q(const PrefillAttnArgs &a, hipStream_t stream)
+{
+    constexpr int QT = 64 * QB;
+    // one line of tiles when the rectangle (tiles of the longest prompt x sequences) would be more than eight times as
+    // large (an empty workgroup costs a few nanoseconds, which only matters when there are very many of them)
+    const int rect_x = (a.max_q_len + QT - 1) / QT, flat_x = a.num_tokens / QT + a.num_seqs;
+    static const int forced = getenv("FXP_PREFILL_FLAT_GRID") ? atoi(getenv("FXP_PREFILL_FLAT_GRID")) : -1;
+    const bool flat = forced >= 0 ? forced != 0 : (int64_t)rect_x * a.num_seqs > 8 * (int64_t)flat_x;
+    const dim3 grid = flat ? dim3(a.n_q_heads, flat_x * a.kv_split) : dim3(a.n_q_heads, rect_x * a.kv_split, a.num_seqs);
+    const size_t lds = flat ? (size_t)(a.num_seqs + 1) * sizeof(int32_t) : 0;
+    if constexpr (QB == 1) {
+        if (a.dbg_scores) {
+            if (flat) hipLaunchKernelGGL((attn_prefill_kernel<D, 1, true, true>), grid, dim3(kPfThreads), lds, stream, a);
+            else hipLaunchKernelGGL((attn_prefill_kernel<D, 1, true, false>), grid, dim3(kPfThreads), lds, stream, a);
+            hipLaunchKernelGGL(attn_probs_normalize_kernel, dim3(a.num_tokens * a.n_q_heads), dim3(64), 0, stream,
+                               a.dbg_scores, a.dbg_ml, a.dbg_stride);
+            return hipGetLastError();
+        }
+    }
+    if (flat) hipLaunchKernelGGL((attn_prefill_kernel<D, QB, false, true>), grid, dim3(kPfThreads), lds, stream, a);
+    else hipLaunchKernelGGL((attn_prefill_kernel<D, QB, false, false>), grid, dim3(kPfThreads), lds, stream, a);
+    if (a.kv_split > 1) {
+        constexpr int kRowsPerWg = kPfThreads / (D / 4);
+        const int64_t rows = (int64_t)a.num_tokens * a.n_q_heads;
+        hipLaunchKernelGGL((attn_prefill_merge_kernel<D>), dim3((unsigned)((rows + kRowsPerWg - 1) / kRowsPerWg)), dim3(kPfThreads), 0, stream, a);
+    }
+    return hipGetLastError();
 }
 
 template <int D>
 static hipError_t launch_d(const PrefillAttnArgs &a_in, hipStream_t stream)
 {
     PrefillAttnArgs a = a_in;
-    if (a.dbg_scores || !a.part_acc || a.kv_split < 1) a.kv_split = 1;      // the probability dump runs every tile as one piece
-    // one line of tiles when the rectangle (tiles of the longest prompt x sequences) would be more than eight times as
-    // large (an empty workgroup costs a few nanoseconds, which only matters when there are very many of them)
-    const int rect_x = (a.max_q_len + kPfQTile - 1) / kPfQTile, flat_x = a.num_tokens / kPfQTile + a.num_seqs;
-    static const int forced = getenv("FXP_PREFILL_FLAT_GRID") ? atoi(getenv("FXP_PREFILL_FLAT_GRID")) : -1;
-    const bool flat = forced >= 0 ? forced != 0 : (int64_t)rect_x * a.num_seqs > 8 * (int64_t)flat_x;
-    const dim3 grid = flat ? dim3(a.n_q_heads, flat_x * a.kv_split) : dim3(a.n_q_heads, rect_x * a.kv_split, a.num_seqs);
-    const size_t lds = flat ? (size_t)(a.num_seqs + 1) * sizeof(int32_t) : 0;
-    if (a.dbg_scores) {
-        if (flat) hipLaunchKernelGGL((attn_prefill_kernel<D, true, true>), grid, dim3(kPfThreads), lds, stream, a);
-        else hipLaunchKernelGGL((attn_prefill_kernel<D, true, false>), grid, dim3(kPfThreads), lds, stream, a);
-        hipLaunchKernelGGL(attn_probs_normalize_kernel, dim3(a.num_tokens * a.n_q_heads), dim3(64), 0, stream,
-                           a.dbg_scores, a.dbg_ml, a.dbg_stride);
-    } else {
-        if (flat) hipLaunchKernelGGL((attn_prefill_kernel<D, false, true>), grid, dim3(kPfThreads), lds, stream, a);
-        else hipLaunchKernelGGL((attn_prefill_kernel<D, false, false>), grid, dim3(kPfThreads), lds, stream, a);
-        if (a.kv_split > 1) {
-            constexpr int kRowsPerWg = kPfThreads / (D / 4);
-            const int64_t rows = (int64_t)a.num_tokens * a.n_q_heads;
-            hipLaunchKernelGGL((attn_prefill_merge_kernel<D>), dim3((unsigned)((rows + kRowsPerWg - 1) / kRowsPerWg)), dim3(kPfThreads), 0, stream, a);
-        }
-    }
-    return hipGetLastError();
+    // the probability dump runs every tile as one piece, 64 rows per workgroup
+    if (a.dbg_scores || !a.part_acc || a.kv_split < 1) a.kv_split = 1;
+    if (a.dbg_scores || a.q_tile != 128) a.q_tile = 64;
+    return a.q_tile == 128 ? launch_q<D, 2>(a, stream) : launch_q<D, 1>(a, stream);
 }
 
 hipError_t launch_attn_prefill(const PrefillAttnArgs &a, hipStream_t stream)

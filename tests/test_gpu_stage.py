@@ -135,6 +135,9 @@ PREFILL_CASES = [
     ("chunks-behind-prefixes", GQA64, 1, [2100, 0, 600, 1030], [100, 130, 64, 3]),
     ("mixed-long-prefix", TINY, 1, [3000, 900, 2047], [33, 1, 1]),
     ("gqa128-long-prefix", GQA128, 1, [1100, 40], [80, 5]),
+    # long prompts: 128 query rows per workgroup (two column blocks per wave), with and without cut keys, ragged last tile
+    ("wide-tiles-long-chunk", TINY, 1, [1100], [2100]),
+    ("wide-tiles-gqa128", GQA128, 1, [0, 200], [1100, 300]),
     ("opt-prompts", OPT_TINY, 2, [0, 0, 0, 0], [37, 128, 32, 100]),
     ("opt-small", OPT_TINY, 2, [0, 0], [20, 45]),
     ("opt-chunked", OPT_GQA, 1, [16, 70, 33], [48, 10, 64]),
