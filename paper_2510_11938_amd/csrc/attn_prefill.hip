@@ -171,16 +171,12 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_kernel(PrefillAttnArg
             vreg[i] = ld16(kp + v_off);
         }
     };
-    fetch_tile(tile_begin);
-
-    for (int tile = tile_begin; tile < tile_end; ++tile) {
-        const int kv0 = tile * kPfKvTile;
-        // ---- stage K and V (both row-major, padded pitches) of keys kv0 .. kv0+63
-        __syncthreads();
+    // stage K and V (both row-major, padded pitches) of the tile held in registers
+    auto store_tile = [&](int tile) {
         if (tile == last_tile) {
 #pragma unroll
             for (int i = 0; i < kChunksPerThread; ++i)
-                if (kv0 + r0 + i * kRowsPerPass >= n_keys) vreg[i] = u32x4{0u, 0u, 0u, 0u};
+                if (tile * kPfKvTile + r0 + i * kRowsPerPass >= n_keys) vreg[i] = u32x4{0u, 0u, 0u, 0u};
         }
 #pragma unroll
         for (int i = 0; i < kChunksPerThread; ++i) {
@@ -188,6 +184,13 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_kernel(PrefillAttnArg
             *reinterpret_cast<u32x4 *>(s_k + r * kKPitch + dc0 * 16) = kreg[i];
             *reinterpret_cast<u32x4 *>(s_v + r * kVPitch + dc0 * 16) = vreg[i];
         }
+    };
+    fetch_tile(tile_begin);
+
+    for (int tile = tile_begin; tile < tile_end; ++tile) {
+        const int kv0 = tile * kPfKvTile;
+        __syncthreads();
+        store_tile(tile);
         __syncthreads();
         if (tile + 1 < tile_end) fetch_tile(tile + 1);
         __builtin_amdgcn_sched_barrier(0);          // the requests go out before the products, not after them
@@ -197,40 +200,68 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_kernel(PrefillAttnArg
         // (below the diagonal every key of the tile is visible to every query row of the wave:
         // no mask arithmetic there)
         const bool full_tile = !DEBUG && kv0 + kPfKvTile - 1 <= ctx + j0;
+        // The operands of the next sub-tile are requested before the products of the current one (the compiler
+        // on its own asks for each operand right before its use and then waits out the LDS latency 8 times per phase);
+        // the scheduling barriers keep that order.
         f32x4_t acc[QB][4];
+        u32x4 kop[2][KS];
+        auto read_k = [&](int st, u32x4 (&dst)[KS]) {
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+                dst[ks] = *reinterpret_cast<const u32x4 *>(s_k + (st * 16 + col) * kKPitch + ks * 64 + c * 16);
+        };
+        read_k(0, kop[0]);
 #pragma unroll
         for (int st = 0; st < 4; ++st) {
+            if (st + 1 < 4) read_k(st + 1, kop[(st + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int b = 0; b < QB; ++b) acc[b][st] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                const u32x4 kop = *reinterpret_cast<const u32x4 *>(s_k + (st * 16 + col) * kKPitch + ks * 64 + c * 16);
+            for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
                 for (int b = 0; b < QB; ++b)
-                    acc[b][st] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kop),
+                    acc[b][st] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kop[st & 1][ks]),
                                                                          __builtin_bit_cast(bf16x8_t, qreg[b][ks]), acc[b][st], 0, 0, 0);
-            }
+            __builtin_amdgcn_sched_barrier(0);
         }
+        // the first V^T operands travel while the softmax runs
+        u32x4 vop[2][2];
+        auto read_v = [&](int dt, u32x4 (&dst)[2]) {
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                // row operand: dim 16*dt + col; k slots 8c..8c+3 = keys 32u+4c.., 8c+4.. = keys 32u+16+4c..
+                // LDS transpose load: lane j' of a 16-lane group points at key 4c + j'/4, dims
+                // 4*(j'%4)..+3 of the tile; the hardware hands lane i the four keys of dim i.
+                const char *vsrc = s_v + (32 * u + 4 * c + (col >> 2)) * kVPitch + dt * 32 + (col & 3) * 8;
+                const u32x2 lo = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s *)(vsrc)));
+                const u32x2 hi = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s *)(vsrc + 16 * kVPitch)));
+                dst[u] = u32x4{lo.x, lo.y, hi.x, hi.y};
+            }
+        };
+        read_v(0, vop[0]);
+        __builtin_amdgcn_sched_barrier(0);
         u32x4 pop[QB][2];                             // P^T column operands for sub-tile pairs (0,1) and (2,3)
 #pragma unroll
         for (int b = 0; b < QB; ++b) {
+            // scores stay unscaled: the scale (log2(e) / sqrt(D), positive) is applied inside the exponent's
+            // multiply-add, and the running maximum is kept unscaled too
             float s[4][4];
             if (full_tile) {
 #pragma unroll
                 for (int st = 0; st < 4; ++st)
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) s[st][v] = acc[b][st][v] * a.scale_log2e;
+                    for (int v = 0; v < 4; ++v) s[st][v] = acc[b][st][v];
             } else {
 #pragma unroll
                 for (int st = 0; st < 4; ++st)
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
                         const int kv = kv0 + st * 16 + 4 * c + v;
-                        const float sv = acc[b][st][v] * a.scale_log2e;
-                        s[st][v] = (kv <= q_pos[b]) ? sv : -INFINITY;
+                        s[st][v] = (kv <= q_pos[b]) ? acc[b][st][v] : -INFINITY;
                         if constexpr (DEBUG) {
                             if (jq[b] < q_len && kv <= q_pos[b])
-                                a.dbg_scores[((int64_t)(t0 + jq[b]) * a.n_q_heads + h) * a.dbg_stride + kv] = sv;
+                                a.dbg_scores[((int64_t)(t0 + jq[b]) * a.n_q_heads + h) * a.dbg_stride + kv] = acc[b][st][v] * a.scale_log2e;
                         }
                     }
             }
@@ -243,16 +274,17 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_kernel(PrefillAttnArg
             mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
             mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
             const float ms = (mx == -INFINITY) ? 0.f : mx;
-            const float alpha = __builtin_amdgcn_exp2f(m_run[b] - ms);
+            const float alpha = __builtin_amdgcn_exp2f((m_run[b] - ms) * a.scale_log2e);
             m_run[b] = mx;
+            const float neg_ms = -ms * a.scale_log2e;
             float psum = 0.f;
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
                 float p[8];
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    p[v] = __builtin_amdgcn_exp2f(s[2 * u][v] - ms);
-                    p[4 + v] = __builtin_amdgcn_exp2f(s[2 * u + 1][v] - ms);
+                    p[v] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[2 * u][v], a.scale_log2e, neg_ms));
+                    p[4 + v] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[2 * u + 1][v], a.scale_log2e, neg_ms));
                 }
 #pragma unroll
                 for (int e = 0; e < 8; ++e) psum += p[e];
@@ -266,22 +298,18 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_kernel(PrefillAttnArg
             }
         }
         // ---- O^T += V^T . P^T; a V^T operand read from LDS serves every column block
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
+            if (dt + 1 < DT) read_v(dt + 1, vop[(dt + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                // row operand: dim 16*dt + col; k slots 8c..8c+3 = keys 32u+4c.., 8c+4.. = keys 32u+16+4c..
-                // LDS transpose load: lane j' of a 16-lane group points at key 4c + j'/4, dims
-                // 4*(j'%4)..+3 of the tile; the hardware hands lane i the four keys of dim i.
-                const char *vsrc = s_v + (32 * u + 4 * c + (col >> 2)) * kVPitch + dt * 32 + (col & 3) * 8;
-                const u32x2 lo = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s *)(vsrc)));
-                const u32x2 hi = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s *)(vsrc + 16 * kVPitch)));
-                const u32x4 vop = {lo.x, lo.y, hi.x, hi.y};
+            for (int u = 0; u < 2; ++u)
 #pragma unroll
                 for (int b = 0; b < QB; ++b)
-                    o[b][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, vop),
+                    o[b][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, vop[dt & 1][u]),
                                                                        __builtin_bit_cast(bf16x8_t, pop[b][u]), o[b][dt], 0, 0, 0);
-            }
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
 
@@ -298,7 +326,7 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_kernel(PrefillAttnArg
             float *pa = a.part_acc + row * D + 4 * c;
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt) *reinterpret_cast<f32x4_t *>(pa + dt * 16) = o[b][dt];
-            if (c == 0) { a.part_ml[row * 2] = m_run[b]; a.part_ml[row * 2 + 1] = l; }
+            if (c == 0) { a.part_ml[row * 2] = m_run[b] * a.scale_log2e; a.part_ml[row * 2 + 1] = l; }
             continue;
         }
         const float inv = 1.f / l;
@@ -311,7 +339,7 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_kernel(PrefillAttnArg
         if constexpr (DEBUG) {
             if (c == 0) {
                 float *ml = a.dbg_ml + ((int64_t)(t0 + jq[b]) * a.n_q_heads + h) * 3;
-                ml[0] = m_run[b]; ml[1] = l; ml[2] = __int_as_float(q_pos[b] + 1);
+                ml[0] = m_run[b] * a.scale_log2e; ml[1] = l; ml[2] = __int_as_float(q_pos[b] + 1);
             }
         }
     }
