@@ -62,11 +62,13 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_kernel(PrefillAttnArg
     __shared__ __attribute__((aligned(16))) char s_v[kPfKvTile * kVPitch];
 
     // Workgroups are launched in index order and a causal tile's work grows with its position in the sequence:
-    // heads vary fastest and the tiles are taken from the last one down, so the long tiles start first and the
-    // short ones fill the tail of the launch.
+    // heads vary fastest, then sequences, and the tiles are taken from the last one of every sequence down, so
+    // the long tiles of all sequences start first and the short ones fill the tail of the launch.
     int seq, t0, q_len, qt;
     const int h = blockIdx.x;
-    const int piece = (int)blockIdx.y % a.kv_split, by = (int)blockIdx.y / a.kv_split, ny = (int)gridDim.y / a.kv_split;
+    // the tile index (from the last one down) and the piece share the slowest grid dimension that is used
+    const int slow = FLAT ? (int)blockIdx.y : (int)blockIdx.z;
+    const int piece = slow % a.kv_split, by = slow / a.kv_split;
     if constexpr (FLAT) {
         // Query tiles of all sequences as one line: sequence i owns the slots from cu[i] / QT + i on (cu = first
         // token of the sequence).  The ranges cannot overlap (the next one starts at least ceil(len / QT) further)
@@ -77,14 +79,14 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_kernel(PrefillAttnArg
         __syncthreads();
         seq = 0;
         int hi = a.num_seqs;
-        const int slot = ny - 1 - by;
+        const int slot = (int)gridDim.y / a.kv_split - 1 - by;
         while (hi - seq > 1) { const int mid = (seq + hi) >> 1; if (s_cu[mid] / QT + mid <= slot) seq = mid; else hi = mid; }
         t0 = s_cu[seq];
         q_len = s_cu[seq + 1] - t0;
         qt = slot - (t0 / QT + seq);
         if (qt * QT >= q_len) return;
     } else {
-        seq = blockIdx.z;
+        seq = blockIdx.y;
         t0 = a.cu_seqlens_q[seq];
         q_len = a.cu_seqlens_q[seq + 1] - t0;
         qt = (q_len + QT - 1) / QT - 1 - by;
@@ -427,7 +429,7 @@ static hipError_t launch_q(const PrefillAttnArgs &a, hipStream_t stream)
     const int rect_x = (a.max_q_len + QT - 1) / QT, flat_x = a.num_tokens / QT + a.num_seqs;
     static const int forced = getenv("FXP_PREFILL_FLAT_GRID") ? atoi(getenv("FXP_PREFILL_FLAT_GRID")) : -1;
     const bool flat = forced >= 0 ? forced != 0 : (int64_t)rect_x * a.num_seqs > 8 * (int64_t)flat_x;
-    const dim3 grid = flat ? dim3(a.n_q_heads, flat_x * a.kv_split) : dim3(a.n_q_heads, rect_x * a.kv_split, a.num_seqs);
+    const dim3 grid = flat ? dim3(a.n_q_heads, flat_x * a.kv_split) : dim3(a.n_q_heads, a.num_seqs, rect_x * a.kv_split);
     const size_t lds = flat ? (size_t)(a.num_seqs + 1) * sizeof(int32_t) : 0;
     if constexpr (QB == 1) {
         if (a.dbg_scores) {
