@@ -138,6 +138,7 @@ PREFILL_CASES = [
     # long prompts: 128 query rows per workgroup (two column blocks per wave), with and without cut keys, ragged last tile
     ("wide-tiles-long-chunk", TINY, 1, [1100], [2100]),
     ("wide-tiles-gqa128", GQA128, 1, [0, 200], [1100, 300]),
+    ("wide-tiles-one-line", TINY, 1, [0] * 20, [3200] + [100] * 19),          # ... launched as one line of tiles, keys cut in two
     ("opt-prompts", OPT_TINY, 2, [0, 0, 0, 0], [37, 128, 32, 100]),
     ("opt-small", OPT_TINY, 2, [0, 0], [20, 45]),
     ("opt-chunked", OPT_GQA, 1, [16, 70, 33], [48, 10, 64]),
