@@ -154,6 +154,31 @@ def test_prefill_matches_oracle(name, ms, L, ctx, q):
     check_appended_rows(case, cache, opool)
 
 
+RANDOM_SHAPES = [TINY, GQA64, MID128, GQA128, KV6, GQA_KV3, ODD_K, OPT_TINY, OPT_GQA]
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_ragged_batches_match_oracle(seed):
+    # seeded sweep over what the launch rules branch on: shape, number of sequences, how many of them are decode rows,
+    # chunk lengths around the 16 / 64 / 128-row tile edges, and cached prefixes from none to several key pieces
+    rng = np.random.default_rng(1000 + seed)
+    ms = RANDOM_SHAPES[seed % len(RANDOM_SHAPES)]
+    B = int(rng.integers(1, 9))
+    p_decode = float(rng.choice([0.0, 0.5, 1.0]))
+    q, ctx = [], []
+    for _ in range(B):
+        if rng.random() < p_decode:
+            q.append(1)
+        else:
+            q.append(int(rng.choice([2, 15, 16, 17, 63, 64, 65, 127, 128, 129, 200, 300])) + int(rng.integers(0, 3)))
+        ctx.append(int(rng.choice([0, 0, 1, 15, 16, 100, 513, 1100, 2300])) + int(rng.integers(0, 5)))
+    case = Case(ms, 1 + seed % 2, ctx, q, seed=50 + seed)
+    want, opool = case.oracle_run()
+    got, cache = case.gpu_run()
+    assert rel_err(host_f64(got), want) <= TOL_OUT, (ms, q, ctx)
+    check_appended_rows(case, cache, opool)
+
+
 def test_prefill_then_decode_end_to_end_on_gpu_cache():
     # the GPU decodes on top of the cache its own prefill wrote; the oracle does the same with its float cache
     ms, L = TINY, 2
