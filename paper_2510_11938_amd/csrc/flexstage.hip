@@ -147,9 +147,10 @@ SkinnyCfg skinny_cfg(int N, int K, int M)
     const int wgs_n = (N + 64 * c.R - 1) / (64 * c.R);
     int s = 1;
     if (M > 32) {
-        // 33..64 rows: the token rows cost a workgroup as much L2 traffic as its weights cost HBM traffic,
-        // and more, smaller workgroups hide that better (13B shape, 64 rows: 168 -> 156 us per layer)
-        static const int wgs64 = env_int("FXP_SKINNY_MAX_WGS64", 512), cap64 = env_int("FXP_SKINNY_CAP64", 12);
+        // 33..64 rows: one workgroup per CU as well, with the ring of four register buffers (two workgroups per CU
+        // with two buffers each had been the better of the two-buffer forms; with four buffers one per CU wins on
+        // every shape tried: 7B 64 rows 117 -> 106 us per layer, 13B 143 -> 135, 70B 313 -> 305)
+        static const int wgs64 = env_int("FXP_SKINNY_MAX_WGS64", 256), cap64 = env_int("FXP_SKINNY_CAP64", 12);
         s = std::max(1, std::min(std::min(cap64, ks / 16), wgs64 / wgs_n));
     } else {
         // up to 32 rows: as many workgroups as fit once on a 256-CU chip, any integer split (13B and 70B shapes:
@@ -480,12 +481,12 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
         a.W = (const uint16_t *)wbase; a.X = X; a.P = w.P; a.A = nullptr; a.bias = nullptr; a.act = 0;
         a.M = T; a.N = N; a.K = K; a.KS = k_steps(K); a.NT = N / 16; a.ldx = ldx; a.S = skinny_cfg(N, K, T).S; a.R = skinny_cfg(N, K, T).R;
         // register ring of the weight stream (NB buffers of U k-steps), measured: four buffers of two k-steps
-        // beat two of four everywhere up to 32 rows (7B shape: 96 -> 90 us per layer) and in the unsplit form
-        // with its long k range (13B shape, 64 rows: 62 -> 53 us); the short k ranges of the split form at
-        // 33..64 rows do not fill a deeper ring and keep two buffers
+        // beat two of four everywhere up to 32 rows (7B shape: 96 -> 90 us per layer), in the unsplit form
+        // with its long k range (13B shape, 64 rows: 62 -> 53 us), and at 33..64 rows once there is one workgroup
+        // per CU (a shape whose registers do not allow four buffers falls back to two in the launcher)
         static const int forced_u = env_int("FXP_SKINNY_U", 0), forced_nb = env_int("FXP_SKINNY_NB", 0);
         a.U = forced_u ? forced_u : 2;
-        a.NB = forced_nb ? forced_nb : ((T <= 32 || act_out) ? 4 : 2);
+        a.NB = forced_nb ? forced_nb : 4;
         if (act_out) {       // activation in the epilogue: no split; for SwiGLU the gate and the up tile sit in one wavefront
             a.A = act_out; a.S = 1; a.R = 2;
             if (act_bias) { a.act = 1; a.bias = act_bias; }
