@@ -141,7 +141,10 @@ SkinnyCfg skinny_cfg(int N, int K, int M)
         // time of the launch; measured: 320 workgroups 57 us, 240 workgroups 45 us).  With several hundred
         // token rows a narrow matrix still has few tiles (hidden 4096: 16 x rows/128) and is split as well.
         const int wgs = ((N + 255) / 256) * ((M + 127) / 128);
-        c.S = forced_s ? forced_s : std::max(1, std::min(std::min(8, ks / 8), 256 / wgs));
+        // Up to 16 pieces: a narrow matrix at 65..128 rows (hidden 4096 or 5120: 16 or 20 tiles) otherwise fills half
+        // the chip, which costs more than the extra partial sums (7B shape, 128 rows: 130 -> 123 us per layer).
+        static const int cap = env_int("FXP_TILED_SPLIT_CAP", 16);
+        c.S = forced_s ? forced_s : std::max(1, std::min(std::min(cap, ks / 8), 256 / wgs));
         return c;
     }
     const int wgs_n = (N + 64 * c.R - 1) / (64 * c.R);
