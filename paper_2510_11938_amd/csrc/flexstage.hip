@@ -256,7 +256,10 @@ Workspace carve(const fxp_stage_desc &d, int T, int B, int max_blocks, char *bas
     }
     w.P = (float *)take(pmax);
     (void)max_blocks;
-    w.n_workers = device_cus() * env_int("FXP_DECODE_WORKERS_PER_CU", fxp::kDecodeWorkersPerCu) / 4 * 4;
+    // wavefronts of the decode attention kernel per CU: eight, but four for the grouped-query kernel at head_dim 128,
+    // whose wavefronts each keep twice the bytes in flight (70B shape, batch 128: 373 -> 360 us per layer)
+    const int per_cu = (d.n_q_heads != d.n_kv_heads && d.head_dim == 128) ? fxp::kDecodeWorkersPerCu / 2 : fxp::kDecodeWorkersPerCu;
+    w.n_workers = device_cus() * env_int("FXP_DECODE_WORKERS_PER_CU", per_cu) / 4 * 4;
     const size_t rows = ((size_t)w.n_workers + (size_t)(B > 0 ? B : 1) * d.n_kv_heads) * (d.n_q_heads / d.n_kv_heads);
     w.part_acc = (float *)take(rows * d.head_dim * 4);
     w.part_ml = (float *)take(rows * 2 * 4);

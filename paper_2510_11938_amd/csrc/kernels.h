@@ -138,7 +138,7 @@ struct RopeArgs {
 hipError_t launch_qkv_rope_kvwrite(const RopeArgs &a, hipStream_t stream);
 
 // ---------------------------------------------------------------- attention
-constexpr int kDecodeWorkersPerCu = 8;    // wavefronts of the decode kernel per compute unit
+constexpr int kDecodeWorkersPerCu = 8;    // wavefronts of the decode kernel per compute unit (half of it for grouped queries at head_dim 128)
 
 struct DecodeAttnArgs {
     const uint16_t *q;     // [num_seqs][Hq][D] bf16 (rotated)
