@@ -135,6 +135,9 @@ PREFILL_CASES = [
     ("chunks-behind-prefixes", GQA64, 1, [2100, 0, 600, 1030], [100, 130, 64, 3]),
     ("mixed-long-prefix", TINY, 1, [3000, 900, 2047], [33, 1, 1]),
     ("gqa128-long-prefix", GQA128, 1, [1100, 40], [80, 5]),
+    # key walks longer than one 16-tile stretch of block-table entries, uncut (many sequences) and cut in two
+    ("many-pairs-long-prefix", TINY, 1, [1100 + (7 * i) % 500 for i in range(200)], [2] * 200),
+    ("chunks-long-pieces", GQA64, 1, [2500 + 37 * i for i in range(30)], [40] * 30),
     # long prompts: 128 query rows per workgroup (two column blocks per wave), with and without cut keys, ragged last tile
     ("wide-tiles-long-chunk", TINY, 1, [1100], [2100]),
     ("wide-tiles-gqa128", GQA128, 1, [0, 200], [1100, 300]),
