@@ -87,7 +87,7 @@ def bench_prefill(args, wl) -> int:
     mq = int(lens.max())
 
     def step():
-        stage.forward(cache, cu, cl, x, mq, hidden_out=y)
+        stage.forward(cache, cu, cl, x, mq, hidden_out=y, min_q_len=int(lens.min()))
 
     for _ in range(args.warmup):
         step()

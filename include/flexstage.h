@@ -110,6 +110,10 @@ typedef struct {
     const int32_t *cu_seqlens_q;              /* DEVICE [num_seqs + 1]                   */
     const int32_t *ctx_lens;                  /* DEVICE [num_seqs]                       */
     const int32_t *block_table;               /* DEVICE [num_seqs][max_blocks_per_seq]   */
+    int32_t min_q_len;                        /* min over i of q_len_i, or 0 = not known.  A hint only: the lengths
+                                                 live on the device, so a ragged call launches the decode-attention
+                                                 kernels for its single-token sequences unless this says there are
+                                                 none (>= 2).  A wrong value costs time, never correctness.        */
 } fxp_batch;
 
 /* A stage's cache as seen by the repartition calls: pool + that stage's table. */

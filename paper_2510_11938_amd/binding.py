@@ -76,6 +76,7 @@ class Batch(C.Structure):
         ("num_seqs", C.c_int32), ("num_tokens", C.c_int32), ("max_q_len", C.c_int32),
         ("max_blocks_per_seq", C.c_int32),
         ("cu_seqlens_q", C.c_void_p), ("ctx_lens", C.c_void_p), ("block_table", C.c_void_p),
+        ("min_q_len", C.c_int32),
     ]
 
 
@@ -285,9 +286,10 @@ class Stage:
 
     def forward(self, cache: KVCache, cu_seqlens_q: torch.Tensor, ctx_lens: torch.Tensor, hidden_in: torch.Tensor,
                 max_q_len: int, hidden_out: Optional[torch.Tensor] = None,
-                probs: Optional[torch.Tensor] = None) -> torch.Tensor:
+                probs: Optional[torch.Tensor] = None, min_q_len: int = 0) -> torch.Tensor:
         """One step.  ``hidden_in`` bf16 CUDA [T,H]; ``cu_seqlens_q`` int32 CUDA [B+1]; ``ctx_lens`` int32 CUDA [B].
-        ``probs`` (float32 CUDA [layers][T][Hq][stride]) switches to the debug entry point."""
+        ``probs`` (float32 CUDA [layers][T][Hq][stride]) switches to the debug entry point.  ``min_q_len`` is the
+        optional hint of the ABI (0 = not known)."""
         T = hidden_in.shape[0]
         B = ctx_lens.shape[0]
         assert hidden_in.is_cuda and hidden_in.is_contiguous() and hidden_in.element_size() == 2
@@ -296,7 +298,7 @@ class Stage:
             hidden_out = torch.empty_like(hidden_in)
         pool = cache.c_pool()
         batch = Batch(B, T, max_q_len, cache.block_table.shape[1], cu_seqlens_q.data_ptr(), ctx_lens.data_ptr(),
-                      cache.block_table.data_ptr())
+                      cache.block_table.data_ptr(), min_q_len)
         nbytes = self.workspace_bytes(T, B, cache.block_table.shape[1])
         ws = self._workspace(nbytes)
         if probs is None:

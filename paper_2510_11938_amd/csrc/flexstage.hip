@@ -464,7 +464,9 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
     const bool skinny = T <= kSkinnyMaxTokens;
     const bool decode = batch->max_q_len == 1 && T == B;
     // lengths live on the device: a ragged call with several sequences may mix prompt chunks and single-token rows
-    const bool mixed = !decode && !probs && B >= 2 && batch->max_q_len > 1 && (int64_t)T < (int64_t)B * batch->max_q_len;
+    // (unless the caller says that no sequence has fewer than two new tokens)
+    const bool mixed = !decode && !probs && B >= 2 && batch->max_q_len > 1 && (int64_t)T < (int64_t)B * batch->max_q_len &&
+                       batch->min_q_len < 2;
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
     hipError_t e;
 

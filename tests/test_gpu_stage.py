@@ -182,6 +182,26 @@ def test_random_ragged_batches_match_oracle(seed):
     check_appended_rows(case, cache, opool)
 
 
+def test_min_q_len_hint_changes_time_only():
+    # without single-token sequences the hint only drops two empty launches: same bits; a wrong hint on a mixed batch
+    # sends the single-token rows through the prefill kernel: still the oracle's result
+    pure = Case(GQA64, 1, [0, 40, 700, 3], [70, 2, 33, 129], seed=31)
+    stage = make_stage(pure.ms, pure.w, 0, 1)
+    outs = []
+    for hint in (0, 2):
+        cache = pure.gpu_cache()
+        y = stage.forward(cache, dev_i32(pure.cu), dev_i32(pure.ctx), dev_bf16(pure.hidden_bits), int(pure.q_lens.max()), min_q_len=hint)
+        torch.cuda.synchronize()
+        outs.append((host_bits(y), host_bits(cache.pool)))
+    assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1])
+    mixed = Case(TINY, 2, [0, 700, 33, 128], [130, 1, 1, 20], seed=32)
+    want, _ = mixed.oracle_run()
+    stage = make_stage(mixed.ms, mixed.w, 0, 2)
+    y = stage.forward(mixed.gpu_cache(), dev_i32(mixed.cu), dev_i32(mixed.ctx), dev_bf16(mixed.hidden_bits), int(mixed.q_lens.max()), min_q_len=2)
+    torch.cuda.synchronize()
+    assert rel_err(host_f64(y), want) <= TOL_OUT
+
+
 def test_prefill_then_decode_end_to_end_on_gpu_cache():
     # the GPU decodes on top of the cache its own prefill wrote; the oracle does the same with its float cache
     ms, L = TINY, 2
