@@ -163,7 +163,11 @@ int    fxp_stage_layers(const fxp_stage *stage, int32_t *layer_begin, int32_t *l
  * (rotate-half pairing), append of K,V to the paged cache, causal softmax
  * attention over the cached prefix plus the new tokens, output projection +
  * residual, RMSNorm, SwiGLU feed-forward + residual.  The pool's layer range
- * must equal the stage's.  `workspace` is DEVICE scratch of at least
+ * must equal the stage's.  Any mix of sequences is one call: decode rows (one
+ * new token), whole prompts, prompt chunks behind a cached prefix.  Low-order
+ * bits of the result may depend on the host-side bounds of the call (token and
+ * sequence counts, table width), which select tile shapes, never on where the
+ * blocks lie.  `workspace` is DEVICE scratch of at least
  * fxp_stage_workspace_bytes(...) bytes for the given bounds, 256-byte aligned;
  * its contents are undefined afterwards. */
 size_t fxp_stage_workspace_bytes(const fxp_stage *stage, int32_t max_tokens, int32_t max_seqs,
