@@ -28,6 +28,7 @@
 //   decode batches of 65..128 tokens where one 128-row tile covers the batch and
 //   the k split supplies the parallelism.
 #include "kernels.h"
+#include <stdlib.h>
 #include "common.hip.h"
 
 namespace fxp {
@@ -39,7 +40,7 @@ constexpr int kTgStages = 3;                               // LDS buffers, each 
 constexpr int kTgXChunks = 2 * kTgRm * 64;                 // 16-byte chunks of one stage (16 KiB)
 constexpr int kTgXPerThread = kTgXChunks / kTgThreads;     // 4
 
-template <int EPI, bool K_TAIL>
+template <int EPI, bool K_TAIL, bool W_EARLY>
 __global__ __launch_bounds__(kTgThreads, 2) void gemm_tiled_kernel(TiledArgs a)
 {
     __shared__ u32x4 s_x[kTgStages][kTgXChunks];
@@ -180,10 +181,12 @@ __global__ __launch_bounds__(kTgThreads, 2) void gemm_tiled_kernel(TiledArgs a)
     const uint32_t lds_h1 = lds_base + (kTgRm * 64 + 16 * c + ((col + 2 * c + 8) & 15)) * 16;
     constexpr uint32_t kStageBytes = kTgXChunks * 16;
 
-    // Weights: ring of three k-steps; w(ks+2) is requested after the products of k-step ks, one k-step ahead of
-    // its use, and not together with the token rows at the start of the stage: requests spread evenly over the
-    // stage measured 4 % faster than the same loads in one burst a k-step earlier (prefetch distance is not what
-    // this kernel lacks; placements between the two were all within 1 % of this one).  Token rows:
+    // Weights: ring of three k-steps.  With many row tiles (matrix-core bound) w(ks+2) is requested after the
+    // products of k-step ks, one k-step ahead of its use, and not together with the token rows at the start of
+    // the stage: requests spread evenly over the stage measured 4 % faster than the same loads in one burst a
+    // k-step earlier (placements between the two were all within 1 % of this one).  With one or two row tiles
+    // (W_EARLY: the launch streams the weights once and is bound by HBM) the earlier request keeps more bytes
+    // in flight and is the faster one (70B shape, 256 rows: 305 against 318 us per layer).  Token rows:
     // three LDS buffers; stage t+2 is fetched to registers at the start of stage t and written to
     // buffer (t+2) % 3 at its end.  That buffer was last read in stage t-1, so the one barrier per
     // stage (at its end) orders those reads before these writes, and it makes the rows of stage
@@ -202,10 +205,11 @@ __global__ __launch_bounds__(kTgThreads, 2) void gemm_tiled_kernel(TiledArgs a)
                  : [n0] "=&v"(xa0), [n1] "=&v"(xa1) : [addr] "v"(lds_h0) : "memory");
 #define FXP_TG_STAGE(WA, WB, WC2, WD2, KTV, BUF, BUF_NEXT, BUF_STORE)          \
     fetch_x(xg, (KTV) + 2);                                                    \
+    if constexpr (W_EARLY) fetch_w(WC2, 2 * (KTV) + 2);                        \
     compute(WA, lds_h0 + (BUF) * kStageBytes, lds_h1 + (BUF) * kStageBytes);   \
-    fetch_w(WC2, 2 * (KTV) + 2);                                               \
+    if constexpr (W_EARLY) fetch_w(WD2, 2 * (KTV) + 3); else fetch_w(WC2, 2 * (KTV) + 2); \
     compute(WB, lds_h1 + (BUF) * kStageBytes, lds_h0 + (BUF_NEXT) * kStageBytes); \
-    fetch_w(WD2, 2 * (KTV) + 3);                                               \
+    if constexpr (!W_EARLY) fetch_w(WD2, 2 * (KTV) + 3);                       \
     store_x(xg, BUF_STORE);                                                    \
     __syncthreads();
     // k-step s lives in weight set s % 3 and stage t in LDS buffer t % 3, so the names repeat every three stages
@@ -283,9 +287,16 @@ hipError_t launch_gemm_tiled(const TiledArgs &a, hipStream_t stream)
     if (tiles_m == 1) grid.x = tiles_n;
     else if (tiles_m < 16) grid.x = (tiles_n + 7) / 8 * 8 * tiles_m;
     const bool tail = a.K % 64 != 0;                  // a stage is 64 wide: the token rows end inside the last one
+    static const int early_tiles = getenv("FXP_TILED_EARLY_W_TILES") ? atoi(getenv("FXP_TILED_EARLY_W_TILES")) : 2;
+    const bool early = tiles_m <= early_tiles;        // few row tiles: bound by the weight stream, see the kernel
 #define FXP_TG_LAUNCH(E)                                                                                       \
-    if (tail) hipLaunchKernelGGL((gemm_tiled_kernel<E, true>), grid, dim3(kTgThreads), 0, stream, a);          \
-    else hipLaunchKernelGGL((gemm_tiled_kernel<E, false>), grid, dim3(kTgThreads), 0, stream, a);
+    if (tail) {                                                                                                \
+        if (early) hipLaunchKernelGGL((gemm_tiled_kernel<E, true, true>), grid, dim3(kTgThreads), 0, stream, a);   \
+        else hipLaunchKernelGGL((gemm_tiled_kernel<E, true, false>), grid, dim3(kTgThreads), 0, stream, a);    \
+    } else {                                                                                                   \
+        if (early) hipLaunchKernelGGL((gemm_tiled_kernel<E, false, true>), grid, dim3(kTgThreads), 0, stream, a);  \
+        else hipLaunchKernelGGL((gemm_tiled_kernel<E, false, false>), grid, dim3(kTgThreads), 0, stream, a);   \
+    }
     switch (a.epilogue) {
     case kEpiStore: FXP_TG_LAUNCH(kEpiStore) break;
     case kEpiResidual: FXP_TG_LAUNCH(kEpiResidual) break;
