@@ -99,3 +99,34 @@ def test_7b_shape_prefill_chunk_of_514_tokens_sampled_against_oracle():
         want = oracle.stage_forward(osh, wf, sub_pool, [0, int(lens[i])], [0], np.arange(nb, dtype=np.int32)[None, :],
                                     synth.bf16_bits_to_f32(hidden_bits[rows]).astype(np.float64))
         check_wide_output(got[rows], want, f"prompt {i} ({lens[i]} tokens):")
+
+
+def test_full_size_prefill_workload_sampled_against_oracle():
+    # the prefill workload of the benchmark at its full size (16 prompts, 15,928 tokens, 7B shape, 1 layer): 128-row
+    # attention tiles, tiled projections over 125 row tiles with a ragged last one.  Attention is causal and prompts are
+    # independent, so the first n output rows of a prompt are what the stage gives for its first n tokens alone: the
+    # oracle recomputes three such heads of prompts (first, shortest, last in the batch).
+    wl = synth.WORKLOADS["C3"]
+    ms = wl.shape
+    lens = synth.draw_lengths(wl.length_dist, wl.num_seqs, wl.seed)
+    T, B = int(lens.sum()), wl.num_seqs
+    table, nblk = synth.block_table(lens, 16, wl.seed)
+    w = make_weights(ms, wl.seed, 1, want_f32=False)
+    hidden_bits = synth.hidden_states(T, ms.hidden, wl.seed)
+    stage = make_stage(ms, w, 0, 1)
+    pool = torch.zeros((1, nblk, 2, ms.n_kv_heads, 16, ms.head_dim), dtype=torch.int16, device="cuda")
+    cache = binding.KVCache(pool, 0, 1, dev_i32(table))
+    cu = synth.cu_seqlens(lens)
+    y = stage.forward(cache, dev_i32(cu), dev_i32(np.zeros(B)), dev_bf16(hidden_bits), int(lens.max()), min_q_len=int(lens.min()))
+    torch.cuda.synchronize()
+    got = host_f64(y)
+    assert np.isfinite(got).all()
+    osh = oracle_shape(ms)
+    wf = [{k: synth.bf16_bits_to_f32(v) for k, v in lw.items()} for lw in w.bits]
+    for i, n in ((0, 150), (int(np.argmin(lens)), 130), (B - 1, 100)):
+        nb = (n + 15) // 16
+        sub_pool = np.zeros((1, nb, 2, ms.n_kv_heads, 16, ms.head_dim), dtype=np.float32)
+        rows = slice(int(cu[i]), int(cu[i]) + n)
+        want = oracle.stage_forward(osh, wf, sub_pool, [0, n], [0], np.arange(nb, dtype=np.int32)[None, :],
+                                    synth.bf16_bits_to_f32(hidden_bits[rows]).astype(np.float64))
+        check_wide_output(got[rows], want, f"prompt {i}, first {n} of {lens[i]} tokens:")
