@@ -33,6 +33,7 @@ WIDE_FFN = synth.ModelShape(hidden=256, n_q_heads=4, n_kv_heads=4, head_dim=64, 
 KV6 = synth.ModelShape(hidden=384, n_q_heads=6, n_kv_heads=6, head_dim=64, ffn=512)            # kv heads in groups of two per decode worker
 GQA_KV3 = synth.ModelShape(hidden=384, n_q_heads=6, n_kv_heads=3, head_dim=64, ffn=512)        # an odd number of kv heads: one per worker
 HEADS_7B = synth.ModelShape(hidden=256, n_q_heads=32, n_kv_heads=32, head_dim=128, ffn=512)  # the 7B head geometry behind a narrow model: attention at the benchmark's launch shape, cheap projections
+HEADS_70B = synth.ModelShape(hidden=256, n_q_heads=64, n_kv_heads=8, head_dim=128, ffn=512)  # likewise the 70B grouped-query geometry
 ODD_K = synth.ModelShape(hidden=160, n_q_heads=2, n_kv_heads=2, head_dim=64, ffn=224)        # contraction lengths of 32 mod 64 (and heads narrower than hidden)
 
 
@@ -144,6 +145,7 @@ PREFILL_CASES = [
     ("wide-tiles-gqa128", GQA128, 1, [0, 200], [1100, 300]),
     ("7b-heads-long-prompts", HEADS_7B, 1, [0, 300], [2300, 700]),           # 32 heads x 128: wide tiles without cut keys, 37 key tiles deep
     ("7b-heads-chunk-long-prefix", HEADS_7B, 1, [6000], [512]),               # ... and a 512-token chunk behind 6000 cached: wide tiles, keys cut in three
+    ("70b-heads-prompts", HEADS_70B, 1, [0, 100, 1500], [700, 300, 1]),      # 64 query / 8 kv heads x 128, with one decode row
     ("wide-tiles-one-line", TINY, 1, [0] * 20, [3200] + [100] * 19),          # ... launched as one line of tiles, keys cut in two
     ("opt-prompts", OPT_TINY, 2, [0, 0, 0, 0], [37, 128, 32, 100]),
     ("opt-small", OPT_TINY, 2, [0, 0], [20, 45]),
