@@ -421,9 +421,14 @@ int prefill_kv_split(int n_q_heads, int num_tokens, int num_seqs, int max_blocks
 }
 
 template <int D, int QB>
-static hipError_t launch_q(const PrefillAttnArgs &a, hipStream_t stream)
+static hipError_t launch_q(const PrefillAttnArgs &a_in, hipStream_t stream)
 {
     constexpr int QT = 64 * QB;
+    PrefillAttnArgs a = a_in;
+    // the tile index and the piece share one grid dimension of at most 65535 (both kernels read the factor from here)
+    const int64_t widest = std::max<int64_t>((a.max_q_len + QT - 1) / QT, a.num_tokens / QT + a.num_seqs);
+    while (a.kv_split > 1 && widest * a.kv_split > 65535) --a.kv_split;
+    if (widest > 65535 || a.num_seqs > 65535) return hipErrorInvalidValue;
     // one line of tiles when the rectangle (tiles of the longest prompt x sequences) would be more than eight times as
     // large (an empty workgroup costs a few nanoseconds, which only matters when there are very many of them)
     const int rect_x = (a.max_q_len + QT - 1) / QT, flat_x = a.num_tokens / QT + a.num_seqs;
