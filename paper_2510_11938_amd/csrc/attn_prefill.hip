@@ -389,18 +389,21 @@ __global__ void attn_probs_normalize_kernel(float *scores, const float *ml, int6
         scores[row * stride + r] = __builtin_amdgcn_exp2f(scores[row * stride + r] - m) / l;
 }
 
-// Query rows per workgroup: 128 (two column blocks per wave) when the prompts are long enough to fill such tiles and
-// there are enough of them for every compute unit -- counting the pieces their keys may be cut into when the block
-// table is wide enough for a long cached prefix -- else 64.
-int prefill_q_tile(int n_q_heads, int num_tokens, int num_seqs, int max_blocks_per_seq)
+// Query rows per workgroup: 128 (two column blocks per wave) or 64.  The wide tile has the higher throughput and the
+// longer critical path (the last tile of a prompt walks all its keys at twice the work per step), so it needs enough
+// tiles to keep the chip busy past the long ones -- measured with 32 heads: one prompt of 2048 tokens (512 wide tiles)
+// is 10 % faster on 64-row tiles, one of 3072 (768) 16 % faster on 128-row tiles, several prompts break even at 512 --
+// or, with fewer, a block table with room for a cached prefix of at least two key pieces besides the longest chunk
+// (then the walks are long and even, and cut keys fill the chip: 512 tokens behind 8192 cached: 146 -> 122 us).
+int prefill_q_tile(int n_q_heads, int num_tokens, int num_seqs, int max_q_len, int max_blocks_per_seq)
 {
     static const int forced = getenv("FXP_PREFILL_Q_TILE") ? atoi(getenv("FXP_PREFILL_Q_TILE")) : 0;
     if (forced == 64 || forced == 128) return forced;
     if (num_tokens < 128 * (int64_t)std::max(num_seqs, 1)) return 64;
     const int64_t tiles = (int64_t)n_q_heads * (num_tokens / 128);
-    if (tiles >= 256) return 128;
-    const bool wide = (int64_t)max_blocks_per_seq * kBlockTokens >= 2 * kPfMinPieceTiles * kPfKvTile;
-    return wide && tiles * kPfMaxPieces >= prefill_resident_wgs(128) ? 128 : 64;
+    if (tiles >= 768) return 128;
+    const bool prefix_room = (int64_t)max_blocks_per_seq * kBlockTokens - max_q_len >= 2 * kPfMinPieceTiles * kPfKvTile;
+    return prefix_room && tiles * kPfMaxPieces >= prefill_resident_wgs(128) ? 128 : 64;
 }
 size_t prefill_piece_rows(int n_q_heads, int max_tokens)
 {

@@ -600,7 +600,7 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
             pa.max_blocks_per_seq = batch->max_blocks_per_seq; pa.layer_local = ll; pa.n_q_heads = d.n_q_heads;
             pa.n_kv_heads = d.n_kv_heads; pa.head_dim = D; pa.scale_log2e = scale_log2e;
             pa.tok_seq = w.tok_seq; pa.part_acc = w.pf_acc; pa.part_ml = w.pf_ml;
-            pa.q_tile = fxp::prefill_q_tile(d.n_q_heads, T, B, batch->max_blocks_per_seq);
+            pa.q_tile = fxp::prefill_q_tile(d.n_q_heads, T, B, batch->max_q_len, batch->max_blocks_per_seq);
             pa.kv_split = fxp::prefill_kv_split(d.n_q_heads, T, B, batch->max_blocks_per_seq, pa.q_tile);
             KernelTimer kt(kKcAttnPrefill, st);
             if ((e = fxp::launch_attn_prefill(pa, st))) return hip_fail(e, "prefill attention");

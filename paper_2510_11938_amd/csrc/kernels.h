@@ -182,7 +182,7 @@ struct PrefillAttnArgs {
     int kv_split;
     int q_tile;                  // query rows per workgroup: 64 or 128 (prefill_q_tile)
 };
-int prefill_q_tile(int n_q_heads, int num_tokens, int num_seqs, int max_blocks_per_seq);
+int prefill_q_tile(int n_q_heads, int num_tokens, int num_seqs, int max_q_len, int max_blocks_per_seq);
 int prefill_kv_split(int n_q_heads, int num_tokens, int num_seqs, int max_blocks_per_seq, int q_tile);
 size_t prefill_piece_rows(int n_q_heads, int max_tokens);     // rows of part_acc / part_ml for calls of up to max_tokens
 hipError_t launch_attn_prefill(const PrefillAttnArgs &a, hipStream_t stream);

@@ -142,11 +142,11 @@ PREFILL_CASES = [
     ("chunks-long-pieces", GQA64, 1, [2500 + 37 * i for i in range(30)], [40] * 30),
     # long prompts: 128 query rows per workgroup (two column blocks per wave), with and without cut keys, ragged last tile
     ("wide-tiles-long-chunk", TINY, 1, [1100], [2100]),
-    ("wide-tiles-gqa128", GQA128, 1, [0, 200], [1100, 300]),
-    ("7b-heads-long-prompts", HEADS_7B, 1, [0, 300], [2300, 700]),           # 32 heads x 128: wide tiles without cut keys, 37 key tiles deep
+    ("wide-tiles-gqa128", GQA128, 1, [0, 2000], [1100, 300]),
+    ("7b-heads-long-prompts", HEADS_7B, 1, [0, 300], [2500, 700]),           # 32 heads x 128: wide tiles without cut keys, 40 key tiles deep
     ("7b-heads-chunk-long-prefix", HEADS_7B, 1, [6000], [512]),               # ... and a 512-token chunk behind 6000 cached: wide tiles, keys cut in three
-    ("70b-heads-prompts", HEADS_70B, 1, [0, 100, 1500], [700, 300, 1]),      # 64 query / 8 kv heads x 128, with one decode row
-    ("wide-tiles-one-line", TINY, 1, [0] * 20, [3200] + [100] * 19),          # ... launched as one line of tiles, keys cut in two
+    ("70b-heads-prompts", HEADS_70B, 1, [0, 100, 2000], [700, 300, 1]),      # 64 query / 8 kv heads x 128, with one decode row
+    ("wide-tiles-one-line", TINY, 1, [1100] + [0] * 19, [3200] + [100] * 19),          # ... launched as one line of tiles, keys cut in two
     ("opt-prompts", OPT_TINY, 2, [0, 0, 0, 0], [37, 128, 32, 100]),
     ("opt-small", OPT_TINY, 2, [0, 0], [20, 45]),
     ("opt-chunked", OPT_GQA, 1, [16, 70, 33], [48, 10, 64]),

@@ -21,14 +21,14 @@ def resident_wgs(q_tile):
     return 768 if q_tile == 64 else 512
 
 
-def q_tile_of(Hq, T, B, max_blocks):
+def q_tile_of(Hq, T, B, max_q, max_blocks):
     if T < 128 * max(B, 1):
         return 64
     tiles = Hq * (T // 128)
-    if tiles >= 256:
+    if tiles >= 768:
         return 128
-    wide = max_blocks * BLOCK >= 2 * MIN_PIECE_TILES * KV_TILE
-    return 128 if wide and tiles * MAX_PIECES >= resident_wgs(128) else 64
+    prefix_room = max_blocks * BLOCK - max_q >= 2 * MIN_PIECE_TILES * KV_TILE
+    return 128 if prefix_room and tiles * MAX_PIECES >= resident_wgs(128) else 64
 
 
 def piece_rows(Hq, max_tokens):
@@ -65,7 +65,7 @@ def test_pieces_cover_every_key_tile_once_and_rows_stay_inside_the_buffer(seed):
     rng = np.random.default_rng(seed)
     Hq, q, ctx, max_blocks = random_batch(rng)
     T, B = int(q.sum()), len(q)
-    qt_rows = q_tile_of(Hq, T, B, max_blocks)
+    qt_rows = q_tile_of(Hq, T, B, int(q.max()), max_blocks)
     split = kv_split_of(Hq, T, B, max_blocks, qt_rows)
     assert 1 <= split <= MAX_PIECES
     # the buffer of a workspace sized for a larger call serves this one too
@@ -103,7 +103,9 @@ def test_piece_zero_always_holds_the_first_key_so_the_merged_maximum_is_finite()
 def test_narrow_block_table_never_cuts_and_long_prompts_take_wide_tiles():
     assert kv_split_of(32, 512, 1, (2 * MIN_PIECE_TILES * KV_TILE) // BLOCK - 1, 64) == 1
     assert kv_split_of(32, 512, 1, 4096, 64) == 768 // (32 * 9)
-    assert q_tile_of(32, 15928, 16, 128) == 128          # the prefill workload of the benchmark
-    assert q_tile_of(32, 512, 1, 16) == 64               # a chunk without room for a prefix
-    assert q_tile_of(32, 512, 1, 4096) == 128            # the same chunk behind a wide table
-    assert q_tile_of(32, 2560, 64, 4096) == 64           # many short prompts
+    assert q_tile_of(32, 15928, 16, 1962, 128) == 128      # the prefill workload of the benchmark
+    assert q_tile_of(32, 512, 1, 512, 32) == 64            # a chunk without room for a prefix
+    assert q_tile_of(32, 512, 1, 512, 4096) == 128         # the same chunk behind a wide table
+    assert q_tile_of(32, 2048, 1, 2048, 128) == 64         # one prompt, too few wide tiles to hide its last one
+    assert q_tile_of(32, 3072, 1, 3072, 192) == 128
+    assert q_tile_of(32, 2560, 64, 40, 4096) == 64         # many short prompts
