@@ -147,6 +147,7 @@ PREFILL_CASES = [
     ("7b-heads-chunk-long-prefix", HEADS_7B, 1, [6000], [512]),               # ... and a 512-token chunk behind 6000 cached: wide tiles, keys cut in three
     ("70b-heads-prompts", HEADS_70B, 1, [0, 100, 2000], [700, 300, 1]),      # 64 query / 8 kv heads x 128, with one decode row
     ("wide-tiles-one-line", TINY, 1, [1100] + [0] * 19, [3200] + [100] * 19),          # ... launched as one line of tiles, keys cut in two
+    ("max-seqs-mixed", TINY, 1, [(7 * i) % 40 for i in range(4096)], [1 + i % 3 for i in range(4096)]),   # the most sequences a call may hold, decode rows among them
     ("opt-prompts", OPT_TINY, 2, [0, 0, 0, 0], [37, 128, 32, 100]),
     ("opt-small", OPT_TINY, 2, [0, 0], [20, 45]),
     ("opt-chunked", OPT_GQA, 1, [16, 70, 33], [48, 10, 64]),
