@@ -96,6 +96,35 @@ def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
     return (np.ascontiguousarray(bits, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
 
 
+_CHUNK = 1 << 20
+
+
+def _normal_bf16(g: np.random.Generator, shape, scale: float = 1.0, offset: float = 0.0) -> np.ndarray:
+    """bf16 bit patterns of ``offset + scale * N(0,1)`` drawn from ``g`` in float32 and rounded to
+    nearest even: the values of ``f32_to_bf16_bits(g.standard_normal(shape, float32) * scale + offset)``,
+    produced a chunk at a time in reused buffers (large temporaries cost more than the draw itself)."""
+    n = int(np.prod(shape, dtype=np.int64))
+    out = np.empty(n, dtype=np.uint16)
+    buf = np.empty(min(n, _CHUNK), dtype=np.float32)
+    tmp = np.empty(min(n, _CHUNK), dtype=np.uint32)
+    for at in range(0, n, _CHUNK):
+        m = min(_CHUNK, n - at)
+        a, t = buf[:m], tmp[:m]
+        g.standard_normal(out=a, dtype=np.float32)
+        if scale != 1.0:
+            a *= np.float32(scale)
+        if offset != 0.0:
+            a += np.float32(offset)
+        u = a.view(np.uint32)
+        np.right_shift(u, np.uint32(16), out=t)
+        t &= np.uint32(1)
+        t += np.uint32(0x7FFF)
+        u += t
+        u >>= np.uint32(16)
+        out[at:at + m] = u
+    return out.reshape(shape)
+
+
 # ---------------------------------------------------------------- draws
 def layer_weights(shape: ModelShape, seed: int, layer: int) -> Dict[str, np.ndarray]:
     """bf16 bit patterns of one decoder layer's tensors.  Projection matrices
@@ -109,10 +138,7 @@ def layer_weights(shape: ModelShape, seed: int, layer: int) -> Dict[str, np.ndar
     }
     out = {}
     for name in LAYER_TENSORS:
-        a = g.standard_normal(dims[name], dtype=np.float32) * np.float32(0.02)
-        if name.startswith("g_"):
-            a = a + np.float32(1.0)
-        out[name] = f32_to_bf16_bits(a)
+        out[name] = _normal_bf16(g, dims[name], 0.02, 1.0 if name.startswith("g_") else 0.0)
     return out
 
 
@@ -132,10 +158,7 @@ def opt_layer_weights(shape: ModelShape, seed: int, layer: int) -> Dict[str, np.
     }
     out = {}
     for name in OPT_LAYER_TENSORS:
-        a = g.standard_normal(dims[name], dtype=np.float32) * np.float32(0.02)
-        if name.endswith("_g"):
-            a = a + np.float32(1.0)
-        out[name] = f32_to_bf16_bits(a)
+        out[name] = _normal_bf16(g, dims[name], 0.02, 1.0 if name.endswith("_g") else 0.0)
     return out
 
 
@@ -175,14 +198,13 @@ def block_table(tokens_after: np.ndarray, block_size: int, seed: int, salt: int 
 
 def hidden_states(num_tokens: int, hidden: int, seed: int, salt: int = 0) -> np.ndarray:
     """bf16 bit patterns of N(0,1) hidden rows, [num_tokens, hidden]."""
-    return f32_to_bf16_bits(_rng(seed, _TAG_HIDDEN, salt).standard_normal((num_tokens, hidden), dtype=np.float32))
+    return _normal_bf16(_rng(seed, _TAG_HIDDEN, salt), (num_tokens, hidden))
 
 
 def cache_rows(shape: ModelShape, seed: int, seq: int, layer: int, n_tokens: int) -> np.ndarray:
     """Synthetic cache contents of one (sequence, layer): bf16 bit patterns of
     N(0,1) values, [n_tokens][2: K,V][kv_head][head_dim]."""
-    g = _rng(seed, _TAG_CACHE, seq, layer)
-    return f32_to_bf16_bits(g.standard_normal((n_tokens, 2, shape.n_kv_heads, shape.head_dim), dtype=np.float32))
+    return _normal_bf16(_rng(seed, _TAG_CACHE, seq, layer), (n_tokens, 2, shape.n_kv_heads, shape.head_dim))
 
 
 def fill_pool_rows(pool: np.ndarray, layer_local: int, table_row: np.ndarray, rows: np.ndarray,

@@ -43,21 +43,6 @@ def rel_err(gpu: np.ndarray, ref: np.ndarray) -> float:
     return float((np.abs(gpu - ref) / np.maximum(np.abs(ref), rms)).max())
 
 
-def check_wide_output(gpu: np.ndarray, ref: np.ndarray, what: str = "") -> None:
-    """Stage-output check for wide models (hidden >= 4096, several rounding stages).  The
-    element-wise maximum over 10^4..10^6 outputs is an extreme-value statistic of the bf16
-    rounding noise (sigma ~ 0.5 % of the row rms => 4-5 sigma ~ 2-3 %), so the 2e-2 bar is
-    applied to the row-wise relative L2 error, and the element-wise measure must stay below
-    2e-2 for all but 2 % of the elements and below 5e-2 everywhere."""
-    rms = np.sqrt((ref ** 2).mean(axis=-1, keepdims=True))
-    elem = np.abs(gpu - ref) / np.maximum(np.abs(ref), rms)
-    l2 = np.sqrt(((gpu - ref) ** 2).sum(axis=-1) / (ref ** 2).sum(axis=-1))
-    print(f"{what} rel l2 max {l2.max():.3e}  element-wise max {elem.max():.3e}  fraction > 2e-2: {(elem > 2e-2).mean():.2e}")
-    assert l2.max() <= 2e-2, what
-    assert (elem > 2e-2).mean() <= 2e-2, what
-    assert elem.max() <= 5e-2, what
-
-
 @dataclass
 class Weights:
     bits: List[Dict[str, np.ndarray]]         # per layer: name -> uint16 bf16 patterns
@@ -67,7 +52,8 @@ class Weights:
 
 def make_weights(ms: synth.ModelShape, seed: int, n_layers: int, want_f32: bool = True, want_dev: bool = True) -> Weights:
     gen = synth.opt_layer_weights if ms.arch == 1 else synth.layer_weights
-    bits = [gen(ms, seed, l) for l in range(n_layers)]
+    with ThreadPoolExecutor(max_workers=8) as ex:             # layers have generators of their own: drawn side by side
+        bits = list(ex.map(lambda l: gen(ms, seed, l), range(n_layers)))
     f32 = [{k: synth.bf16_bits_to_f32(v) for k, v in lw.items()} for lw in bits] if want_f32 else []
     dev = [{k: dev_bf16(v) for k, v in lw.items()} for lw in bits] if want_dev else []
     return Weights(bits, f32, dev)
