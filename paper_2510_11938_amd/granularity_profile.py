@@ -74,24 +74,34 @@ def layer_tensor_shapes(ms: synth.ModelShape) -> dict:
     return dict(g_attn=(H,), wq=(Nq, H), wk=(Nkv, H), wv=(Nkv, H), wo=(H, Nq), g_ffn=(H,), w_gate=(F, H), w_up=(F, H), w_down=(H, F))
 
 
+def load_stage(ms: synth.ModelShape, host_layers, layer_begin: int = 0):
+    """A stage's parameters from pinned host memory (``host_layers``: one dict of pinned bf16 CPU tensors per
+    layer, named as binding.Stage expects) to the GPU, then fxp_stage_create's re-tiling into the stage's
+    arena.  Returns (stage, host -> GPU ms, re-tile ms)."""
+    dev = torch.device("cuda:0")
+    for lw in host_layers:
+        assert all(t.is_pinned() for t in lw.values())
+    e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    e[0].record()
+    layers = [{k: t.to(dev, non_blocking=True) for k, t in lw.items()} for lw in host_layers]
+    e[1].record()
+    stage = binding.Stage(ms, layer_begin, layer_begin + len(host_layers), layers)
+    e[2].record()
+    torch.cuda.synchronize()
+    return stage, e[0].elapsed_time(e[1]), e[1].elapsed_time(e[2])
+
+
 def measure_load_ms(ms: synth.ModelShape, depth: int) -> dict:
     """The load column of Table 2 as far as one GPU can show it: a stage's parameters go from pinned
     host memory to the GPU (one layer's worth of pinned buffers, copied once per layer: the contents do
     not matter for the time) and fxp_stage_create re-tiles them into the stage's arena."""
-    dev = torch.device("cuda:0")
     shapes = layer_tensor_shapes(ms)
     host = {k: torch.zeros(shp, dtype=torch.bfloat16).pin_memory() for k, shp in shapes.items()}
     layer_bytes = sum(t.numel() * 2 for t in host.values())
     torch.cuda.synchronize()
-    e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
-    e[0].record()
-    layers = [{k: t.to(dev, non_blocking=True) for k, t in host.items()} for _ in range(depth)]
-    e[1].record()
-    stage = binding.Stage(ms, 0, depth, layers)
-    e[2].record()
-    torch.cuda.synchronize()
+    stage, h2d_ms, retile_ms = load_stage(ms, [host] * depth)
     stage.close()
-    return {"bytes": layer_bytes * depth, "h2d_ms": e[0].elapsed_time(e[1]), "retile_ms": e[1].elapsed_time(e[2])}
+    return {"bytes": layer_bytes * depth, "h2d_ms": h2d_ms, "retile_ms": retile_ms}
 
 
 def max_batch(ms: synth.ModelShape, depth: int, ctx_len: int, hbm_bytes: float) -> int:
@@ -100,6 +110,29 @@ def max_batch(ms: synth.ModelShape, depth: int, ctx_len: int, hbm_bytes: float) 
     weights = ms.params_per_layer * 2 * depth
     per_seq = -(-(ctx_len + 1) // 16) * ms.block_elems * 2 * depth
     return int(max(0.0, hbm_bytes - weights) // per_seq)
+
+
+def stage_candidate(layers_total: int, depth: int, batch: int, compute_ms: float, handoff_ms: float) -> binding.Granularity:
+    """The candidate g_k = (eta_k stages, batch b_k) of Eq. 4 from a measured stage time: with one GPU per stage and
+    the pipeline full, T_k = batch / (t_stage + t_handoff) tokens/s and L_k = eta_k (t_stage + t_handoff) ms."""
+    n_stages = layers_total // depth
+    return binding.Granularity(n_stages, batch, batch / ((compute_ms + handoff_ms) * 1e-3), n_stages * (compute_ms + handoff_ms), 0.0)
+
+
+def spread_cv_opt(cands, cvs) -> None:
+    """nu_k: finer granularities suit burstier traffic; the candidates are spread over the CVs scored."""
+    order = np.argsort([c.n_stages for c in cands])
+    for rank, k in enumerate(order):
+        cands[k].cv_opt = cvs[min(rank * len(cvs) // len(cands), len(cvs) - 1)]
+
+
+def select_for_cvs(cands, cvs, alpha: float, sigma: float):
+    """fxp_ctl_select_granularity (Eq. 4) at each traffic CV."""
+    picks = []
+    for cv in cvs:
+        best, scores = binding.ctl_select_granularity(cands, cv, alpha, sigma)
+        picks.append({"cv": cv, "selected_n_stages": cands[best].n_stages, "scores": scores})
+    return picks
 
 
 def main(argv=None) -> int:
@@ -130,8 +163,8 @@ def main(argv=None) -> int:
     for depth in depths:
         n_stages = args.layers_total // depth
         t = measure_stage_ms(ms, depth, args.batch, ctx, args.steps)
-        thr = args.batch / ((t + handoff_ms) * 1e-3)
-        lat = n_stages * (t + handoff_ms)
+        cand = stage_candidate(args.layers_total, depth, args.batch, t, handoff_ms)
+        thr, lat = cand.throughput, cand.latency
         rows.append({"layers_per_stage": depth, "n_stages": n_stages, "compute_ms": t, "handoff_ms": handoff_ms,
                      "throughput_tokens_s": thr, "latency_ms": lat, "max_batch_at_ctx_hi": max_batch(ms, depth, hi, args.hbm_gb * 1e9)})
         print(f"depth {depth:2d}: {n_stages:2d} stages, compute {t:7.3f} ms, hand-off {handoff_ms:6.3f} ms, "
@@ -141,16 +174,10 @@ def main(argv=None) -> int:
             print(f"          load {rows[-1]['load']['bytes'] / 1e9:6.2f} GB: host -> GPU {rows[-1]['load']['h2d_ms']:8.1f} ms, "
                   f"re-tile {rows[-1]['load']['retile_ms']:7.1f} ms; max batch at ctx {hi}: {rows[-1]['max_batch_at_ctx_hi']}",
                   file=sys.stderr, flush=True)
-        # nu_k: finer granularities suit burstier traffic; spread the candidates over the CV range scored
-        cands.append(binding.Granularity(n_stages, args.batch, thr, lat, 0.0))
+        cands.append(cand)
     cvs = [float(v) for v in args.cvs.split(",")]
-    order = np.argsort([c.n_stages for c in cands])
-    for rank, k in enumerate(order):
-        cands[k].cv_opt = cvs[min(rank * len(cvs) // len(cands), len(cvs) - 1)]
-    picks = []
-    for cv in cvs:
-        best, scores = binding.ctl_select_granularity(cands, cv, args.alpha, args.sigma)
-        picks.append({"cv": cv, "selected_n_stages": cands[best].n_stages, "scores": scores})
+    spread_cv_opt(cands, cvs)
+    picks = select_for_cvs(cands, cvs, args.alpha, args.sigma)
     print(json.dumps({"model": args.model, "batch": args.batch, "ctx_range": [lo, hi], "stages": rows,
                       "cv_opt": [c.cv_opt for c in cands], "alpha": args.alpha, "sigma": args.sigma, "picks": picks}))
     return 0
