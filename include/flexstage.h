@@ -176,6 +176,21 @@ int    fxp_stage_forward(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_ba
                          const void *hidden_in, void *hidden_out,
                          void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* The same step for callers that cannot allocate device memory or size a workspace (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid allocation): the
+ * workspace is a file-scope device array of FXP_STATIC_SCRATCH_BYTES inside the library,
+ * which every GPU the library runs on holds until the process ends.  No device or pinned
+ * memory is allocated or freed by this call, ever.  Arguments, kernels and results are
+ * those of fxp_stage_forward (bit-identical for the same inputs).  A step whose bounds
+ * need more than the static array (fxp_stage_workspace_bytes > FXP_STATIC_SCRATCH_BYTES:
+ * long prefill chunks) is FXP_ENOSPC and nothing is enqueued.  The first call on a device
+ * looks the array's device address up (once per device; do it outside a graph capture).
+ * All calls on one GPU share the one array, whose contents are undefined between calls:
+ * calls that overlap on one GPU (two streams, two threads) race; serialise them. */
+#define FXP_STATIC_SCRATCH_BYTES (64u << 20)
+int    fxp_stage_forward_static(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_batch *batch,
+                                const void *hidden_in, void *hidden_out, void *hip_stream);
+
 /* Test-only variant: additionally writes the attention probabilities the
  * kernels computed, DEVICE float [n_layers][num_tokens][n_q_heads][probs_stride],
  * entries 0..position of each token (the rest is left untouched).  Meant for

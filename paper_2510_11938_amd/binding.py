@@ -22,7 +22,7 @@ FXP_OK, FXP_EINVAL, FXP_ENOSPC, FXP_EHIP = 0, -1, -2, -3
 
 EXPORTS = (
     "fxp_stage_weight_arena_bytes", "fxp_stage_create", "fxp_stage_destroy",
-    "fxp_stage_workspace_bytes", "fxp_stage_forward", "fxp_stage_forward_debug",
+    "fxp_stage_workspace_bytes", "fxp_stage_forward", "fxp_stage_forward_static", "fxp_stage_forward_debug",
     "fxp_stage_split", "fxp_stage_merge", "fxp_stage_layers",
     "fxp_kv_repartition", "fxp_kv_packed_bytes", "fxp_kv_pack", "fxp_kv_unpack",
     "fxp_kv_repartition_range", "fxp_kv_packed_tokens_bytes", "fxp_kv_pack_tokens", "fxp_kv_unpack_tokens",
@@ -111,6 +111,7 @@ def lib() -> C.CDLL:
         l.fxp_stage_workspace_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32]
         l.fxp_stage_forward.argtypes = [C.c_void_p, C.POINTER(KvPool), C.POINTER(Batch), C.c_void_p, C.c_void_p,
                                         C.c_void_p, C.c_size_t, C.c_void_p]
+        l.fxp_stage_forward_static.argtypes = [C.c_void_p, C.POINTER(KvPool), C.POINTER(Batch), C.c_void_p, C.c_void_p, C.c_void_p]
         l.fxp_stage_forward_debug.argtypes = [C.c_void_p, C.POINTER(KvPool), C.POINTER(Batch), C.c_void_p, C.c_void_p,
                                               C.c_void_p, C.c_size_t, C.c_void_p, C.c_int64, C.c_void_p]
         l.fxp_kv_repartition.argtypes = [C.POINTER(StageDesc), C.POINTER(KvView), C.c_int32, C.POINTER(KvView),
@@ -309,6 +310,21 @@ class Stage:
             _check(lib().fxp_stage_forward_debug(self.handle, C.byref(pool), C.byref(batch), hidden_in.data_ptr(),
                                                  hidden_out.data_ptr(), ws.data_ptr(), ws.numel(), probs.data_ptr(),
                                                  probs.shape[-1], _stream()))
+        return hidden_out
+
+    def forward_static(self, cache: KVCache, cu_seqlens_q: torch.Tensor, ctx_lens: torch.Tensor, hidden_in: torch.Tensor,
+                       max_q_len: int, hidden_out: torch.Tensor, min_q_len: int = 0) -> torch.Tensor:
+        """fxp_stage_forward_static: the same step with the library's static scratch as workspace; the caller
+        passes the output buffer too, so nothing is allocated on this path."""
+        T, B = hidden_in.shape[0], ctx_lens.shape[0]
+        assert hidden_in.is_cuda and hidden_in.is_contiguous() and hidden_in.element_size() == 2
+        assert hidden_out.is_cuda and hidden_out.is_contiguous() and hidden_out.shape == hidden_in.shape
+        assert cu_seqlens_q.dtype == torch.int32 and ctx_lens.dtype == torch.int32
+        pool = cache.c_pool()
+        batch = Batch(B, T, max_q_len, cache.block_table.shape[1], cu_seqlens_q.data_ptr(), ctx_lens.data_ptr(),
+                      cache.block_table.data_ptr(), min_q_len)
+        _check(lib().fxp_stage_forward_static(self.handle, C.byref(pool), C.byref(batch), hidden_in.data_ptr(),
+                                              hidden_out.data_ptr(), _stream()))
         return hidden_out
 
 

@@ -10,6 +10,7 @@
 #include <stdlib.h>
 #include <string.h>
 #include <algorithm>
+#include <mutex>
 #include <new>
 
 namespace {
@@ -663,6 +664,50 @@ int fxp_stage_forward(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_batch
                       void *hidden_out, void *workspace, size_t workspace_bytes, void *hip_stream)
 {
     return forward_impl(stage, pool, batch, hidden_in, hidden_out, workspace, workspace_bytes, nullptr, 0, hip_stream);
+}
+
+// ---- the forward step for callers that cannot allocate: the workspace is a file-scope device array.
+// The array's name is only a host-side stand-in; its address on the current device comes from
+// hipGetSymbolAddress, once per device, and that pointer is what the kernels get.
+static __device__ __align__(256) unsigned char scratch[FXP_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices];
+std::mutex g_scratch_mutex;
+
+int static_scratch(void **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return fail(FXP_EINVAL, "device index %d out of range", dev);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if ((e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch))) != hipSuccess) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+        if (!p || (uintptr_t)p % 256) return fail(FXP_EHIP, "static scratch has no usable device address");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return FXP_OK;
+}
+}  // namespace
+
+int fxp_stage_forward_static(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_batch *batch, const void *hidden_in,
+                             void *hidden_out, void *hip_stream)
+{
+    if (!stage || !pool || !batch) return fail(FXP_EINVAL, "null argument to fxp_stage_forward_static");
+    if (batch->num_tokens < 0 || batch->num_seqs < 0) return fail(FXP_EINVAL, "negative batch size");
+    if (batch->num_seqs > FXP_MAX_SEQS) return fail(FXP_EINVAL, "num_seqs %d above the limit of %d", batch->num_seqs, FXP_MAX_SEQS);
+    const size_t need = carve(stage->d, batch->num_tokens, batch->num_seqs, batch->max_blocks_per_seq, nullptr).bytes;
+    if (need > (size_t)FXP_STATIC_SCRATCH_BYTES)
+        return fail(FXP_ENOSPC, "a step of %d tokens and %d sequences needs %zu bytes of scratch; the static scratch holds %zu "
+                                "(use fxp_stage_forward with a workspace of the caller's)",
+                    batch->num_tokens, batch->num_seqs, need, (size_t)FXP_STATIC_SCRATCH_BYTES);
+    void *ws = nullptr;
+    if (int rc = static_scratch(&ws)) return rc;
+    return forward_impl(stage, pool, batch, hidden_in, hidden_out, ws, (size_t)FXP_STATIC_SCRATCH_BYTES, nullptr, 0, hip_stream);
 }
 
 int fxp_stage_forward_debug(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_batch *batch, const void *hidden_in,

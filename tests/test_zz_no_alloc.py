@@ -1,0 +1,67 @@
+"""fxp_stage_forward_static (the forward step with the library's static scratch as
+workspace, for callers that cannot allocate) against fxp_stage_forward on the same
+inputs: both run the same kernels over the same workspace layout, so outputs and
+appended cache rows are bit-identical.  Two calls in a row share the one static
+array; the second is smaller and must not see anything the first left behind."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2510_11938_amd import binding, synth
+
+from gpu_util import dev_bf16, dev_i32, filled_pool_bits, make_stage, make_weights
+
+pytestmark = pytest.mark.gpu
+
+SHAPE = synth.ModelShape(hidden=1024, n_q_heads=8, n_kv_heads=2, head_dim=128, ffn=2816)
+
+
+def both_ways(stage, ms, seed, ctx, q_lens, pool_bits, table):
+    """One step through either entry point on its own copy of the cache -> (outputs, pools)."""
+    ctx, q_lens = np.asarray(ctx, dtype=np.int32), np.asarray(q_lens, dtype=np.int32)
+    T = int(q_lens.sum())
+    x = dev_bf16(synth.hidden_states(T, ms.hidden, seed))
+    cu, cl = dev_i32(synth.cu_seqlens(q_lens)), dev_i32(ctx)
+    outs, pools = [], []
+    for static in (False, True):
+        cache = binding.KVCache(torch.from_numpy(pool_bits.view(np.int16)).cuda(), 0, pool_bits.shape[0], dev_i32(table))
+        y = torch.full_like(x, 7.0)
+        if static:
+            stage.forward_static(cache, cu, cl, x, int(q_lens.max()), y)
+        else:
+            stage.forward(cache, cu, cl, x, int(q_lens.max()), hidden_out=y)
+        torch.cuda.synchronize()
+        outs.append(y.view(torch.int16).cpu())
+        pools.append(cache.pool.cpu())
+    return outs, pools
+
+
+def test_static_scratch_forward_equals_workspace_forward_on_two_calls_in_a_row():
+    ms, L, seed = SHAPE, 2, 31
+    w = make_weights(ms, seed, L, want_f32=False)
+    stage = make_stage(ms, w, 0, L)
+    # first call: a mixed batch (one prompt chunk behind a prefix, decode rows); second call: a smaller decode batch
+    calls = [([300, 1100, 17, 640, 2047, 5], [70, 1, 1, 1, 1, 33]), ([513, 40, 900], [1, 1, 1])]
+    for ctx, q_lens in calls:
+        ctx_a, q_a = np.asarray(ctx, dtype=np.int32), np.asarray(q_lens, dtype=np.int32)
+        table, nblk = synth.block_table(ctx_a + q_a, 16, seed, salt=len(ctx))
+        pool_bits = filled_pool_bits(ms, seed, L, ctx_a, table, nblk)
+        (y_ws, y_static), (p_ws, p_static) = both_ways(stage, ms, seed, ctx, q_lens, pool_bits, table)
+        assert torch.isfinite(y_ws.view(torch.bfloat16).float()).all()
+        assert torch.equal(y_ws, y_static), f"outputs differ for a step of {int(q_a.sum())} tokens"
+        assert torch.equal(p_ws, p_static), "appended cache rows differ"
+        assert not torch.equal(p_ws, torch.from_numpy(pool_bits.view(np.int16))), "the step appended nothing"
+
+
+def test_static_scratch_rejects_a_step_beyond_its_size():
+    # a 65536-token prompt needs far more workspace than the static array holds: rejected on the host, nothing enqueued
+    w = make_weights(SHAPE, 32, 1, want_f32=False)
+    stage = make_stage(SHAPE, w, 0, 1)
+    T = 65536
+    assert stage.workspace_bytes(T, 1, T // 16 + 1) > 64 << 20
+    table = dev_i32(np.zeros((1, T // 16 + 1)))
+    cache = binding.KVCache(torch.zeros((1, 1, 2, SHAPE.n_kv_heads, 16, SHAPE.head_dim), dtype=torch.int16, device="cuda"), 0, 1, table)
+    x = torch.zeros((T, SHAPE.hidden), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(binding.FxpError) as err:
+        stage.forward_static(cache, dev_i32([0, T]), dev_i32([0]), x, T, torch.empty_like(x))
+    assert err.value.code == binding.FXP_ENOSPC and "static scratch" in str(err.value)
