@@ -58,29 +58,34 @@ def calibration_copy(torch, dev) -> None:
 
 
 
-def bench_prefill(args, wl) -> int:
-    """Secondary mode (--workload C3): one step = the chunked-prefill forward of the whole ragged
-    batch (prompts log-uniform in [256,2048], empty cache).  Reports prefill tokens/s and the MFMA
-    roofline of the tiled projection kernel."""
-    import torch
+def timed_steps(torch, step, k):
+    """k steps, each between two events on the current stream, the whole loop between two synchronisations.
+    Returns ([ms of each step], wall-clock ms per step over the loop)."""
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(k + 1)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev[0].record()
+    for i in range(k):
+        step()
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) * 1e3 / k
+    return [ev[i].elapsed_time(ev[i + 1]) for i in range(k)], wall
+
+
+def prefill_record(torch, wl, stage, steps, warmup, weights_note=""):
+    """One step = the chunked-prefill forward of the whole ragged batch of workload ``wl`` (prompts log-uniform in
+    [256,2048], empty cache) through ``stage``.  Returns the record: prefill tokens/s (median of event-timed steps) and
+    the MFMA roofline of the tiled projection kernel from HIP events around each of its launches."""
     from paper_2510_11938_amd import binding, synth
     ms, L, B = wl.shape, wl.n_layers, wl.num_seqs
     dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
-
-    def to_dev(bits):
-        return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(dev).view(torch.bfloat16)
-
     lens = synth.draw_lengths(wl.length_dist, B, wl.seed)
     T = int(lens.sum())
     table, nblk = synth.block_table(lens, 16, wl.seed)
-    w_dev = [{k: to_dev(v) for k, v in synth.layer_weights(ms, wl.seed, l).items()} for l in range(L)]
-    stage = binding.Stage(ms, 0, L, w_dev)
-    torch.cuda.synchronize()
-    del w_dev
     cache = binding.KVCache(torch.zeros((L, nblk, 2, ms.n_kv_heads, 16, ms.head_dim), dtype=torch.int16, device=dev), 0, L,
                             torch.from_numpy(table).to(dev))
-    x = to_dev(synth.hidden_states(T, ms.hidden, wl.seed))
+    x = torch.from_numpy(synth.hidden_states(T, ms.hidden, wl.seed).view(np.int16)).to(dev).view(torch.bfloat16)
     y = torch.empty_like(x)
     cu = torch.from_numpy(synth.cu_seqlens(lens)).to(dev)
     cl = torch.zeros(B, dtype=torch.int32, device=dev)
@@ -89,35 +94,49 @@ def bench_prefill(args, wl) -> int:
     def step():
         stage.forward(cache, cu, cl, x, mq, hidden_out=y, min_q_len=int(lens.min()))
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    step_ms, wall_ms = timed_steps(torch, step, steps)
+    ms_per_step = float(np.median(step_ms))
     binding.profile_enable(True)
-    for _ in range(args.steps):
+    for _ in range(steps):
         step()
     torch.cuda.synchronize()
     prof = binding.profile_read()
     binding.profile_enable(False)
-    kernels = {k: {"avg_us": v["ms"] * 1e3 / v["launches"], "launches_per_step": v["launches"] / args.steps} for k, v in prof.items()}
+    kernels = {k: {"avg_us": v["ms"] * 1e3 / v["launches"], "launches_per_step": v["launches"] / steps} for k, v in prof.items()}
     flops_layer = 2 * T * (ms.params_per_layer - 2 * ms.hidden)          # the four projections of one layer
     gemm_ms_layer = kernels["gemm_tiled"]["avg_us"] * 4 / 1e3
     tflops = flops_layer / (gemm_ms_layer * 1e-3) / 1e12
-    out = {
+    attn_flops_layer = 2 * 2 * int((lens.astype(np.int64) * (lens.astype(np.int64) + 1) // 2).sum()) * ms.n_q_heads * ms.head_dim
+    return {
         "metric": "stage prefill tokens/s (7B shape, 4 layers, 16 ragged prompts)", "value": T / (ms_per_step * 1e-3), "unit": "tokens/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step, "ms_per_step_wall_mean": wall_ms, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{wl.name}: {ms.hidden}-hidden {ms.n_q_heads}/{ms.n_kv_heads}x{ms.head_dim} heads, ffn {ms.ffn}, {L} layers, "
-                               f"{B} prompts {wl.length_dist}, {T} tokens, kv block 16", "seed": wl.seed},
+                               f"{B} prompts {wl.length_dist}, {T} tokens, kv block 16" + weights_note, "seed": wl.seed},
         "roofline": {"kernel": "gemm_tiled_kernel", "bound": "mfma", "achieved": tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
                      "algorithmic_flops_per_layer": flops_layer, "avg_launch_us": kernels["gemm_tiled"]["avg_us"]},
+        "attn_prefill": {"avg_launch_us": kernels["attn_prefill"]["avg_us"], "causal_flops_per_layer": attn_flops_layer,
+                         "TFLOPs": attn_flops_layer / (kernels["attn_prefill"]["avg_us"] * 1e-6) / 1e12},
         "kernels": kernels,
     }
+
+
+def bench_prefill(args, wl) -> int:
+    """Secondary mode (--workload C3): the prefill step as the headline of its own JSON line."""
+    import torch
+    from paper_2510_11938_amd import binding, synth
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    ms, L = wl.shape, wl.n_layers
+    w_dev = [{k: torch.from_numpy(np.ascontiguousarray(v).view(np.int16)).to(dev).view(torch.bfloat16)
+              for k, v in synth.layer_weights(ms, wl.seed, l).items()} for l in range(L)]
+    stage = binding.Stage(ms, 0, L, w_dev)
+    torch.cuda.synchronize()
+    del w_dev
+    out = prefill_record(torch, wl, stage, args.steps, args.warmup)
+    out.update({"n_gpus": 1, "higher_is_better": True, "scaling": "weak", "vs_baseline": None})
     calibration_copy(torch, dev)
     print(json.dumps(out))
     return 0
@@ -130,6 +149,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="C2", help="synthetic workload id (C2 is the headline configuration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-prefill", action="store_true", help="skip the chunked-prefill sub-record (workload C3 through the same stage)")
     ap.add_argument("--no-incremental", action="store_true",
                     help="skip the concurrent-snapshot / delta-pass leg (keeps a kernel trace free of deliberately overlapped kernels)")
     ap.add_argument("--cpu-sample-seqs", type=int, default=0, help="sequences the oracle is timed on (0 = the whole batch)")
@@ -160,7 +180,8 @@ def main() -> int:
     t_setup = time.time()
     ctx = synth.draw_lengths(wl.length_dist, B, wl.seed)
     table, nblk = synth.block_table(ctx + 1, 16, wl.seed)
-    w_bits = [synth.layer_weights(ms, wl.seed, l) for l in range(L)]
+    with ThreadPoolExecutor(max_workers=8) as ex:        # every layer has a generator of its own
+        w_bits = list(ex.map(lambda l: synth.layer_weights(ms, wl.seed, l), range(L)))
     w_dev = [{k: to_dev(v) for k, v in lw.items()} for lw in w_bits]
     stage = binding.Stage(ms, 0, L, w_dev)
     torch.cuda.synchronize()
@@ -186,14 +207,13 @@ def main() -> int:
         stage.forward(cache, cu, cl, x, 1, hidden_out=y)
 
     # ---- decode: W warm-up steps, then exactly K timed steps -------------------------
-    for _ in range(args.warmup):
+    # Every step is bracketed by HIP events on the stream the library launches on; `value` is the median step, the
+    # wall-clock mean over the same K steps and the very first step of the process are reported beside it.
+    first_ms = timed_steps(torch, step, 1)[0][0]
+    for _ in range(max(0, args.warmup - 1)):
         step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    step_ms, wall_ms = timed_steps(torch, step, args.steps)
+    ms_per_step = float(np.median(step_ms))
     tokens_per_s = B / (ms_per_step * 1e-3)
 
     # ---- per-kernel durations: the same K steps again with an event pair around each launch
@@ -239,6 +259,33 @@ def main() -> int:
     torch.cuda.synchronize()
     move_ms = ev0.elapsed_time(ev1) / reps
     move_gbps = move_bytes / (move_ms * 1e-3) / 1e9
+
+    def event_timed(fn, n):
+        fn()
+        torch.cuda.synchronize()
+        ev0.record()
+        for _ in range(n):
+            fn()
+        ev1.record()
+        torch.cuda.synchronize()
+        return ev0.elapsed_time(ev1) / n
+
+    # What a copy reaches on this machine, timed in the same run: (a) the runtime's own device-to-device copy of about
+    # the same number of bytes, contiguous; (b) this library's mover on the same blocks through IDENTITY tables
+    # (block j of the pool -> block j of another pool: a contiguous copy issued by the kernel under test).
+    ceil_src = cache.pool.view(-1)[: move_bytes // 4]                 # read + write = move_bytes
+    ceil_dst = torch.empty_like(ceil_src)
+    copy_ms = event_timed(lambda: ceil_dst.copy_(ceil_src), reps)
+    del ceil_dst
+    ident_lens = np.full(B, (moved_blocks // B) * 16, dtype=np.int32)   # the same blocks in total (to within B - 1), equal per sequence
+    nb_i = int(ident_lens[0]) // 16
+    ident_table = torch.arange(B * nb_i, dtype=torch.int32, device=dev).reshape(B, nb_i)
+    id_src = binding.KVCache(cache.pool[:, : B * nb_i].contiguous(), 0, L, ident_table)
+    id_dst = binding.KVCache(torch.empty_like(id_src.pool), 0, L, ident_table)
+    ident_cl = torch.from_numpy(ident_lens).to(dev)
+    ident_ms = event_timed(lambda: binding.kv_repartition(ms, [id_src], [id_dst], ident_cl), reps)
+    ident_bytes = 2 * B * nb_i * L * ms.block_elems * 2
+    del id_src, id_dst
 
     # ---- incremental repartition (Section 6.3: transfers run while inference continues) -----
     # (a) the snapshot pass on a second stream while decode steps run on the first: both are
@@ -286,6 +333,9 @@ def main() -> int:
                   f"stage decode tokens/s ({wl.name}: hidden {ms.hidden}, {L} layers, B={B}); KV repartition GB/s vs HBM",
         "value": tokens_per_s, "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "timing": {"value_from": "median of the K steps, each timed with a HIP event pair on the launch stream",
+                   "ms_per_step_wall_mean": wall_ms, "ms_per_step_min": float(np.min(step_ms)), "ms_per_step_max": float(np.max(step_ms)),
+                   "first_step_of_process_ms": first_ms},
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{wl.name}: {ms.hidden}-hidden {ms.n_q_heads}/{ms.n_kv_heads}x{ms.head_dim} heads, ffn {ms.ffn}, "
@@ -293,15 +343,26 @@ def main() -> int:
                    "seed": wl.seed, "tokens_in_cache": int(ctx.sum())},
         "hbm_ideal_ms_per_step": ideal_ms, "frac_of_hbm_ideal": ideal_ms / ms_per_step,
         "kv_repartition": {"GBps": move_gbps, "ms": move_ms, "bytes_read_plus_written": move_bytes,
-                           "frac_of_hbm_peak": move_gbps / HBM_PEAK_GBPS, "split": f"[0,{L}) -> [0,{half}) + [{half},{L})"},
+                           "frac_of_hbm_peak": move_gbps / HBM_PEAK_GBPS, "split": f"[0,{L}) -> [0,{half}) + [{half},{L})",
+                           "copy_ceiling_GBps": move_bytes / (copy_ms * 1e-3) / 1e9,
+                           "copy_ceiling": f"the runtime's device-to-device copy of {move_bytes // 2} contiguous bytes, read + write counted, same run",
+                           "identity_tables_GBps": ident_bytes / (ident_ms * 1e-3) / 1e9,
+                           "frac_of_copy_ceiling": move_gbps / (move_bytes / (copy_ms * 1e-3) / 1e9)},
         "roofline": {"kernel": "attn_decode_kernel", "bound": "hbm", "achieved": attn_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": attn_gbps / HBM_PEAK_GBPS,
                      "traffic": read_traffic(os.path.join(ROOT, "profiles", "attn_decode_c2_pmc.txt"), "attn_decode_kernel"),
+                     "traffic_source": "profiles/attn_decode_c2_pmc.txt (rocprofv3 --pmc runs of this command, committed; not measured in this run)",
                      "algorithmic_bytes_per_launch": attn_bytes, "avg_launch_us": attn_us},
         "incremental_repartition": incremental,
         "kernels": kernels,
         "setup_s": setup_s,
     }
+
+    # ---- the chunked-prefill variant of the step (workload C3: 16 ragged prompts, 15,928 tokens) through the same stage:
+    # the MFMA-bound side of the path, timed in the same run
+    if wl.name == "C2" and not args.no_prefill:
+        out["prefill"] = prefill_record(torch, synth.WORKLOADS["C3"], stage, 5, 2,
+                                        weights_note="; through the decode workload's stage (same shape and depth, weights of seed 1)")
 
     # ---- the oracle on the host cores, on a bounded sample of the same workload ------
     if not args.no_cpu_baseline:
@@ -333,6 +394,21 @@ def main() -> int:
                                          f"sequences of the batch ({int(ctx[sample].sum())} cached tokens), {cpu_s:.1f} s of oracle time",
                                "gpu_vs_oracle_rel_l2": float(np.sqrt(((got - ref) ** 2).sum(axis=1) / (ref ** 2).sum(axis=1)).max()),
                                "gpu_vs_oracle_max_elem": float((np.abs(got - ref) / np.maximum(np.abs(ref), rms)).max())}
+        # the plain-loop repartition of the oracle on the same cache, same split, same tables, host memory
+        osrc = [oracle.KVView(pool_host, 0, L, table)]
+        odst = []
+        for dv in dst:
+            t_host = dv.block_table.cpu().numpy()
+            odst.append(oracle.KVView(np.zeros(tuple(dv.pool.shape), dtype=np.uint16), dv.layer_begin, dv.layer_end, t_host))
+        oracle.kv_repartition(osh, osrc, odst, ctx)                  # first pass touches the destination pages
+        t0 = time.perf_counter()
+        oracle.kv_repartition(osh, osrc, odst, ctx)
+        o_s = time.perf_counter() - t0
+        same = all(np.array_equal(dv.pool.cpu().numpy().view(np.uint16), od.pool) for dv, od in zip(dst, odst))
+        out["kv_repartition"]["cpu_baseline"] = {"GBps": move_bytes / o_s / 1e9, "ms": o_s * 1e3, "cores": 1, "kind": "oracle",
+                                                 "sample": f"the whole workload: every block of the {B} sequences, {L} layers, one pass "
+                                                           "(the oracle's repartition is one plain loop on one thread)",
+                                                 "gpu_equals_oracle_bit_exact": bool(same)}
     calibration_copy(torch, dev)
     print(json.dumps(out))
     return 0
