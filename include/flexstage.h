@@ -22,7 +22,8 @@
  *   - bf16 = the 16-bit brain-float format (1 sign, 8 exponent, 7 mantissa bits).
  *   - Results are deterministic: the same inputs give bit-identical outputs,
  *     independent of the physical block placement and of how many layers the
- *     stage holds.
+ *     stage holds.  Launch shapes are fixed by the shapes of a call and the
+ *     device's compute-unit count; no environment variable changes them.
  */
 #ifndef FLEXSTAGE_H
 #define FLEXSTAGE_H
@@ -217,7 +218,10 @@ int    fxp_kv_repartition(const fxp_stage_desc *desc,
                           const fxp_kv_view *dst, int32_t n_dst,
                           const int32_t *ctx_lens, int32_t num_seqs, void *hip_stream);
 
-/* The two halves of a repartition that crosses devices: pack gathers layers
+/* The two halves of a repartition that crosses devices (Section 8: the cache moves between
+ * GPU devices over a network transfer; Section 6.3, Eq. 10 fixes WHAT arrives: the source
+ * cache times the token validity mask).  Each half applies that rule on its side of the
+ * transfer, so unpack(pack(src)) leaves exactly what fxp_kv_repartition leaves.  pack gathers layers
  * [layer_begin, layer_end) of ONE source view into a contiguous DEVICE buffer
  *   [sequence][layer - layer_begin][logical block][2: K,V][kv_head][slot][head_dim]
  * (invalid slots zero); unpack scatters such a buffer into ONE destination
@@ -227,12 +231,18 @@ int    fxp_kv_repartition(const fxp_stage_desc *desc,
  * the caller really has, and a (layer, block) unit that would not lie wholly
  * inside it is skipped, so neither call ever touches memory past the buffer;
  * FXP_ENOSPC is returned only when not even one block per layer fits. */
+/* fxp_kv_packed_bytes: sum over sequences of ceil(ctx_lens[i]/16) blocks x layers x one (layer, block)
+ * unit of 2 * n_kv_heads * 16 * head_dim bf16 values: the valid blocks of Eq. 10's mask, whole blocks. */
 size_t fxp_kv_packed_bytes(const fxp_stage_desc *desc, int32_t layer_begin, int32_t layer_end,
                            const int32_t *ctx_lens_host, int32_t num_seqs);
+/* fxp_kv_pack (source side of Eq. 10): block j of sequence i, layer l goes from src_table[i][j] to its place in
+ * the buffer; slots at or beyond ctx_lens[i] are written as zero. */
 int    fxp_kv_pack(const fxp_stage_desc *desc, const fxp_kv_view *src,
                    int32_t layer_begin, int32_t layer_end,
                    const int32_t *ctx_lens, int32_t num_seqs,
                    void *packed, size_t packed_bytes, void *hip_stream);
+/* fxp_kv_unpack (destination side of Eq. 10): the buffer's blocks go to dst_table[i][j] of the fresh table;
+ * blocks that no listed sequence maps to are not written. */
 int    fxp_kv_unpack(const fxp_stage_desc *desc, const void *packed, size_t packed_bytes,
                      const fxp_kv_view *dst, int32_t layer_begin, int32_t layer_end,
                      const int32_t *ctx_lens, int32_t num_seqs, void *hip_stream);

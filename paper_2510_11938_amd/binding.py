@@ -15,8 +15,8 @@ from typing import Dict, List, Optional, Sequence
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-# FXP_LIBRARY may point at another build of the same library (kernel tuning experiments)
-LIB_PATH = os.environ.get("FXP_LIBRARY") or os.path.join(_HERE, "libflexstage.so")
+# the library this binding opens (a kernel experiment may assign another build's path here before the first call)
+LIB_PATH = os.path.join(_HERE, "libflexstage.so")
 
 FXP_OK, FXP_EINVAL, FXP_ENOSPC, FXP_EHIP = 0, -1, -2, -3
 

@@ -28,7 +28,12 @@ def _stale(target: str, deps) -> bool:
     return any(os.path.getmtime(d) > t for d in deps)
 
 
-def build(force: bool = False, verbose: bool = False) -> str:
+def build(force: bool = False, verbose: bool = False, tuning: bool = False) -> str:
+    """tuning=True builds libflexstage_tuning.so instead: the same sources with -DFXP_TUNING, whose launch shapes can be
+    overridden through FXP_* environment variables (kernel experiments only; the normal build ignores them)."""
+    global OBJ, LIB
+    if tuning:
+        OBJ, LIB = os.path.join(HERE, "_build_tuning"), os.path.join(HERE, "libflexstage_tuning.so")
     os.makedirs(OBJ, exist_ok=True)
     headers = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")]
     headers.append(os.path.join(os.path.dirname(HERE), "include", "flexstage.h"))
@@ -36,7 +41,8 @@ def build(force: bool = False, verbose: bool = False) -> str:
     def compile_one(u: str) -> str:
         src, obj = os.path.join(CSRC, u + ".hip"), os.path.join(OBJ, u + ".o")
         if force or _stale(obj, [src] + headers):
-            r = subprocess.run(["hipcc", *FLAGS, *UNIT_FLAGS.get(u, []), "-c", src, "-o", obj], capture_output=True, text=True)
+            r = subprocess.run(["hipcc", *FLAGS, *(["-DFXP_TUNING"] if tuning else []), *UNIT_FLAGS.get(u, []), "-c", src, "-o", obj],
+                               capture_output=True, text=True)
             err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
             if r.returncode != 0:
                 raise RuntimeError(f"hipcc failed on {u}.hip:\n{err}")
@@ -52,4 +58,4 @@ def build(force: bool = False, verbose: bool = False) -> str:
 
 
 if __name__ == "__main__":
-    print(build(force="--force" in sys.argv, verbose=True))
+    print(build(force="--force" in sys.argv, verbose=True, tuning="--tuning" in sys.argv))

@@ -590,7 +590,7 @@ hipError_t launch_attn_decode_combine(const DecodeAttnArgs &a, hipStream_t strea
 
 int decode_head_group(int n_kv_heads)
 {
-    static const int forced = getenv("FXP_DECODE_HEAD_GROUP") ? atoi(getenv("FXP_DECODE_HEAD_GROUP")) : 0;
+    static const int forced = tuning_int("FXP_DECODE_HEAD_GROUP", 0);
     if (forced > 0 && kDecWaves % forced == 0 && n_kv_heads % forced == 0) return forced;
     return n_kv_heads % 4 == 0 ? 4 : (n_kv_heads % 2 == 0 ? 2 : 1);
 }

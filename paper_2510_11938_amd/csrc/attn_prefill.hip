@@ -38,7 +38,7 @@ constexpr int kPfKvTile = 64;       // keys per LDS tile (4 cache blocks)
 constexpr int kPfMinPieceTiles = 8; // a query tile's keys are cut into pieces of at least this many LDS tiles
 constexpr int kPfMaxPieces = 8;
 // workgroups of this kernel that the chip holds at a time: 3 per compute unit with 64 query rows, 2 with 128
-constexpr int prefill_resident_wgs(int q_tile) { return q_tile == 64 ? 768 : 512; }
+static int prefill_resident_wgs(int q_tile) { return (q_tile == 64 ? 3 : 2) * device_cus(); }
 
 // Pieces that the keys of one query tile are cut into when the launch has too few query tiles to fill the chip (a short
 // chunk behind a long cached prefix): as many as the launch allows, each at least kPfMinPieceTiles tiles long.
@@ -397,11 +397,11 @@ __global__ void attn_probs_normalize_kernel(float *scores, const float *ml, int6
 // (then the walks are long and even, and cut keys fill the chip: 512 tokens behind 8192 cached: 146 -> 122 us).
 int prefill_q_tile(int n_q_heads, int num_tokens, int num_seqs, int max_q_len, int max_blocks_per_seq)
 {
-    static const int forced = getenv("FXP_PREFILL_Q_TILE") ? atoi(getenv("FXP_PREFILL_Q_TILE")) : 0;
+    static const int forced = tuning_int("FXP_PREFILL_Q_TILE", 0);
     if (forced == 64 || forced == 128) return forced;
     if (num_tokens < 128 * (int64_t)std::max(num_seqs, 1)) return 64;
     const int64_t tiles = (int64_t)n_q_heads * (num_tokens / 128);
-    if (tiles >= 768) return 128;
+    if (tiles >= prefill_resident_wgs(64)) return 128;
     const bool prefix_room = (int64_t)max_blocks_per_seq * kBlockTokens - max_q_len >= 2 * kPfMinPieceTiles * kPfKvTile;
     return prefix_room && tiles * kPfMaxPieces >= prefill_resident_wgs(128) ? 128 : 64;
 }
@@ -413,7 +413,7 @@ size_t prefill_piece_rows(int n_q_heads, int max_tokens)
 }
 int prefill_kv_split(int n_q_heads, int num_tokens, int num_seqs, int max_blocks_per_seq, int q_tile)
 {
-    static const int forced = getenv("FXP_PREFILL_KV_SPLIT") ? atoi(getenv("FXP_PREFILL_KV_SPLIT")) : 0;
+    static const int forced = tuning_int("FXP_PREFILL_KV_SPLIT", 0);
     const int64_t rows = (int64_t)std::max(num_tokens, 1) * n_q_heads;
     const int64_t fits = (int64_t)prefill_piece_rows(n_q_heads, num_tokens) / rows;      // pieces the workspace has rows for
     if (forced > 0) return (int)std::max<int64_t>(1, std::min<int64_t>(std::min(forced, kPfMaxPieces), fits));
@@ -435,7 +435,7 @@ static hipError_t launch_q(const PrefillAttnArgs &a_in, hipStream_t stream)
     // one line of tiles when the rectangle (tiles of the longest prompt x sequences) would be more than eight times as
     // large (an empty workgroup costs a few nanoseconds, which only matters when there are very many of them)
     const int rect_x = (a.max_q_len + QT - 1) / QT, flat_x = a.num_tokens / QT + a.num_seqs;
-    static const int forced = getenv("FXP_PREFILL_FLAT_GRID") ? atoi(getenv("FXP_PREFILL_FLAT_GRID")) : -1;
+    static const int forced = tuning_int("FXP_PREFILL_FLAT_GRID", -1);
     const bool flat = forced >= 0 ? forced != 0 : (int64_t)rect_x * a.num_seqs > 8 * (int64_t)flat_x;
     const dim3 grid = flat ? dim3(a.n_q_heads, flat_x * a.kv_split) : dim3(a.n_q_heads, a.num_seqs, rect_x * a.kv_split);
     const size_t lds = flat ? (size_t)(a.num_seqs + 1) * sizeof(int32_t) : 0;

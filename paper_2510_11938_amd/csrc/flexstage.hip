@@ -95,23 +95,8 @@ LayerRecord layer_record(const fxp_stage_desc &d)
     return r;
 }
 
-int device_cus()
-{
-    static int cus = 0;
-    if (!cus) {
-        int dev = 0;
-        hipDeviceProp_t p;
-        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&p, dev) == hipSuccess) cus = p.multiProcessorCount;
-        if (cus <= 0) cus = 256;
-    }
-    return cus;
-}
-
-int env_int(const char *name, int dflt)
-{
-    const char *v = getenv(name);
-    return (v && *v) ? atoi(v) : dflt;
-}
+using fxp::device_cus;
+int env_int(const char *name, int dflt) { return fxp::tuning_int(name, dflt); }
 
 // Launch shape of a skinny projection: R weight tiles per wavefront (workgroup =
 // 4 wavefronts = 64*R rows) and the split-K factor S.  Enough workgroups to put
@@ -120,17 +105,17 @@ int env_int(const char *name, int dflt)
 // Depends on shapes only, so results do not depend on anything else.
 struct SkinnyCfg { int R, S; };
 // The gate|up projection applies SwiGLU in its epilogue (no split-K, no partial sums) when its
-// 2F weight rows alone give every CU of a 256-CU chip most of a workgroup (128 rows each).
+// 2F weight rows alone give every second CU a workgroup (128 rows each) or more.
 bool skinny_fused_swiglu(int N2)
 {
     static const int off = env_int("FXP_NO_FUSED_SWIGLU", 0);
-    return !off && N2 / 128 >= 128;
+    return !off && N2 / 128 >= device_cus() / 2;
 }
 
 SkinnyCfg skinny_cfg(int N, int K, int M)
 {
     static const int forced_s = env_int("FXP_SKINNY_SPLIT", 0), forced_r = env_int("FXP_SKINNY_R", 0);
-    static const int max_wgs = env_int("FXP_SKINNY_MAX_WGS", 256);
+    static const int max_wgs = env_int("FXP_SKINNY_MAX_WGS", device_cus());
     const int ks = k_steps(K);
     SkinnyCfg c;
     // Measured on MI355X: about one workgroup (4 wavefronts, 8-16 KiB of weights in flight each)
@@ -145,7 +130,7 @@ SkinnyCfg skinny_cfg(int N, int K, int M)
         // Up to 16 pieces: a narrow matrix at 65..128 rows (hidden 4096 or 5120: 16 or 20 tiles) otherwise fills half
         // the chip, which costs more than the extra partial sums (7B shape, 128 rows: 130 -> 123 us per layer).
         static const int cap = env_int("FXP_TILED_SPLIT_CAP", 16);
-        c.S = forced_s ? forced_s : std::max(1, std::min(std::min(cap, ks / 8), 256 / wgs));
+        c.S = forced_s ? forced_s : std::max(1, std::min(std::min(cap, ks / 8), device_cus() / wgs));
         return c;
     }
     const int wgs_n = (N + 64 * c.R - 1) / (64 * c.R);
@@ -154,7 +139,7 @@ SkinnyCfg skinny_cfg(int N, int K, int M)
         // 33..64 rows: one workgroup per CU as well, with the ring of four register buffers (two workgroups per CU
         // with two buffers each had been the better of the two-buffer forms; with four buffers one per CU wins on
         // every shape tried: 7B 64 rows 117 -> 106 us per layer, 13B 143 -> 135, 70B 313 -> 305)
-        static const int wgs64 = env_int("FXP_SKINNY_MAX_WGS64", 256), cap64 = env_int("FXP_SKINNY_CAP64", 12);
+        static const int wgs64 = env_int("FXP_SKINNY_MAX_WGS64", device_cus()), cap64 = env_int("FXP_SKINNY_CAP64", 12);
         s = std::max(1, std::min(std::min(cap64, ks / 16), wgs64 / wgs_n));
     } else {
         // up to 32 rows: as many workgroups as fit once on a 256-CU chip, any integer split (13B and 70B shapes:
@@ -203,6 +188,17 @@ struct KernelTimer {     // records an event pair around the launches made durin
 namespace fxp {
 // error reporting for the host-only translation units of the library
 int ctl_fail(int code, const char *msg) { return fail(code, "%s", msg); }
+
+int device_cus()
+{
+    static int cus = 0;
+    if (!cus) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess) cus = n;
+        if (cus <= 0) cus = 256;          // no device visible (host-only use of the size queries): the MI355X count
+    }
+    return cus;
+}
 }
 
 struct fxp_stage {

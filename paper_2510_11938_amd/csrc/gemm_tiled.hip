@@ -56,11 +56,11 @@ __global__ __launch_bounds__(kTgThreads, 2) void gemm_tiled_kernel(TiledArgs a)
     } else if (tiles_m < 16) {
         // up to 15 rows of tiles: XCD x takes the weight tiles n = x mod 8 and walks the token tiles of each in turn,
         // so the workgroups that share weight rows follow each other on one L2
-        const int xcd = blockIdx.x % 8, seq = blockIdx.x / 8;
+        const int xcd = blockIdx.x % kXcds, seq = blockIdx.x / kXcds;
         tile_m = seq % tiles_m;
-        tile_n = (seq / tiles_m) * 8 + xcd;
+        tile_n = (seq / tiles_m) * kXcds + xcd;
     } else {
-        constexpr int kXcds = 8, kBlkN = 4, kBlkM = 8;      // 32 workgroups of one XCD = 4 x 8 tiles
+        constexpr int kBlkN = 4, kBlkM = 8;                 // 32 workgroups of one XCD = 4 x 8 tiles
         const int blocks_n = (tiles_n + kBlkN - 1) / kBlkN;
         const int id = blockIdx.x;
         const int xcd = id % kXcds, seq = id / kXcds;          // seq-th workgroup given to this XCD
@@ -283,11 +283,11 @@ hipError_t launch_gemm_tiled(const TiledArgs &a, hipStream_t stream)
     const int tiles_m = (a.M + kTgBM - 1) / kTgBM;
     // the XCD-aware numbering covers whole 4 x 8 super-blocks, rounded up to a multiple of 8 of them
     const int blocks = ((tiles_n + 3) / 4) * ((tiles_m + 7) / 8);
-    dim3 grid((blocks + 7) / 8 * 8 * 32, a.epilogue == kEpiPartial ? a.S : 1);
+    dim3 grid((blocks + kXcds - 1) / kXcds * kXcds * 32, a.epilogue == kEpiPartial ? a.S : 1);
     if (tiles_m == 1) grid.x = tiles_n;
-    else if (tiles_m < 16) grid.x = (tiles_n + 7) / 8 * 8 * tiles_m;
+    else if (tiles_m < 16) grid.x = (tiles_n + kXcds - 1) / kXcds * kXcds * tiles_m;
     const bool tail = a.K % 64 != 0;                  // a stage is 64 wide: the token rows end inside the last one
-    static const int early_tiles = getenv("FXP_TILED_EARLY_W_TILES") ? atoi(getenv("FXP_TILED_EARLY_W_TILES")) : 2;
+    static const int early_tiles = tuning_int("FXP_TILED_EARLY_W_TILES", 2);
     const bool early = tiles_m <= early_tiles;        // few row tiles: bound by the weight stream, see the kernel
 #define FXP_TG_LAUNCH(E)                                                                                       \
     if (tail) {                                                                                                \

@@ -4,8 +4,28 @@
 #include <hip/hip_runtime.h>
 #include <stddef.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 namespace fxp {
+
+// ---------------------------------------------------------------- machine and tuning
+// gfx950 is built from eight accelerator dies (XCDs) with an L2 each; workgroup i of a launch goes to die i % kXcds.
+constexpr int kXcds = 8;
+// Compute units of the current device (256 on MI355X), asked once from the runtime.
+int device_cus();
+// Launch-shape overrides for kernel experiments.  Only a -DFXP_TUNING build reads them from the environment; the
+// normal build compiles the defaults in, so launch shapes -- and with them the low-order bits of a result -- depend
+// on the shapes of a call alone.
+inline int tuning_int(const char *name, int dflt)
+{
+#ifdef FXP_TUNING
+    const char *v = getenv(name);
+    return (v && *v) ? atoi(v) : dflt;
+#else
+    (void)name;
+    return dflt;
+#endif
+}
 
 // ---------------------------------------------------------------- KV mover
 constexpr int kMaxMoveJobs = 8;

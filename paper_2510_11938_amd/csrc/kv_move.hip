@@ -175,6 +175,7 @@ __global__ __launch_bounds__(kMoveThreads, TOKEN_DENSE ? 4 : 8) void kv_move_ker
     }
 }
 
+
 hipError_t launch_kv_move(const KvMoveArgs &args, int grid, hipStream_t stream)
 {
     size_t lds = 2 * (size_t)(args.num_seqs + 1) * sizeof(int32_t);

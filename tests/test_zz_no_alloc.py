@@ -65,3 +65,19 @@ def test_static_scratch_rejects_a_step_beyond_its_size():
     with pytest.raises(binding.FxpError) as err:
         stage.forward_static(cache, dev_i32([0, T]), dev_i32([0]), x, T, torch.empty_like(x))
     assert err.value.code == binding.FXP_ENOSPC and "static scratch" in str(err.value)
+
+
+def test_static_scratch_holds_the_decode_steps_of_every_benchmark_workload():
+    # workspace of one decode step at each workload's width and batch (weights left uninitialised: only sizes matter)
+    for name in ("C2", "C4", "C5"):
+        wl = synth.WORKLOADS[name]
+        ms = wl.shape
+        shapes = {"g_attn": (ms.hidden,), "wq": (ms.n_q_heads * ms.head_dim, ms.hidden), "wk": (ms.n_kv_heads * ms.head_dim, ms.hidden),
+                  "wv": (ms.n_kv_heads * ms.head_dim, ms.hidden), "wo": (ms.hidden, ms.n_q_heads * ms.head_dim), "g_ffn": (ms.hidden,),
+                  "w_gate": (ms.ffn, ms.hidden), "w_up": (ms.ffn, ms.hidden), "w_down": (ms.hidden, ms.ffn)}
+        stage = binding.Stage(ms, 0, 1, [{k: torch.empty(v, dtype=torch.bfloat16, device="cuda") for k, v in shapes.items()}])
+        torch.cuda.synchronize()
+        need = stage.workspace_bytes(wl.num_seqs, wl.num_seqs, 8192 // 16 + 1)
+        print(f"{name}: decode step of batch {wl.num_seqs} needs {need / 2 ** 20:.1f} MiB of workspace")
+        assert need <= 64 << 20
+        stage.close()
