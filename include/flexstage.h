@@ -188,7 +188,7 @@ int    fxp_stage_forward(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_ba
  * looks the array's device address up (once per device; do it outside a graph capture).
  * All calls on one GPU share the one array, whose contents are undefined between calls:
  * calls that overlap on one GPU (two streams, two threads) race; serialise them. */
-#define FXP_STATIC_SCRATCH_BYTES (64u << 20)
+#define FXP_STATIC_SCRATCH_BYTES (128u << 20)
 int    fxp_stage_forward_static(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_batch *batch,
                                 const void *hidden_in, void *hidden_out, void *hip_stream);
 

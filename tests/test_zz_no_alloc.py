@@ -58,7 +58,7 @@ def test_static_scratch_rejects_a_step_beyond_its_size():
     w = make_weights(SHAPE, 32, 1, want_f32=False)
     stage = make_stage(SHAPE, w, 0, 1)
     T = 65536
-    assert stage.workspace_bytes(T, 1, T // 16 + 1) > 64 << 20
+    assert stage.workspace_bytes(T, 1, T // 16 + 1) > 128 << 20
     table = dev_i32(np.zeros((1, T // 16 + 1)))
     cache = binding.KVCache(torch.zeros((1, 1, 2, SHAPE.n_kv_heads, 16, SHAPE.head_dim), dtype=torch.int16, device="cuda"), 0, 1, table)
     x = torch.zeros((T, SHAPE.hidden), dtype=torch.bfloat16, device="cuda")
@@ -79,5 +79,5 @@ def test_static_scratch_holds_the_decode_steps_of_every_benchmark_workload():
         torch.cuda.synchronize()
         need = stage.workspace_bytes(wl.num_seqs, wl.num_seqs, 8192 // 16 + 1)
         print(f"{name}: decode step of batch {wl.num_seqs} needs {need / 2 ** 20:.1f} MiB of workspace")
-        assert need <= 64 << 20
+        assert need <= 128 << 20
         stage.close()
