@@ -277,8 +277,320 @@ __global__ __launch_bounds__(kTgThreads, 2) void gemm_tiled_kernel(TiledArgs a)
     }
 }
 
+
+// ---------------------------------------------------------------------------------------------------------
+// Wide tile for matrix-core-bound launches (thousands of token rows): 256 weight rows x 256 token rows per
+// workgroup, ONE workgroup of four waves per CU.  Each wave owns 64 weight rows and all 256 token rows: 64
+// accumulator tiles in the 256 accumulation registers.  Against the 256 x 128 tile above this halves the weight
+// bytes a CU has to pull in per product (128 B instead of 192 B per MFMA through the 64 B/clk vector-memory path,
+// which was what bounded that kernel at two thirds of the matrix cores).
+//   - weights: still straight from global memory into registers in operand order (never through LDS), requested
+//     three stages (six k-steps) ahead into a ring of four register sets;
+//   - token rows: global -> LDS directly (16-byte LDS-DMA loads, no registers, no LDS store instructions), three
+//     stages ahead, four LDS buffers of one 64-wide stage each (32 KiB).  One DMA instruction brings eight full
+//     128-byte rows; the data lands in lane order, so the LDS image is row-major with 128 bytes per row, and the
+//     swizzle that keeps the operand reads conflict-free is applied on the GLOBAL side: the lane that fills
+//     16-byte position p of row r fetches chunk p ^ ((r >> 1) & 7) of that row (measured: no bank conflicts);
+//   - with one wave per SIMD nothing else covers a wave's stalls or the issue time of its own loads, so the main
+//     loop is hand-placed: blocks of eight MFMAs, each with the two LDS reads of the operand pair of the block
+//     THREE further on and one load of the stage (sixteen blocks, sixteen loads) issued between its products,
+//     wave-uniform load addresses in scalar registers so that a load is one instruction, and every wait written
+//     by hand (the compiler, left to count the loads, drained them where a stage first touched its weights).
+//     Measured on the way, 7B gate|up projection at 15,928 rows: loads as compiler statements between the blocks
+//     and reads one block ahead 1.33 PFLOP/s (the 256 x 128 tile: 1.30); reads three blocks ahead between the
+//     products 1.41; loads inside the blocks 1.50; the same loop without any load 1.70.
+// Requirements (else the kernel above is used): at least 2048 token rows, K a multiple of 256, whole 64-row wave
+// tiles, token-row byte offsets below 4 GiB.
+constexpr int kWdBM = 256, kWdBN = 256, kWdRn = 4, kWdRm = 16, kWdBufs = 4;
+constexpr int kWdStageBytes = kWdBM * 128;                 // 256 rows x 64 k of bf16
+constexpr int kWdLdsBytes = kWdBufs * kWdStageBytes;       // 128 KiB
+
+// PROBE != 0 (tuning builds only; results are wrong on purpose, every access that remains is unchanged): the main loop
+// without its loads, i.e. what the LDS reads and the products alone take.
+template <int EPI, int PROBE = 0>
+__global__ __launch_bounds__(kTgThreads, 1) void gemm_wide_kernel(TiledArgs a)
+{
+    extern __shared__ __attribute__((aligned(1024))) char s_wide[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int col = lane & 15, c = lane >> 4;
+
+    // ---- tile of this workgroup: the 32 workgroups of one XCD (one per CU) form a 4 x 8 block of tiles
+    const int tiles_n = (a.NT * 16 + kWdBN - 1) / kWdBN, tiles_m = (a.M + kWdBM - 1) / kWdBM;
+    int tile_m, tile_n;
+    {
+        constexpr int kBlkN = 4, kBlkM = 8;
+        const int blocks_n = (tiles_n + kBlkN - 1) / kBlkN;
+        const int id = blockIdx.x;
+        const int xcd = id % kXcds, seq = id / kXcds;
+        const int super = seq / (kBlkN * kBlkM), within = seq % (kBlkN * kBlkM);
+        const int sb = super * kXcds + xcd;
+        tile_n = (sb % blocks_n) * kBlkN + within % kBlkN;
+        tile_m = (sb / blocks_n) * kBlkM + within / kBlkN;
+    }
+    if (tile_n >= tiles_n || tile_m >= tiles_m) return;
+    const int m0 = tile_m * kWdBM;
+    const int nt0 = tile_n * (kWdBN / 16) + wave * kWdRn;      // first 16-row tile of this wave (a multiple of 4)
+    const int KS = a.KS, KT = KS / 2;                          // stages of 64 k
+
+    // Loads are issued from inside the inline-assembly blocks of the main loop (below), with a wave-uniform base address
+    // in scalar registers plus a constant per-lane offset, so that a load costs one instruction and no address arithmetic
+    // in the vector pipe, and the compiler keeps no account of them: every wait is placed by hand.
+    // weights of this wave: tiles nt0 .. nt0+3 lie in one group of the packed layout, 1 KiB apart; k-steps 8 KiB apart
+    const char *wbase = reinterpret_cast<const char *>(a.W) + packed_operand(min(nt0, a.NT - kWdRn), 0, KS) * 16;
+    const uint32_t wlane = lane * 16;
+    auto wptr = [&](int ks) { return wbase + (int64_t)min(ks, KS - 1) * (kPackStepStride * 16); };
+    // token rows: DMA instruction i of this wave brings rows wave*64 + 8i .. +7 of the stage (lane / 8 = row, lane % 8 =
+    // position in the row); source chunk = position ^ swizzle(row); byte offsets fit 32 bits (checked by the launcher)
+    uint32_t xoff[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int row = wave * 64 + i * 8 + (lane >> 3);
+        const int chunk = (lane & 7) ^ ((row >> 1) & 7);
+        xoff[i] = (uint32_t)min(m0 + row, a.M - 1) * (uint32_t)(a.ldx * 2) + chunk * 16;      // rows past the end: clamped, never stored
+    }
+    const char *xbase = reinterpret_cast<const char *>(a.X);
+    auto xptr = [&](int kt) { return xbase + (int64_t)min(kt, KT - 1) * 128; };
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)s_wide;
+    const uint32_t lds_dma = lds_base + wave * (64 * 128);          // this wave's rows inside a stage buffer
+
+    f32x4_t acc[kWdRn][kWdRm];
+#pragma unroll
+    for (int r = 0; r < kWdRn; ++r)
+#pragma unroll
+        for (int mt = 0; mt < kWdRm; ++mt) acc[r][mt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    // operand reads: lane (col, c) of column tile mt, k-step half h reads row mt*16 + col, chunk 4h + c
+    const int sw = (col >> 1) & 7;
+    const uint32_t lds_h0 = lds_base + (col * 8 + (c ^ sw)) * 16;
+    const uint32_t lds_h1 = lds_base + (col * 8 + ((4 + c) ^ sw)) * 16;
+
+#define FXP_ACC8(M)                                                                  \
+    [a0] "+a"(acc[0][M]), [a1] "+a"(acc[1][M]), [a2] "+a"(acc[2][M]), [a3] "+a"(acc[3][M]),         \
+    [b0] "+a"(acc[0][M + 1]), [b1] "+a"(acc[1][M + 1]), [b2] "+a"(acc[2][M + 1]), [b3] "+a"(acc[3][M + 1])
+    // One block: the eight MFMAs of column tiles M, M+1 (operands in C0, C1, asked for three blocks earlier) with the two
+    // LDS reads of the operand pair of the block three further on (NADDR + OFF0, OFF1 -> N0, N1) and one load of the
+    // stage (EXTRA: assembly text, outputs, inputs, clobbers) issued between its products, where they cost the matrix
+    // cores little or nothing.  LDS returns in order: when the block starts, the pairs of the next two blocks (four
+    // reads) may still be on their way.
+#define FXP_WTEXT(OFF0, OFF1, XASM)                                                                  \
+    "s_waitcnt lgkmcnt(4)\n"                                                                         \
+    "v_mfma_f32_16x16x32_bf16 %[a0], %[w0], %[c0], %[a0]\n"                                           \
+    "ds_read_b128 %[n0], %[naddr] offset:" #OFF0 "\n"                                                 \
+    "v_mfma_f32_16x16x32_bf16 %[a1], %[w1], %[c0], %[a1]\n"                                           \
+    "ds_read_b128 %[n1], %[naddr] offset:" #OFF1 "\n"                                                 \
+    "v_mfma_f32_16x16x32_bf16 %[a2], %[w2], %[c0], %[a2]\n"                                           \
+    "v_mfma_f32_16x16x32_bf16 %[a3], %[w3], %[c0], %[a3]\n"                                           \
+    XASM                                                                                             \
+    "v_mfma_f32_16x16x32_bf16 %[b0], %[w0], %[c1], %[b0]\n"                                           \
+    "v_mfma_f32_16x16x32_bf16 %[b1], %[w1], %[c1], %[b1]\n"                                           \
+    "v_mfma_f32_16x16x32_bf16 %[b2], %[w2], %[c1], %[b2]\n"                                           \
+    "v_mfma_f32_16x16x32_bf16 %[b3], %[w3], %[c1], %[b3]\n"
+#define FXP_WINS(W, NADDR, C0, C1)                                                                   \
+    [naddr] "v"(NADDR), [w0] "v"(W[0]), [w1] "v"(W[1]), [w2] "v"(W[2]), [w3] "v"(W[3]), [c0] "v"(C0), [c1] "v"(C1)
+    // block without a load
+#define FXP_WBLOCK_N(W, N0, N1, NADDR, OFF0, OFF1, C0, C1, M)                                        \
+    asm volatile(FXP_WTEXT(OFF0, OFF1, "")                                                           \
+                 : [n0] "=&v"(N0), [n1] "=&v"(N1), FXP_ACC8(M) : FXP_WINS(W, NADDR, C0, C1) : "memory");
+    // block that carries token-row DMA instruction I of the stage (M0 = LDS address of lane 0's 16 bytes)
+#define FXP_WBLOCK_X(W, N0, N1, NADDR, OFF0, OFF1, C0, C1, M, I, XB, BUF)                            \
+    asm volatile(FXP_WTEXT(OFF0, OFF1, "s_mov_b32 m0, %[ld]\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %[xo], %[xb]\n") \
+                 : [n0] "=&v"(N0), [n1] "=&v"(N1), FXP_ACC8(M)                                        \
+                 : FXP_WINS(W, NADDR, C0, C1), [ld] "s"(lds_dma + (BUF) * kWdStageBytes + (I) * 1024), [xo] "v"(xoff[I]), [xb] "s"(XB) \
+                 : "memory");
+    // block that carries one weight load
+#define FXP_WBLOCK_W(W, N0, N1, NADDR, OFF0, OFF1, C0, C1, M, WD, WB, WOFF)                          \
+    asm volatile(FXP_WTEXT(OFF0, OFF1, "global_load_dwordx4 %[wd], %[wo], %[wb] offset:" #WOFF "\n")  \
+                 : [n0] "=&v"(N0), [n1] "=&v"(N1), FXP_ACC8(M), [wd] "=&v"(WD)                        \
+                 : FXP_WINS(W, NADDR, C0, C1), [wo] "v"(wlane), [wb] "s"(WB) : "memory");
+    u32x4 x0a, x0b, x1a, x1b, x2a, x2b, x3a, x3b;          // four operand pairs: block j of a k-step multiplies pair j % 4
+    // One k-step (16 column tiles, 64 MFMAs) in eight blocks, each carrying one load of the stage.  ADDR: this lane's slot
+    // of column tile 0 of this k-step; NEXT: of the next one.
+#define FXP_WKSTEP_X(W, ADDR, NEXT, XB, BUF)                                      \
+    FXP_WBLOCK_X(W, x3a, x3b, ADDR, 12288, 14336, x0a, x0b, 0, 0, XB, BUF)        \
+    FXP_WBLOCK_X(W, x0a, x0b, ADDR, 16384, 18432, x1a, x1b, 2, 1, XB, BUF)        \
+    FXP_WBLOCK_X(W, x1a, x1b, ADDR, 20480, 22528, x2a, x2b, 4, 2, XB, BUF)        \
+    FXP_WBLOCK_X(W, x2a, x2b, ADDR, 24576, 26624, x3a, x3b, 6, 3, XB, BUF)        \
+    FXP_WBLOCK_X(W, x3a, x3b, ADDR, 28672, 30720, x0a, x0b, 8, 4, XB, BUF)        \
+    FXP_WBLOCK_X(W, x0a, x0b, NEXT, 0, 2048, x1a, x1b, 10, 5, XB, BUF)            \
+    FXP_WBLOCK_X(W, x1a, x1b, NEXT, 4096, 6144, x2a, x2b, 12, 6, XB, BUF)         \
+    FXP_WBLOCK_X(W, x2a, x2b, NEXT, 8192, 10240, x3a, x3b, 14, 7, XB, BUF)
+#define FXP_WKSTEP_W(W, ADDR, NEXT, WN, WB0, WB1)                                 \
+    FXP_WBLOCK_W(W, x3a, x3b, ADDR, 12288, 14336, x0a, x0b, 0, WN[0][0], WB0, 0)    \
+    FXP_WBLOCK_W(W, x0a, x0b, ADDR, 16384, 18432, x1a, x1b, 2, WN[0][1], WB0, 1024) \
+    FXP_WBLOCK_W(W, x1a, x1b, ADDR, 20480, 22528, x2a, x2b, 4, WN[0][2], WB0, 2048) \
+    FXP_WBLOCK_W(W, x2a, x2b, ADDR, 24576, 26624, x3a, x3b, 6, WN[0][3], WB0, 3072) \
+    FXP_WBLOCK_W(W, x3a, x3b, ADDR, 28672, 30720, x0a, x0b, 8, WN[1][0], WB1, 0)    \
+    FXP_WBLOCK_W(W, x0a, x0b, NEXT, 0, 2048, x1a, x1b, 10, WN[1][1], WB1, 1024)     \
+    FXP_WBLOCK_W(W, x1a, x1b, NEXT, 4096, 6144, x2a, x2b, 12, WN[1][2], WB1, 2048)  \
+    FXP_WBLOCK_W(W, x2a, x2b, NEXT, 8192, 10240, x3a, x3b, 14, WN[1][3], WB1, 3072)
+#define FXP_WKSTEP_N(W, ADDR, NEXT)                                               \
+    FXP_WBLOCK_N(W, x3a, x3b, ADDR, 12288, 14336, x0a, x0b, 0)                    \
+    FXP_WBLOCK_N(W, x0a, x0b, ADDR, 16384, 18432, x1a, x1b, 2)                    \
+    FXP_WBLOCK_N(W, x1a, x1b, ADDR, 20480, 22528, x2a, x2b, 4)                    \
+    FXP_WBLOCK_N(W, x2a, x2b, ADDR, 24576, 26624, x3a, x3b, 6)                    \
+    FXP_WBLOCK_N(W, x3a, x3b, ADDR, 28672, 30720, x0a, x0b, 8)                    \
+    FXP_WBLOCK_N(W, x0a, x0b, NEXT, 0, 2048, x1a, x1b, 10)                        \
+    FXP_WBLOCK_N(W, x1a, x1b, NEXT, 4096, 6144, x2a, x2b, 12)                     \
+    FXP_WBLOCK_N(W, x2a, x2b, NEXT, 8192, 10240, x3a, x3b, 14)
+
+    // ring of four stages of weights (two k-steps of four tiles each); W(s) lives in set s % 4
+    u32x4 w[4][2][kWdRn];
+    // prologue: token rows and weights of stages 0..2
+#pragma unroll
+    for (int st = 0; st < 3; ++st) {
+        const char *xb = xptr(st);
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            asm volatile("s_mov_b32 m0, %[ld]\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %[xo], %[xb]\n"
+                         : : [ld] "s"(lds_dma + st * kWdStageBytes + i * 1024), [xo] "v"(xoff[i]), [xb] "s"(xb) : "memory");
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int r = 0; r < kWdRn; ++r)       // (assembly, like every load of this kernel: the compiler must not count it)
+                asm volatile("global_load_dwordx4 %[wd], %[wo], %[wb]" : [wd] "=&v"(w[st][h][r])
+                             : [wo] "v"(wlane), [wb] "s"(wptr(2 * st + h) + r * 1024) : "memory");
+    }
+    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+    if constexpr (PROBE != 0) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int r = 0; r < kWdRn; ++r) w[3][h][r] = w[1][h][r];
+    }
+    asm volatile("ds_read_b128 %[p0], %[addr]\n"
+                 "ds_read_b128 %[p1], %[addr] offset:2048\n"
+                 "ds_read_b128 %[p2], %[addr] offset:4096\n"
+                 "ds_read_b128 %[p3], %[addr] offset:6144\n"
+                 "ds_read_b128 %[p4], %[addr] offset:8192\n"
+                 "ds_read_b128 %[p5], %[addr] offset:10240\n"
+                 : [p0] "=&v"(x0a), [p1] "=&v"(x0b), [p2] "=&v"(x1a), [p3] "=&v"(x1b), [p4] "=&v"(x2a), [p5] "=&v"(x2b)
+                 : [addr] "v"(lds_h0) : "memory");
+
+    // Stage s: multiply X(s) (buffer s % 4) by W(s); meanwhile ask for X(s+3) -> buffer (s+3) % 4 and W(s+3) -> set
+    // (s+3) % 4 (both last used in stage s-1, behind the barrier that ended it).  The barrier at the end of the stage
+    // publishes X(s+2) for the first operand reads of stage s+2, which the last blocks of stage s+1 issue, and W(s+1)
+    // must have landed: the vector-memory counter is in order, so at that point W(s+2) (asked for a stage ago, behind
+    // X(s+2)) and this stage's own sixteen loads may still be in flight: 24.
+#define FXP_WSTAGE(S, KT0) {                                                                                 \
+    const char *xb = xptr((KT0) + (S) + 3), *wb0 = wptr(2 * ((KT0) + (S) + 3)), *wb1 = wptr(2 * ((KT0) + (S) + 3) + 1); \
+    if constexpr (PROBE == 0) {                                                                              \
+        FXP_WKSTEP_X(w[(S) % 4][0], lds_h0 + ((S) % 4) * kWdStageBytes, lds_h1 + ((S) % 4) * kWdStageBytes, xb, ((S) + 3) % 4) \
+        FXP_WKSTEP_W(w[(S) % 4][1], lds_h1 + ((S) % 4) * kWdStageBytes, lds_h0 + (((S) + 1) % 4) * kWdStageBytes, \
+                     w[((S) + 3) % 4], wb0, wb1)                                                            \
+        asm volatile("s_waitcnt vmcnt(24)\n\ts_barrier" ::: "memory");                                       \
+    } else {                                                                                                 \
+        FXP_WKSTEP_N(w[(S) % 4][0], lds_h0 + ((S) % 4) * kWdStageBytes, lds_h1 + ((S) % 4) * kWdStageBytes) \
+        FXP_WKSTEP_N(w[(S) % 4][1], lds_h1 + ((S) % 4) * kWdStageBytes, lds_h0 + (((S) + 1) % 4) * kWdStageBytes) \
+        asm volatile("s_barrier" ::: "memory");                                                              \
+    } }
+    for (int kt = 0; kt < KT; kt += 4) {
+        FXP_WSTAGE(0, kt)
+        FXP_WSTAGE(1, kt)
+        FXP_WSTAGE(2, kt)
+        FXP_WSTAGE(3, kt)
+    }
+    // loads past the end (clamped, never used) must have landed before their registers or LDS are given up
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" : "+v"(x0a), "+v"(x0b), "+v"(x1a), "+v"(x1b), "+v"(x2a), "+v"(x2b) : : "memory");
+#undef FXP_WSTAGE
+#undef FXP_WKSTEP_X
+#undef FXP_WKSTEP_W
+#undef FXP_WKSTEP_N
+#undef FXP_WBLOCK_X
+#undef FXP_WBLOCK_W
+#undef FXP_WBLOCK_N
+#undef FXP_WINS
+#undef FXP_WTEXT
+#undef FXP_ACC8
+
+    // ---- epilogue (as above; lane holds 4 consecutive n of token row m0 + mt*16 + col)
+#pragma unroll
+    for (int mt = 0; mt < kWdRm; ++mt) {
+        const int m = m0 + mt * 16 + col;
+        if (m >= a.M) continue;
+        if constexpr (EPI == kEpiSwiglu) {
+#pragma unroll
+            for (int r = 0; r < kWdRn; r += 2) {
+                if (nt0 + r >= a.NT) continue;
+                const int f = ((nt0 + r) / 2) * 16 + 4 * c;
+                float y[4];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const float g = acc[r][mt][v];
+                    y[v] = g / (1.f + __expf(-g)) * acc[r + 1][mt][v];
+                }
+                *reinterpret_cast<u32x2 *>(a.C + (int64_t)m * a.ldc + f) = u32x2{pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3])};
+            }
+        } else {
+#pragma unroll
+            for (int r = 0; r < kWdRn; ++r) {
+                if (nt0 + r >= a.NT) continue;
+                const int n = (nt0 + r) * 16 + 4 * c;
+                float y[4] = {acc[r][mt][0], acc[r][mt][1], acc[r][mt][2], acc[r][mt][3]};
+                if (a.bias) {
+                    const u32x2 bv = *reinterpret_cast<const u32x2 *>(a.bias + n);
+                    y[0] += bf16_lo(bv.x); y[1] += bf16_hi(bv.x); y[2] += bf16_lo(bv.y); y[3] += bf16_hi(bv.y);
+                }
+                if constexpr (EPI == kEpiRelu) {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) y[v] = fmaxf(y[v], 0.f);
+                }
+                if constexpr (EPI == kEpiResidual) {
+                    const u32x2 rv = *reinterpret_cast<const u32x2 *>(a.R + (int64_t)m * a.ldc + n);
+                    y[0] += bf16_lo(rv.x); y[1] += bf16_hi(rv.x); y[2] += bf16_lo(rv.y); y[3] += bf16_hi(rv.y);
+                }
+                *reinterpret_cast<u32x2 *>(a.C + (int64_t)m * a.ldc + n) = u32x2{pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3])};
+            }
+        }
+    }
+}
+
+// the wide tile takes a launch when it is matrix-core bound (sixteen or more rows of 128-row tiles) and the shape fits it
+static bool wide_tile_fits(const TiledArgs &a)
+{
+    static const int off = tuning_int("FXP_NO_WIDE_TILE", 0);
+    return !off && a.epilogue != kEpiPartial && a.M >= 16 * kTgBM && a.K % 256 == 0 && a.NT % kWdRn == 0 &&
+           (int64_t)a.M * a.ldx * 2 < (int64_t(1) << 32);
+}
+
+template <int EPI, int PROBE>
+static hipError_t launch_wide_probe(const TiledArgs &a, hipStream_t stream)
+{
+    static bool lds_set = false;       // per kernel instantiation: allow 128 KiB of dynamic LDS
+    if (!lds_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_wide_kernel<EPI, PROBE>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kWdLdsBytes);
+        if (e != hipSuccess) return e;
+        lds_set = true;
+    }
+    const int tiles_n = (a.NT * 16 + kWdBN - 1) / kWdBN, tiles_m = (a.M + kWdBM - 1) / kWdBM;
+    const int blocks = ((tiles_n + 3) / 4) * ((tiles_m + 7) / 8);
+    const dim3 grid((blocks + kXcds - 1) / kXcds * kXcds * 32);
+    hipLaunchKernelGGL((gemm_wide_kernel<EPI, PROBE>), grid, dim3(kTgThreads), kWdLdsBytes, stream, a);
+    return hipGetLastError();
+}
+
+template <int EPI>
+static hipError_t launch_wide(const TiledArgs &a, hipStream_t stream)
+{
+#ifdef FXP_TUNING
+    static const int probe = tuning_int("FXP_WIDE_PROBE", 0);
+    if (probe) return launch_wide_probe<EPI, 1>(a, stream);
+#endif
+    return launch_wide_probe<EPI, 0>(a, stream);
+}
+
 hipError_t launch_gemm_tiled(const TiledArgs &a, hipStream_t stream)
 {
+    if (wide_tile_fits(a)) {
+        switch (a.epilogue) {
+        case kEpiStore: return launch_wide<kEpiStore>(a, stream);
+        case kEpiResidual: return launch_wide<kEpiResidual>(a, stream);
+        case kEpiSwiglu: return launch_wide<kEpiSwiglu>(a, stream);
+        case kEpiRelu: return launch_wide<kEpiRelu>(a, stream);
+        default: break;
+        }
+    }
     const int tiles_n = (a.NT * 16 + kTgBN - 1) / kTgBN;
     const int tiles_m = (a.M + kTgBM - 1) / kTgBM;
     // the XCD-aware numbering covers whole 4 x 8 super-blocks, rounded up to a multiple of 8 of them

@@ -28,6 +28,8 @@ MID128 = synth.ModelShape(hidden=512, n_q_heads=4, n_kv_heads=4, head_dim=128, f
 GQA128 = synth.ModelShape(hidden=1024, n_q_heads=8, n_kv_heads=1, head_dim=128, ffn=1536)
 OPT_TINY = synth.TINY_OPT                                                                    # OPT-style layers (LayerNorm, biases, ReLU)
 OPT_GQA = synth.ModelShape(hidden=512, n_q_heads=8, n_kv_heads=2, head_dim=128, ffn=2048, arch=1)
+WIDE_TILE = synth.ModelShape(hidden=256, n_q_heads=4, n_kv_heads=4, head_dim=64, ffn=1024)      # every contraction length a multiple of 256: all four projections on the 256 x 256 tile
+OPT_WIDE_TILE = synth.ModelShape(hidden=512, n_q_heads=4, n_kv_heads=4, head_dim=128, ffn=1024, arch=1)
 OPT_WIDE = synth.ModelShape(hidden=256, n_q_heads=4, n_kv_heads=4, head_dim=64, ffn=16400, arch=1)    # unsplit first projection with ReLU in its epilogue
 WIDE_FFN = synth.ModelShape(hidden=256, n_q_heads=4, n_kv_heads=4, head_dim=64, ffn=8208)   # gate|up wide enough for the unsplit, SwiGLU-fused projection
 KV6 = synth.ModelShape(hidden=384, n_q_heads=6, n_kv_heads=6, head_dim=64, ffn=512)            # kv heads in groups of two per decode worker
@@ -151,6 +153,10 @@ PREFILL_CASES = [
     ("opt-prompts", OPT_TINY, 2, [0, 0, 0, 0], [37, 128, 32, 100]),
     ("opt-small", OPT_TINY, 2, [0, 0], [20, 45]),
     ("opt-chunked", OPT_GQA, 1, [16, 70, 33], [48, 10, 64]),
+    # 2048 token rows or more: the projections run on the 256 x 256 tile (accumulation registers, LDS-DMA token rows); ragged last tile
+    ("wide-tile-prompts", WIDE_TILE, 2, [0, 0, 0], [1500, 700, 100]),
+    ("wide-tile-two-trips", MID128, 1, [0, 33], [2000, 101]),
+    ("opt-wide-tile", OPT_WIDE_TILE, 1, [0, 0], [1300, 800]),
 ]
 
 
