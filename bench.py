@@ -114,7 +114,7 @@ def prefill_record(torch, wl, stage, steps, warmup, weights_note=""):
         "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step, "ms_per_step_wall_mean": wall_ms, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{wl.name}: {ms.hidden}-hidden {ms.n_q_heads}/{ms.n_kv_heads}x{ms.head_dim} heads, ffn {ms.ffn}, {L} layers, "
                                f"{B} prompts {wl.length_dist}, {T} tokens, kv block 16" + weights_note, "seed": wl.seed},
-        "roofline": {"kernel": "gemm_tiled_kernel", "bound": "mfma", "achieved": tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+        "roofline": {"kernel": "gemm_wide_kernel (the projections of a step above 2047 token rows; profile class gemm_tiled)", "bound": "mfma", "achieved": tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
                      "algorithmic_flops_per_layer": flops_layer, "avg_launch_us": kernels["gemm_tiled"]["avg_us"]},
         "attn_prefill": {"avg_launch_us": kernels["attn_prefill"]["avg_us"], "causal_flops_per_layer": attn_flops_layer,

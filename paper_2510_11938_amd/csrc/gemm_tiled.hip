@@ -370,16 +370,17 @@ __global__ __launch_bounds__(kTgThreads, 1) void gemm_wide_kernel(TiledArgs a)
     [b0] "+a"(acc[0][M + 1]), [b1] "+a"(acc[1][M + 1]), [b2] "+a"(acc[2][M + 1]), [b3] "+a"(acc[3][M + 1])
     // One block: the eight MFMAs of column tiles M, M+1 (operands in C0, C1, asked for three blocks earlier) with the two
     // LDS reads of the operand pair of the block three further on (NADDR + OFF0, OFF1 -> N0, N1) and one load of the
-    // stage (EXTRA: assembly text, outputs, inputs, clobbers) issued between its products, where they cost the matrix
-    // cores little or nothing.  LDS returns in order: when the block starts, the pairs of the next two blocks (four
+    // stage (XPRE: the M0 write of a DMA load, one product ahead of it; XASM: the load) issued between its products,
+    // where they cost the matrix cores little or nothing (other places inside the block measured the same).  LDS returns in order: when the block starts, the pairs of the next two blocks (four
     // reads) may still be on their way.
-#define FXP_WTEXT(OFF0, OFF1, XASM)                                                                  \
+#define FXP_WTEXT(OFF0, OFF1, XPRE, XASM)                                                            \
     "s_waitcnt lgkmcnt(4)\n"                                                                         \
     "v_mfma_f32_16x16x32_bf16 %[a0], %[w0], %[c0], %[a0]\n"                                           \
     "ds_read_b128 %[n0], %[naddr] offset:" #OFF0 "\n"                                                 \
     "v_mfma_f32_16x16x32_bf16 %[a1], %[w1], %[c0], %[a1]\n"                                           \
     "ds_read_b128 %[n1], %[naddr] offset:" #OFF1 "\n"                                                 \
     "v_mfma_f32_16x16x32_bf16 %[a2], %[w2], %[c0], %[a2]\n"                                           \
+    XPRE                                                                                             \
     "v_mfma_f32_16x16x32_bf16 %[a3], %[w3], %[c0], %[a3]\n"                                           \
     XASM                                                                                             \
     "v_mfma_f32_16x16x32_bf16 %[b0], %[w0], %[c1], %[b0]\n"                                           \
@@ -390,17 +391,17 @@ __global__ __launch_bounds__(kTgThreads, 1) void gemm_wide_kernel(TiledArgs a)
     [naddr] "v"(NADDR), [w0] "v"(W[0]), [w1] "v"(W[1]), [w2] "v"(W[2]), [w3] "v"(W[3]), [c0] "v"(C0), [c1] "v"(C1)
     // block without a load
 #define FXP_WBLOCK_N(W, N0, N1, NADDR, OFF0, OFF1, C0, C1, M)                                        \
-    asm volatile(FXP_WTEXT(OFF0, OFF1, "")                                                           \
+    asm volatile(FXP_WTEXT(OFF0, OFF1, "", "")                                                           \
                  : [n0] "=&v"(N0), [n1] "=&v"(N1), FXP_ACC8(M) : FXP_WINS(W, NADDR, C0, C1) : "memory");
     // block that carries token-row DMA instruction I of the stage (M0 = LDS address of lane 0's 16 bytes)
 #define FXP_WBLOCK_X(W, N0, N1, NADDR, OFF0, OFF1, C0, C1, M, I, XB, BUF)                            \
-    asm volatile(FXP_WTEXT(OFF0, OFF1, "s_mov_b32 m0, %[ld]\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %[xo], %[xb]\n") \
+    asm volatile(FXP_WTEXT(OFF0, OFF1, "s_mov_b32 m0, %[ld]\n", "global_load_lds_dwordx4 %[xo], %[xb]\n") \
                  : [n0] "=&v"(N0), [n1] "=&v"(N1), FXP_ACC8(M)                                        \
                  : FXP_WINS(W, NADDR, C0, C1), [ld] "s"(lds_dma + (BUF) * kWdStageBytes + (I) * 1024), [xo] "v"(xoff[I]), [xb] "s"(XB) \
                  : "memory");
     // block that carries one weight load
 #define FXP_WBLOCK_W(W, N0, N1, NADDR, OFF0, OFF1, C0, C1, M, WD, WB, WOFF)                          \
-    asm volatile(FXP_WTEXT(OFF0, OFF1, "global_load_dwordx4 %[wd], %[wo], %[wb] offset:" #WOFF "\n")  \
+    asm volatile(FXP_WTEXT(OFF0, OFF1, "", "global_load_dwordx4 %[wd], %[wo], %[wb] offset:" #WOFF "\n")  \
                  : [n0] "=&v"(N0), [n1] "=&v"(N1), FXP_ACC8(M), [wd] "=&v"(WD)                        \
                  : FXP_WINS(W, NADDR, C0, C1), [wo] "v"(wlane), [wb] "s"(WB) : "memory");
     u32x4 x0a, x0b, x1a, x1b, x2a, x2b, x3a, x3b;          // four operand pairs: block j of a k-step multiplies pair j % 4
