@@ -475,7 +475,7 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
         if (T > kSkinnyWideTokens) {
             // 65..128 token rows: one 128-row tile of the tiled kernel covers the batch; split-K for parallelism
             fxp::TiledArgs t;
-            t.W = (const uint16_t *)wbase; t.X = X; t.R = nullptr; t.C = nullptr; t.P = w.P; t.bias = nullptr;
+            t.W = (const uint16_t *)wbase; t.X = X; t.R = nullptr; t.C = nullptr; t.P = w.P; t.bias = nullptr; t.blk_m = 0;
             t.M = T; t.K = K; t.KS = k_steps(K); t.NT = N / 16; t.ldx = ldx; t.ldc = 0; t.epilogue = fxp::kEpiPartial;
             t.S = skinny_cfg(N, K, T).S;
             *S_out = t.S;
@@ -503,7 +503,7 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
     auto project_tiled = [&](const char *wbase, const uint16_t *X, int N, int K, int ldx, uint16_t *C, int ldc,
                              const uint16_t *R, int epi, const uint16_t *bias = nullptr, int kernel_class = kKcTiled) -> hipError_t {
         fxp::TiledArgs a;
-        a.W = (const uint16_t *)wbase; a.X = X; a.R = R; a.C = C; a.P = nullptr; a.S = 1; a.bias = bias;
+        a.W = (const uint16_t *)wbase; a.X = X; a.R = R; a.C = C; a.P = nullptr; a.S = 1; a.bias = bias; a.blk_m = 0;
         a.M = T; a.K = K; a.KS = k_steps(K); a.NT = N / 16; a.ldx = ldx; a.ldc = ldc; a.epilogue = epi;
         KernelTimer kt(kernel_class, st);
         return fxp::launch_gemm_tiled(a, st);

@@ -299,8 +299,9 @@ __global__ __launch_bounds__(kTgThreads, 2) void gemm_tiled_kernel(TiledArgs a)
 //     Measured on the way, 7B gate|up projection at 15,928 rows: loads as compiler statements between the blocks
 //     and reads one block ahead 1.33 PFLOP/s (the 256 x 128 tile: 1.30); reads three blocks ahead between the
 //     products 1.41; loads inside the blocks 1.50; the same loop without any load 1.70.
-// Requirements (else the kernel above is used): at least 2048 token rows, K a multiple of 256, whole 64-row wave
-// tiles, token-row byte offsets below 4 GiB.
+// Requirements (else the kernel above is used): at least 1024 token rows, K a multiple of 256, whole 64-row wave
+// tiles, token-row byte offsets below 4 GiB; and the launcher's estimate that this tile is the faster one for the
+// launch's tile counts (wide_tile_fits).
 constexpr int kWdBM = 256, kWdBN = 256, kWdRn = 4, kWdRm = 16, kWdBufs = 4;
 constexpr int kWdStageBytes = kWdBM * 128;                 // 256 rows x 64 k of bf16
 constexpr int kWdLdsBytes = kWdBufs * kWdStageBytes;       // 128 KiB
@@ -315,18 +316,19 @@ __global__ __launch_bounds__(kTgThreads, 1) void gemm_wide_kernel(TiledArgs a)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 15, c = lane >> 4;
 
-    // ---- tile of this workgroup: the 32 workgroups of one XCD (one per CU) form a 4 x 8 block of tiles
+    // ---- tile of this workgroup: the 32 workgroups of one XCD (one per CU) form a super-block of (32 / blk_m) x blk_m
+    // tiles that share weight and token rows in that XCD's L2; the launcher picks the shape that wastes the fewest slots
     const int tiles_n = (a.NT * 16 + kWdBN - 1) / kWdBN, tiles_m = (a.M + kWdBM - 1) / kWdBM;
     int tile_m, tile_n;
     {
-        constexpr int kBlkN = 4, kBlkM = 8;
-        const int blocks_n = (tiles_n + kBlkN - 1) / kBlkN;
+        const int blk_m = a.blk_m, blk_n = 32 / blk_m;
+        const int blocks_n = (tiles_n + blk_n - 1) / blk_n;
         const int id = blockIdx.x;
         const int xcd = id % kXcds, seq = id / kXcds;
-        const int super = seq / (kBlkN * kBlkM), within = seq % (kBlkN * kBlkM);
+        const int super = seq / 32, within = seq % 32;
         const int sb = super * kXcds + xcd;
-        tile_n = (sb % blocks_n) * kBlkN + within % kBlkN;
-        tile_m = (sb / blocks_n) * kBlkM + within / kBlkN;
+        tile_n = (sb % blocks_n) * blk_n + within % blk_n;
+        tile_m = (sb / blocks_n) * blk_m + within / blk_n;
     }
     if (tile_n >= tiles_n || tile_m >= tiles_m) return;
     const int m0 = tile_m * kWdBM;
@@ -546,16 +548,30 @@ __global__ __launch_bounds__(kTgThreads, 1) void gemm_wide_kernel(TiledArgs a)
     }
 }
 
-// the wide tile takes a launch when it is matrix-core bound (sixteen or more rows of 128-row tiles) and the shape fits it
+// Which tile takes a launch.  The wide tile needs a shape that fits it; then the two are compared by a model of their
+// running times in units of one 256 x 256 x K tile at the wide kernel's rate, fitted to measurements at 2048 .. 15,928
+// rows of the 7B shape (it picks the faster kernel in every one of them):
+//   wide: one workgroup per CU, so rounds = ceil(tiles / CUs), one unit each;
+//   256 x 128: two workgroups per CU take 1.11 units per double round; a last round with at most one workgroup per CU
+//         runs each of them alone in 0.68.
 static bool wide_tile_fits(const TiledArgs &a)
 {
-    static const int off = tuning_int("FXP_NO_WIDE_TILE", 0);
-    return !off && a.epilogue != kEpiPartial && a.M >= 16 * kTgBM && a.K % 256 == 0 && a.NT % kWdRn == 0 &&
-           (int64_t)a.M * a.ldx * 2 < (int64_t(1) << 32);
+    static const int off = tuning_int("FXP_NO_WIDE_TILE", 0), force_rows = tuning_int("FXP_WIDE_MIN_ROWS", 0);
+    if (off || a.epilogue == kEpiPartial || a.M < 4 * kWdBM || a.K % 256 != 0 || a.NT % kWdRn != 0 ||
+        (int64_t)a.M * a.ldx * 2 >= (int64_t(1) << 32))
+        return false;
+    if (force_rows > 0) return a.M >= force_rows;
+    const int cus = device_cus();
+    const int64_t tiles_n = (a.NT * 16 + kWdBN - 1) / kWdBN;
+    const int64_t wide_wgs = tiles_n * ((a.M + kWdBM - 1) / kWdBM), narrow_wgs = tiles_n * ((a.M + kTgBM - 1) / kTgBM);
+    const double t_wide = (double)((wide_wgs + cus - 1) / cus);
+    const int64_t pairs = narrow_wgs / (2 * cus), rest = narrow_wgs - pairs * 2 * cus;
+    const double t_narrow = 1.11 * (double)pairs + (rest == 0 ? 0.0 : rest <= cus ? 0.68 : 1.11);
+    return t_wide < t_narrow;
 }
 
 template <int EPI, int PROBE>
-static hipError_t launch_wide_probe(const TiledArgs &a, hipStream_t stream)
+static hipError_t launch_wide_probe(const TiledArgs &a_in, hipStream_t stream)
 {
     static bool lds_set = false;       // per kernel instantiation: allow 128 KiB of dynamic LDS
     if (!lds_set) {
@@ -564,8 +580,13 @@ static hipError_t launch_wide_probe(const TiledArgs &a, hipStream_t stream)
         if (e != hipSuccess) return e;
         lds_set = true;
     }
-    const int tiles_n = (a.NT * 16 + kWdBN - 1) / kWdBN, tiles_m = (a.M + kWdBM - 1) / kWdBM;
-    const int blocks = ((tiles_n + 3) / 4) * ((tiles_m + 7) / 8);
+    const int tiles_n = (a_in.NT * 16 + kWdBN - 1) / kWdBN, tiles_m = (a_in.M + kWdBM - 1) / kWdBM;
+    TiledArgs a = a_in;
+    int blocks = 0;
+    for (int bm = 8; bm >= 1; bm /= 2) {           // super-block shape with the fewest padded slots (ties: the squarer one)
+        const int bn = 32 / bm, padded = ((tiles_n + bn - 1) / bn) * ((tiles_m + bm - 1) / bm);
+        if (blocks == 0 || padded < blocks) { blocks = padded; a.blk_m = bm; }
+    }
     const dim3 grid((blocks + kXcds - 1) / kXcds * kXcds * 32);
     hipLaunchKernelGGL((gemm_wide_kernel<EPI, PROBE>), grid, dim3(kTgThreads), kWdLdsBytes, stream, a);
     return hipGetLastError();

@@ -97,6 +97,7 @@ struct TiledArgs {
     const uint16_t *bias;  // optional bias [NT*16] bf16, added before the residual / activation (not for kEpiPartial, kEpiSwiglu)
     int M, K, KS, NT, ldx, ldc, epilogue;
     int S;                 // kEpiPartial: split-K factor (grid.y)
+    int blk_m;             // set by the launcher (wide tile): token tiles per XCD super-block, 8, 4, 2 or 1 (weight tiles: 32 / blk_m)
 };
 hipError_t launch_gemm_tiled(const TiledArgs &a, hipStream_t stream);
 

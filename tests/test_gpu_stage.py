@@ -157,6 +157,8 @@ PREFILL_CASES = [
     ("wide-tile-prompts", WIDE_TILE, 2, [0, 0, 0], [1500, 700, 100]),
     ("wide-tile-two-trips", MID128, 1, [0, 33], [2000, 101]),
     ("opt-wide-tile", OPT_WIDE_TILE, 1, [0, 0], [1300, 800]),
+    ("wide-tile-ten-row-tiles", MID128, 1, [0], [2500]),              # a tile count that picks another XCD super-block shape
+    ("wide-tile-1100", WIDE_TILE, 1, [0, 0], [1000, 100]),            # between 1024 and 2048 rows: the launcher's estimate decides per projection
 ]
 
 
