@@ -573,12 +573,15 @@ static bool wide_tile_fits(const TiledArgs &a)
 template <int EPI, int PROBE>
 static hipError_t launch_wide_probe(const TiledArgs &a_in, hipStream_t stream)
 {
-    static bool lds_set = false;       // per kernel instantiation: allow 128 KiB of dynamic LDS
-    if (!lds_set) {
+    // allow 128 KiB of dynamic LDS: once per kernel instantiation and device
+    static bool lds_set[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    if (!lds_set[dev]) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_wide_kernel<EPI, PROBE>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kWdLdsBytes);
         if (e != hipSuccess) return e;
-        lds_set = true;
+        lds_set[dev] = true;
     }
     const int tiles_n = (a_in.NT * 16 + kWdBN - 1) / kWdBN, tiles_m = (a_in.M + kWdBM - 1) / kWdBM;
     TiledArgs a = a_in;

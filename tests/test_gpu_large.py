@@ -160,6 +160,36 @@ def test_7b_shape_prefill_chunk_of_514_tokens_sampled_against_oracle():
         check_wide_output(got[rows], want, ms.hidden, 1, f"prompt {i} ({lens[i]} tokens):", kind="prefill")
 
 
+def test_13b_shape_prefill_of_2100_tokens_sampled_against_oracle():
+    # hidden 5120, 40 x 128 heads, ffn 13824, one layer; a 2000-token prompt and a 100-token prompt in one call: every projection
+    # on the 256 x 256 tile at other contraction lengths and tile counts than the 7B shape (20 / 60 / 108 weight tiles, nine
+    # rows of token tiles with a ragged last one).  The oracle recomputes the short prompt (the last rows of the call) and
+    # the first 64 tokens of the long one, which causal attention makes independent of the rest.
+    ms = synth.WORKLOADS["C4"].shape
+    seed, lens = 23, np.array([2000, 100], dtype=np.int32)
+    T = int(lens.sum())
+    table, nblk = synth.block_table(lens, 16, seed)
+    w = make_weights(ms, seed, 1, want_f32=False)
+    hidden_bits = synth.hidden_states(T, ms.hidden, seed)
+    stage = make_stage(ms, w, 0, 1)
+    pool = torch.zeros((1, nblk, 2, ms.n_kv_heads, 16, ms.head_dim), dtype=torch.int16, device="cuda")
+    cache = binding.KVCache(pool, 0, 1, dev_i32(table))
+    cu = synth.cu_seqlens(lens)
+    y = stage.forward(cache, dev_i32(cu), dev_i32(np.zeros(2)), dev_bf16(hidden_bits), int(lens.max()), min_q_len=int(lens.min()))
+    torch.cuda.synchronize()
+    got = host_f64(y)
+    assert np.isfinite(got).all()
+    osh = oracle_shape(ms)
+    wf = [{k: synth.bf16_bits_to_f32(v) for k, v in lw.items()} for lw in w.bits]
+    for i, n in ((1, 100), (0, 64)):
+        nb = (n + 15) // 16
+        sub_pool = np.zeros((1, nb, 2, ms.n_kv_heads, 16, ms.head_dim), dtype=np.float32)
+        rows = slice(int(cu[i]), int(cu[i]) + n)
+        want = oracle.stage_forward(osh, wf, sub_pool, [0, n], [0], np.arange(nb, dtype=np.int32)[None, :],
+                                    synth.bf16_bits_to_f32(hidden_bits[rows]).astype(np.float64))
+        check_wide_output(got[rows], want, ms.hidden, 1, f"13B prompt {i}, first {n} tokens:", kind="prefill")
+
+
 def test_full_size_prefill_workload_full_depth_sampled_against_oracle():
     # the prefill workload of the benchmark at its full size and depth (16 prompts, 15,928 tokens, 7B shape, 4 layers):
     # 128-row attention tiles, tiled projections over 125 row tiles with a ragged last one.  Attention is causal and

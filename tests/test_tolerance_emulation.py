@@ -105,13 +105,14 @@ def test_bf16_storage_emulation_at_full_width_and_depth_gives_the_bar_of_the_gpu
 
 
 @pytest.mark.slow
-def test_bf16_storage_emulation_of_a_prompt_gives_the_bar_of_the_prefill_tests():
-    run = wt.EMULATED_PREFILL_RUNS["7B"]
+@pytest.mark.parametrize("name", list(wt.EMULATED_PREFILL_RUNS))
+def test_bf16_storage_emulation_of_a_prompt_gives_the_bar_of_the_prefill_tests(name):
+    run = wt.EMULATED_PREFILL_RUNS[name]
     ms, depth = run["shape"], len(run["l2"])
     res = wt.emulated_prefill_errors(ms, depth, run["tokens"], run["seed"])
     for k, r in enumerate(res):
         l2_rec, frac_rec = wt.EMULATED[("prefill", ms.hidden, k + 1)]
-        print(f"7B prompt after {k + 1} layers: row L2 {r['l2']:.3e} (recorded {l2_rec:.3e}, worst row {int(r['l2_rows'].argmax())})  "
+        print(f"{name} prompt after {k + 1} layers: row L2 {r['l2']:.3e} (recorded {l2_rec:.3e}, worst row {int(r['l2_rows'].argmax())})  "
               f"element-wise max {r['elem']:.3e}  fraction > 2e-2 {r['frac']:.2e} (recorded {frac_rec:.2e})")
         assert abs(r["l2"] - l2_rec) <= 0.02 * l2_rec
         assert abs(r["frac"] - frac_rec) <= 0.05 * frac_rec + 2e-4
@@ -119,6 +120,6 @@ def test_bf16_storage_emulation_of_a_prompt_gives_the_bar_of_the_prefill_tests()
         l2_bar, elem_bar, frac_bar = wt.wide_bar(ms.hidden, k + 1, r["n"], "prefill")
         assert r["l2"] <= l2_bar / 1.2 and r["elem"] <= elem_bar / 1.2 and r["frac"] <= frac_bar
         # the worst rows are early ones and the error falls off behind them, so 48 rows stand for a prompt of any length
-        assert r["l2_rows"].argmax() < 32 and r["l2_rows"][40:].max() < r["l2"]
+        assert r["l2_rows"].argmax() < 40 and r["l2_rows"][40:].max() < r["l2"]
         # larger than a decode row's behind a long context at the same depth
         assert r["l2"] > wt.EMULATED[("decode", ms.hidden, k + 1)][0]

@@ -64,6 +64,7 @@ EMULATED_PREFILL_RUNS = {
     "7B": {"shape": synth.LLAMA2_7B, "seed": 2, "tokens": 48,
            "l2": [6.47e-3, 9.11e-3, 1.122e-2, 1.356e-2],
            "frac": [3.0e-4, 1.08e-2, 3.83e-2, 7.35e-2]},
+    "13B": {"shape": synth.LLAMA2_13B, "seed": 3, "tokens": 48, "l2": [8.10e-3], "frac": [3.56e-3]},
 }
 for _kind, _runs in (("decode", EMULATED_RUNS), ("prefill", EMULATED_PREFILL_RUNS)):
     for _run in _runs.values():
