@@ -236,6 +236,8 @@ __global__ __launch_bounds__(kRopeTableThreads) void rope_table_kernel(RopeTable
         s_pos = a.ctx_lens[lo] + (t - a.cu_seqlens_q[lo]);
         a.tok_seq[t] = s_seq;
         a.tok_pos[t] = s_pos;
+        a.tok_row[t] = a.block_table[(int64_t)lo * a.max_blocks_per_seq + s_pos / kBlockTokens] * 2 * a.n_kv_heads * kBlockTokens +
+                       s_pos % kBlockTokens;
     }
     __syncthreads();
     if ((int)threadIdx.x < half) {
@@ -291,12 +293,11 @@ __global__ __launch_bounds__(kRowThreads) void qkv_rope_kvwrite_kernel(RopeArgs 
     const int c = blockIdx.y * kRowThreads + threadIdx.x;
     if (c >= n_rot + n_v) return;
     const int64_t src_row = (int64_t)t * Nall;
-    const int seq = a.tok_seq[t], pos = a.tok_pos[t];
-    const int32_t phys = a.block_table[(int64_t)seq * a.max_blocks_per_seq + pos / kBlockTokens];
-    const int slot = pos % kBlockTokens;
-    // cache row of (kv, head): ((((layer*num_blocks + phys)*2 + kv)*Hkv + head)*16 + slot)*D
-    const int64_t blk = ((int64_t)a.layer_local * a.num_blocks + phys) * 2;
+    // cache row of (kv, head) for this token: one layer of the pool is [block][K,V][head][16 slots] rows of D values,
+    // and the rope table has the token's row for K of head 0
+    const int64_t row0 = (int64_t)a.layer_local * a.num_blocks * 2 * a.n_kv_heads * kBlockTokens + a.tok_row[t];
 
+    // col: column of the projection output; q and k heads are in the packed tile order (rotary_col), and so is the bias
     auto fetch8 = [&](int64_t col, float (&f)[8]) {
         if constexpr (FROM_PARTIAL) {
             partial8(a.P, a.S, (int64_t)a.T * Nall, src_row + col, f);
@@ -314,8 +315,8 @@ __global__ __launch_bounds__(kRowThreads) void qkv_rope_kvwrite_kernel(RopeArgs 
     if (c < n_rot) {
         const int head = c / chunks_per_head, d0 = (c % chunks_per_head) * 8;
         float lo[8], hi[8], rl[8], rh[8];
-        fetch8((int64_t)head * D + d0, lo);
-        fetch8((int64_t)head * D + d0 + half, hi);
+        fetch8(rotary_col(head * D, d0, D), lo);
+        fetch8(rotary_col(head * D, d0 + half, D), hi);
         const float *cs = a.cs + (int64_t)t * half + d0, *sn = a.sn + (int64_t)t * half + d0;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
@@ -325,7 +326,7 @@ __global__ __launch_bounds__(kRowThreads) void qkv_rope_kvwrite_kernel(RopeArgs 
         }
         uint16_t *dst;
         if (head < a.n_q_heads) dst = a.q_out + (int64_t)t * Nq + (int64_t)head * D;
-        else dst = a.pool + (((blk + 0) * a.n_kv_heads + (head - a.n_q_heads)) * kBlockTokens + slot) * D;
+        else dst = a.pool + (row0 + (int64_t)(head - a.n_q_heads) * kBlockTokens) * D;
         st16(dst + d0, pack8(rl));
         st16(dst + d0 + half, pack8(rh));
     } else {
@@ -333,7 +334,7 @@ __global__ __launch_bounds__(kRowThreads) void qkv_rope_kvwrite_kernel(RopeArgs 
         const int head = (cv * 8) / D, d0 = (cv * 8) % D;
         float f[8];
         fetch8((int64_t)Nq + Nkv + cv * 8, f);
-        st16(a.pool + (((blk + 1) * a.n_kv_heads + head) * kBlockTokens + slot) * D + d0, pack8(f));
+        st16(a.pool + (row0 + (int64_t)(a.n_kv_heads + head) * kBlockTokens) * D + d0, pack8(f));
     }
 }
 

@@ -213,7 +213,7 @@ namespace {
 struct Workspace {
     uint16_t *x[2], *n, *q, *qkv, *o, *h, *a;
     float *P, *part_acc, *part_ml, *pf_acc, *pf_ml, *dbg_ml, *rope_cs, *rope_sn;
-    int32_t *tok_seq, *tok_pos;
+    int32_t *tok_seq, *tok_pos, *tok_row;
     int32_t *blk_prefix;    // decode attention: cache blocks (per head) before each sequence, [B + 1]
     int n_workers;
     size_t bytes;
@@ -268,6 +268,7 @@ Workspace carve(const fxp_stage_desc &d, int T, int B, int max_blocks, char *bas
     w.rope_sn = (float *)take(t * (d.head_dim / 2) * 4);
     w.tok_seq = (int32_t *)take(t * 4);
     w.tok_pos = (int32_t *)take(t * 4);
+    w.tok_row = (int32_t *)take(t * 4);
     w.blk_prefix = (int32_t *)take(((size_t)B + 1) * 4);
     w.bytes = at;
     return w;
@@ -352,24 +353,27 @@ int fxp_stage_create(const fxp_stage_desc *desc, const fxp_layer_weights *layers
         char *base = (char *)weight_arena + rec.bytes * (size_t)l;
         hipError_t e;
         // q | k | v rows concatenated
-        if ((e = fxp::launch_weight_pack(w.wq, Nq, H, base + rec.wqkv, k_steps(H), 0, 1, st))) return hip_fail(e, "pack wq");
-        if ((e = fxp::launch_weight_pack(w.wk, Nkv, H, base + rec.wqkv, k_steps(H), Nq / 16, 1, st))) return hip_fail(e, "pack wk");
-        if ((e = fxp::launch_weight_pack(w.wv, Nkv, H, base + rec.wqkv, k_steps(H), (Nq + Nkv) / 16, 1, st))) return hip_fail(e, "pack wv");
-        if ((e = fxp::launch_weight_pack(w.wo, H, Nq, base + rec.wo, k_steps(Nq), 0, 1, st))) return hip_fail(e, "pack wo");
+        if ((e = fxp::launch_weight_pack(w.wq, Nq, H, base + rec.wqkv, k_steps(H), 0, 1, D / 32, st))) return hip_fail(e, "pack wq");
+        if ((e = fxp::launch_weight_pack(w.wk, Nkv, H, base + rec.wqkv, k_steps(H), Nq / 16, 1, D / 32, st))) return hip_fail(e, "pack wk");
+        if ((e = fxp::launch_weight_pack(w.wv, Nkv, H, base + rec.wqkv, k_steps(H), (Nq + Nkv) / 16, 1, 0, st))) return hip_fail(e, "pack wv");
+        if ((e = fxp::launch_weight_pack(w.wo, H, Nq, base + rec.wo, k_steps(Nq), 0, 1, 0, st))) return hip_fail(e, "pack wo");
         if (opt) {
-            if ((e = fxp::launch_weight_pack(w.w_up, F, H, base + rec.wgu, k_steps(H), 0, 1, st))) return hip_fail(e, "pack w_up");
+            if ((e = fxp::launch_weight_pack(w.w_up, F, H, base + rec.wgu, k_steps(H), 0, 1, 0, st))) return hip_fail(e, "pack w_up");
+            // the q and k biases follow the tile order of their matrices' rows
+            if ((e = fxp::launch_bias_pack(w.bq, Nq, base + rec.b_qkv, D / 32, st))) return hip_fail(e, "pack bq");
+            if ((e = fxp::launch_bias_pack(w.bk, Nkv, base + rec.b_qkv + (size_t)Nq * 2, D / 32, st))) return hip_fail(e, "pack bk");
             const struct { const void *src; size_t off, n; } vecs[] = {
-                {w.b_attn_norm, rec.b_attn, (size_t)H}, {w.b_ffn_norm, rec.b_ffn, (size_t)H}, {w.bq, rec.b_qkv, (size_t)Nq},
-                {w.bk, rec.b_qkv + (size_t)Nq * 2, (size_t)Nkv}, {w.bv, rec.b_qkv + (size_t)(Nq + Nkv) * 2, (size_t)Nkv},
+                {w.b_attn_norm, rec.b_attn, (size_t)H}, {w.b_ffn_norm, rec.b_ffn, (size_t)H},
+                {w.bv, rec.b_qkv + (size_t)(Nq + Nkv) * 2, (size_t)Nkv},
                 {w.bo, rec.b_o, (size_t)H}, {w.b_up, rec.b_up, (size_t)F}, {w.b_down, rec.b_down, (size_t)H}};
             for (const auto &v : vecs)
                 if ((e = hipMemcpyAsync(base + v.off, v.src, v.n * 2, hipMemcpyDeviceToDevice, st))) return hip_fail(e, "copy bias");
         } else {
             // gate and up rows interleaved in 16-row tiles
-            if ((e = fxp::launch_weight_pack(w.w_gate, F, H, base + rec.wgu, k_steps(H), 0, 2, st))) return hip_fail(e, "pack w_gate");
-            if ((e = fxp::launch_weight_pack(w.w_up, F, H, base + rec.wgu, k_steps(H), 1, 2, st))) return hip_fail(e, "pack w_up");
+            if ((e = fxp::launch_weight_pack(w.w_gate, F, H, base + rec.wgu, k_steps(H), 0, 2, 0, st))) return hip_fail(e, "pack w_gate");
+            if ((e = fxp::launch_weight_pack(w.w_up, F, H, base + rec.wgu, k_steps(H), 1, 2, 0, st))) return hip_fail(e, "pack w_up");
         }
-        if ((e = fxp::launch_weight_pack(w.w_down, H, F, base + rec.wd, k_steps(F), 0, 1, st))) return hip_fail(e, "pack w_down");
+        if ((e = fxp::launch_weight_pack(w.w_down, H, F, base + rec.wd, k_steps(F), 0, 1, 0, st))) return hip_fail(e, "pack w_down");
         if ((e = hipMemcpyAsync(base + rec.g_attn, w.g_attn, (size_t)H * 2, hipMemcpyDeviceToDevice, st))) return hip_fail(e, "copy g_attn");
         if ((e = hipMemcpyAsync(base + rec.g_ffn, w.g_ffn, (size_t)H * 2, hipMemcpyDeviceToDevice, st))) return hip_fail(e, "copy g_ffn");
     }
@@ -475,7 +479,7 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
         if (T > kSkinnyWideTokens) {
             // 65..128 token rows: one 128-row tile of the tiled kernel covers the batch; split-K for parallelism
             fxp::TiledArgs t;
-            t.W = (const uint16_t *)wbase; t.X = X; t.R = nullptr; t.C = nullptr; t.P = w.P; t.bias = nullptr; t.blk_m = 0;
+            t.W = (const uint16_t *)wbase; t.X = X; t.R = nullptr; t.C = nullptr; t.P = w.P; t.bias = nullptr; t.blk_m = 0; t.rope = fxp::RopeArgs{};
             t.M = T; t.K = K; t.KS = k_steps(K); t.NT = N / 16; t.ldx = ldx; t.ldc = 0; t.epilogue = fxp::kEpiPartial;
             t.S = skinny_cfg(N, K, T).S;
             *S_out = t.S;
@@ -503,7 +507,7 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
     auto project_tiled = [&](const char *wbase, const uint16_t *X, int N, int K, int ldx, uint16_t *C, int ldc,
                              const uint16_t *R, int epi, const uint16_t *bias = nullptr, int kernel_class = kKcTiled) -> hipError_t {
         fxp::TiledArgs a;
-        a.W = (const uint16_t *)wbase; a.X = X; a.R = R; a.C = C; a.P = nullptr; a.S = 1; a.bias = bias; a.blk_m = 0;
+        a.W = (const uint16_t *)wbase; a.X = X; a.R = R; a.C = C; a.P = nullptr; a.S = 1; a.bias = bias; a.blk_m = 0; a.rope = fxp::RopeArgs{};
         a.M = T; a.K = K; a.KS = k_steps(K); a.NT = N / 16; a.ldx = ldx; a.ldc = ldc; a.epilogue = epi;
         KernelTimer kt(kernel_class, st);
         return fxp::launch_gemm_tiled(a, st);
@@ -512,6 +516,7 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
     {   // token -> (sequence, position) and the rotation table: the same for every layer
         fxp::RopeTableArgs rt;
         rt.cu_seqlens_q = batch->cu_seqlens_q; rt.ctx_lens = batch->ctx_lens; rt.tok_seq = w.tok_seq; rt.tok_pos = w.tok_pos; rt.blk_prefix = w.blk_prefix;
+        rt.tok_row = w.tok_row; rt.block_table = batch->block_table; rt.max_blocks_per_seq = batch->max_blocks_per_seq; rt.n_kv_heads = d.n_kv_heads;
         rt.cs = w.rope_cs; rt.sn = w.rope_sn; rt.T = T; rt.num_seqs = B; rt.head_dim = D; rt.rope_base = d.rope_base;
         rt.identity = opt ? 1 : 0;
         // the attention norm of the stage's first layer goes with it
@@ -556,15 +561,29 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
         if (part_qkv) {
             if ((e = project_skinny(rec + stage->rec.wqkv, w.n, Nall, H, H, &S))) return hip_fail(e, "qkv projection");
             ra.P = w.P; ra.S = S; ra.bias = b_qkv;
-        } else {
-            if ((e = project_tiled(rec + stage->rec.wqkv, w.n, Nall, H, H, w.qkv, Nall, nullptr, fxp::kEpiStore, b_qkv))) return hip_fail(e, "qkv projection");
-            ra.qkv = w.qkv;
         }
         ra.q_out = w.q; ra.pool = (uint16_t *)pool->base;
-        ra.tok_seq = w.tok_seq; ra.tok_pos = w.tok_pos; ra.cs = w.rope_cs; ra.sn = w.rope_sn; ra.block_table = batch->block_table;
+        ra.tok_seq = w.tok_seq; ra.tok_pos = w.tok_pos; ra.tok_row = w.tok_row; ra.cs = w.rope_cs; ra.sn = w.rope_sn; ra.block_table = batch->block_table;
         ra.num_blocks = pool->num_blocks; ra.T = T; ra.max_blocks_per_seq = batch->max_blocks_per_seq;
         ra.layer_local = ll; ra.n_q_heads = d.n_q_heads; ra.n_kv_heads = d.n_kv_heads; ra.head_dim = D;
-        {
+        bool qkv_done = false;
+        if (!part_qkv) {
+            // unsplit: on the wide tile the projection rotates q and k and appends k, v to the cache in its own epilogue;
+            // otherwise it stores q|k|v as bf16 for the row kernel
+            fxp::TiledArgs ta;
+            ta.W = (const uint16_t *)(rec + stage->rec.wqkv); ta.X = w.n; ta.R = nullptr; ta.C = w.qkv; ta.P = nullptr; ta.S = 1; ta.bias = b_qkv;
+            ta.blk_m = 0; ta.M = T; ta.K = H; ta.KS = k_steps(H); ta.NT = Nall / 16; ta.ldx = H; ta.ldc = Nall; ta.epilogue = fxp::kEpiRope;
+            ta.rope = ra;
+            if (fxp::gemm_wide_applies(ta)) {
+                KernelTimer kt(kKcTiled, st);
+                if ((e = fxp::launch_gemm_tiled(ta, st))) return hip_fail(e, "qkv projection + rope + kv append");
+                qkv_done = true;
+            } else {
+                if ((e = project_tiled(rec + stage->rec.wqkv, w.n, Nall, H, H, w.qkv, Nall, nullptr, fxp::kEpiStore, b_qkv))) return hip_fail(e, "qkv projection");
+                ra.qkv = w.qkv;
+            }
+        }
+        if (!qkv_done) {
             KernelTimer kt(kKcRope, st);
             if ((e = fxp::launch_qkv_rope_kvwrite(ra, st))) return hip_fail(e, "rope + kv append");
         }

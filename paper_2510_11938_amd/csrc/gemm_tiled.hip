@@ -507,6 +507,74 @@ __global__ __launch_bounds__(kTgThreads, 1) void gemm_wide_kernel(TiledArgs a)
 #undef FXP_ACC8
 
     // ---- epilogue (as above; lane holds 4 consecutive n of token row m0 + mt*16 + col)
+    if constexpr (EPI == kEpiRope) {
+        // q|k|v projection: the rotary embedding and the cache append happen here.  The row tiles of a q or k head
+        // were packed with the halves of the head dimension alternating, so accumulator tiles (r, r+1) of this lane
+        // hold the rotary pair (d, d + D/2) of one token; the wave's four tiles lie inside one head and one of the q,
+        // k, v sections (sections and heads start at multiples of four tiles).
+        const RopeArgs &ra = a.rope;
+        const int D = ra.head_dim, tiles_per_head = D / 16, half = D / 2;
+        const int q_tiles = ra.n_q_heads * tiles_per_head, kv_tiles = ra.n_kv_heads * tiles_per_head;
+        const int sect = nt0 < q_tiles ? 0 : (nt0 < q_tiles + kv_tiles ? 1 : 2);            // q, k, v (wave-uniform)
+        const int nts = nt0 - (sect == 0 ? 0 : sect == 1 ? q_tiles : q_tiles + kv_tiles);   // tile inside the section
+        const int head = nts / tiles_per_head, j0 = nts % tiles_per_head;                  // j0: 0 or 4
+        const int64_t Nq = (int64_t)ra.n_q_heads * D;
+        // the cache row of each of this lane's tokens (all requests first, then the uses)
+        int32_t trow[kWdRm];
+        if (sect != 0) {
+#pragma unroll
+            for (int mt = 0; mt < kWdRm; ++mt) trow[mt] = ra.tok_row[min(m0 + mt * 16 + col, a.M - 1)];
+        }
+        if (nt0 < a.NT) {
+#pragma unroll
+            for (int mt = 0; mt < kWdRm; ++mt) {
+                const int m = m0 + mt * 16 + col;
+                if (m >= a.M) continue;
+                // destination of dim 0 of this head for token m
+                uint16_t *dst;
+                if (sect == 0) dst = ra.q_out + (int64_t)m * Nq + (int64_t)head * D;
+                else dst = ra.pool + ((int64_t)ra.layer_local * ra.num_blocks * 2 * ra.n_kv_heads * kBlockTokens + trow[mt] +
+                                      ((sect - 1) * ra.n_kv_heads + head) * kBlockTokens) * D;
+                auto rounded = [&](int r, float (&y)[4]) {          // the projection's values as bf16 (+ bias), as the unfused path stores them
+                    y[0] = acc[r][mt][0]; y[1] = acc[r][mt][1]; y[2] = acc[r][mt][2]; y[3] = acc[r][mt][3];
+                    if (a.bias) {
+                        const u32x2 bv = *reinterpret_cast<const u32x2 *>(a.bias + (nt0 + r) * 16 + 4 * c);
+                        y[0] += bf16_lo(bv.x); y[1] += bf16_hi(bv.x); y[2] += bf16_lo(bv.y); y[3] += bf16_hi(bv.y);
+                    }
+                    const uint32_t p0 = pack_bf16x2(y[0], y[1]), p1 = pack_bf16x2(y[2], y[3]);
+                    y[0] = bf16_lo(p0); y[1] = bf16_hi(p0); y[2] = bf16_lo(p1); y[3] = bf16_hi(p1);
+                };
+                if (sect == 2) {
+                    // v rows: natural order, no rotation
+#pragma unroll
+                    for (int r = 0; r < kWdRn; ++r) {
+                        float y[4];
+                        rounded(r, y);
+                        *reinterpret_cast<u32x2 *>(dst + (j0 + r) * 16 + 4 * c) = u32x2{pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3])};
+                    }
+                } else {
+#pragma unroll
+                    for (int r = 0; r < kWdRn; r += 2) {
+                        const int d = ((j0 + r) / 2) * 16 + 4 * c;          // dim of the first-half value; its partner is d + D/2
+                        float lo[4], hi[4];
+                        rounded(r, lo);
+                        rounded(r + 1, hi);
+                        const f32x4_t co = *reinterpret_cast<const f32x4_t *>(ra.cs + (int64_t)m * half + d);
+                        const f32x4_t si = *reinterpret_cast<const f32x4_t *>(ra.sn + (int64_t)m * half + d);
+                        float rl[4], rh[4];
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) {
+                            rl[v] = lo[v] * co[v] - hi[v] * si[v];
+                            rh[v] = hi[v] * co[v] + lo[v] * si[v];
+                        }
+                        *reinterpret_cast<u32x2 *>(dst + d) = u32x2{pack_bf16x2(rl[0], rl[1]), pack_bf16x2(rl[2], rl[3])};
+                        *reinterpret_cast<u32x2 *>(dst + d + half) = u32x2{pack_bf16x2(rh[0], rh[1]), pack_bf16x2(rh[2], rh[3])};
+                    }
+                }
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int mt = 0; mt < kWdRm; ++mt) {
         const int m = m0 + mt * 16 + col;
@@ -557,6 +625,9 @@ __global__ __launch_bounds__(kTgThreads, 1) void gemm_wide_kernel(TiledArgs a)
 static bool wide_tile_fits(const TiledArgs &a)
 {
     static const int off = tuning_int("FXP_NO_WIDE_TILE", 0), force_rows = tuning_int("FXP_WIDE_MIN_ROWS", 0);
+    static const int no_rope = tuning_int("FXP_NO_ROPE_EPILOGUE", 0);
+    if (a.epilogue == kEpiRope && (no_rope || a.rope.head_dim % 64 != 0 || (a.rope.n_q_heads + 2 * a.rope.n_kv_heads) * (a.rope.head_dim / 16) != a.NT))
+        return false;
     if (off || a.epilogue == kEpiPartial || a.M < 4 * kWdBM || a.K % 256 != 0 || a.NT % kWdRn != 0 ||
         (int64_t)a.M * a.ldx * 2 >= (int64_t(1) << 32))
         return false;
@@ -569,6 +640,8 @@ static bool wide_tile_fits(const TiledArgs &a)
     const double t_narrow = 1.11 * (double)pairs + (rest == 0 ? 0.0 : rest <= cus ? 0.68 : 1.11);
     return t_wide < t_narrow;
 }
+
+bool gemm_wide_applies(const TiledArgs &a) { return wide_tile_fits(a); }
 
 template <int EPI, int PROBE>
 static hipError_t launch_wide_probe(const TiledArgs &a_in, hipStream_t stream)
@@ -613,9 +686,11 @@ hipError_t launch_gemm_tiled(const TiledArgs &a, hipStream_t stream)
         case kEpiResidual: return launch_wide<kEpiResidual>(a, stream);
         case kEpiSwiglu: return launch_wide<kEpiSwiglu>(a, stream);
         case kEpiRelu: return launch_wide<kEpiRelu>(a, stream);
+        case kEpiRope: return launch_wide<kEpiRope>(a, stream);
         default: break;
         }
     }
+    if (a.epilogue == kEpiRope) return hipErrorInvalidValue;       // only the wide tile finishes q|k|v itself
     const int tiles_n = (a.NT * 16 + kTgBN - 1) / kTgBN;
     const int tiles_m = (a.M + kTgBM - 1) / kTgBM;
     // the XCD-aware numbering covers whole 4 x 8 super-blocks, rounded up to a multiple of 8 of them

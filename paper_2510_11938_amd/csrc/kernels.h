@@ -68,8 +68,19 @@ __host__ __device__ inline int64_t packed_operand(int nt, int ks, int KS)
     return (((int64_t)(nt / kPackGroup) * KS + ks) * kPackGroup + nt % kPackGroup) * 64;
 }
 constexpr int kPackStepStride = kPackGroup * 64;      // chunks between consecutive k-steps of one tile
+// half_tiles > 0 (the q and k matrices: head_dim / 32): inside every head of 2 * half_tiles row tiles the tiles of the
+// first and the second half of the head dimension alternate (tile j of the first half -> 2j, of the second -> 2j + 1), so
+// that the two values a rotary pair (d, d + head_dim/2) needs sit in the same lane of neighbouring accumulator tiles.
 hipError_t launch_weight_pack(const void *src, int N, int K, void *dst, int k_steps,
-                              int tile_offset, int tile_stride, hipStream_t stream);
+                              int tile_offset, int tile_stride, int half_tiles, hipStream_t stream);
+hipError_t launch_bias_pack(const void *src, int n, void *dst, int half_tiles, hipStream_t stream);   // a q or k bias, same order
+// column of the q|k|v projection output that holds dim d of a q or k head starting at column head_col
+__host__ __device__ inline int rotary_col(int head_col, int d, int head_dim)
+{
+    const int half_tiles = head_dim / 32, j = d / 16;
+    const int jp = j < half_tiles ? 2 * j : 2 * (j - half_tiles) + 1;
+    return head_col + jp * 16 + d % 16;
+}
 
 // ---------------------------------------------------------------- projections
 struct SkinnyArgs {
@@ -87,7 +98,24 @@ struct SkinnyArgs {
 };
 hipError_t launch_gemm_skinny(const SkinnyArgs &a, hipStream_t stream);
 
-enum { kEpiStore = 0, kEpiResidual = 1, kEpiSwiglu = 2, kEpiPartial = 3, kEpiRelu = 4 };
+struct RopeArgs {
+    const float *P;        // q|k|v partial sums [S][T][Nall], or nullptr
+    const uint16_t *qkv;   // q|k|v bf16 [T][Nall] (when P == nullptr)
+    const uint16_t *bias;  // optional q|k|v bias [Nall] bf16, added to the partial sums (P != nullptr only)
+    uint16_t *q_out;       // rotated q [T][Hq*D] bf16
+    uint16_t *pool;        // stage KV pool
+    const int32_t *tok_seq, *tok_pos;   // from the rope table
+    const int32_t *tok_row;             // from the rope table: the token's K row for kv head 0 inside a layer of the pool
+    const float *cs, *sn;
+    const int32_t *block_table;
+    int64_t num_blocks;
+    int T, S, max_blocks_per_seq, layer_local;
+    int n_q_heads, n_kv_heads, head_dim;
+};
+// kEpiRope: the q|k|v projection finishes its own rows: (+ bias,) round to bf16, rotary embedding of the q and k heads at
+// the token's position, q -> bf16 buffer, rotated k and raw v -> the token's slot of the paged cache (`rope`; P, qkv, S
+// and bias of it are not used).  Only the wide tile has this epilogue: gemm_wide_applies() says whether a launch gets it.
+enum { kEpiStore = 0, kEpiResidual = 1, kEpiSwiglu = 2, kEpiPartial = 3, kEpiRelu = 4, kEpiRope = 5 };
 struct TiledArgs {
     const uint16_t *W;     // packed weights
     const uint16_t *X;     // token rows [M][ldx] bf16
@@ -98,8 +126,10 @@ struct TiledArgs {
     int M, K, KS, NT, ldx, ldc, epilogue;
     int S;                 // kEpiPartial: split-K factor (grid.y)
     int blk_m;             // set by the launcher (wide tile): token tiles per XCD super-block, 8, 4, 2 or 1 (weight tiles: 32 / blk_m)
+    RopeArgs rope;         // kEpiRope
 };
 hipError_t launch_gemm_tiled(const TiledArgs &a, hipStream_t stream);
+bool gemm_wide_applies(const TiledArgs &a);      // the launch would run on the 256 x 256 tile (shape fits and it is the faster one)
 
 // ---------------------------------------------------------------- row-wise kernels
 // b == nullptr: RMSNorm, n = x * rsqrt(mean(x^2) + eps) * g;  else LayerNorm, n = (x - mean) * rsqrt(var + eps) * g + b
@@ -130,6 +160,11 @@ hipError_t launch_swiglu(const SwigluArgs &a, hipStream_t stream);
 struct RopeTableArgs {
     const int32_t *cu_seqlens_q, *ctx_lens;
     int32_t *tok_seq, *tok_pos;   // [T]
+    // [T] cache row of each token's K for kv head 0: (block_table[seq][pos / 16] * 2 * n_kv_heads) * 16 + pos % 16, in
+    // rows of head_dim values inside one layer of the pool (V: + n_kv_heads * 16; head h: + h * 16); the same for every layer
+    int32_t *tok_row;
+    const int32_t *block_table;
+    int max_blocks_per_seq, n_kv_heads;
     int32_t *blk_prefix;          // [num_seqs + 1] exclusive prefix of ceil((ctx+1)/16): the decode kernels' work cut
     float *cs, *sn;               // [T][D/2]
     int T, num_seqs, head_dim;
@@ -143,19 +178,6 @@ struct RopeTableArgs {
 };
 hipError_t launch_rope_table(const RopeTableArgs &a, hipStream_t stream);
 
-struct RopeArgs {
-    const float *P;        // q|k|v partial sums [S][T][Nall], or nullptr
-    const uint16_t *qkv;   // q|k|v bf16 [T][Nall] (when P == nullptr)
-    const uint16_t *bias;  // optional q|k|v bias [Nall] bf16, added to the partial sums (P != nullptr only)
-    uint16_t *q_out;       // rotated q [T][Hq*D] bf16
-    uint16_t *pool;        // stage KV pool
-    const int32_t *tok_seq, *tok_pos;   // from the rope table
-    const float *cs, *sn;
-    const int32_t *block_table;
-    int64_t num_blocks;
-    int T, S, max_blocks_per_seq, layer_local;
-    int n_q_heads, n_kv_heads, head_dim;
-};
 hipError_t launch_qkv_rope_kvwrite(const RopeArgs &a, hipStream_t stream);
 
 // ---------------------------------------------------------------- attention
