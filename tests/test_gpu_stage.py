@@ -158,7 +158,12 @@ PREFILL_CASES = [
     ("wide-tile-two-trips", MID128, 1, [0, 33], [2000, 101]),
     ("opt-wide-tile", OPT_WIDE_TILE, 1, [0, 0], [1300, 800]),
     ("wide-tile-ten-row-tiles", MID128, 1, [0], [2500]),              # a tile count that picks another XCD super-block shape
-    ("wide-tile-1100", WIDE_TILE, 1, [0, 0], [1000, 100]),            # between 1024 and 2048 rows: the launcher's estimate decides per projection
+    ("wide-tile-1100", WIDE_TILE, 1, [0, 0], [1000, 100]),
+    # grouped-query geometries on the wide tile: the q, k and v sections of the projection end inside a 256-row tile, and the
+    # rotary epilogue writes q, k and v rows of one workgroup to three places; a chunk behind a cached prefix (positions > 0)
+    ("wide-tile-gqa128", GQA128, 1, [0, 0], [1800, 400]),
+    ("wide-tile-gqa64", GQA64, 1, [0], [2100]),
+    ("wide-tile-chunk-behind-prefix", WIDE_TILE, 2, [700, 0], [1500, 600]),            # between 1024 and 2048 rows: the launcher's estimate decides per projection
 ]
 
 
