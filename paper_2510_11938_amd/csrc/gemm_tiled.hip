@@ -228,50 +228,69 @@ __global__ __launch_bounds__(kTgThreads, 2) void gemm_tiled_kernel(TiledArgs a)
     asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(xa0), "+v"(xa1) : : "memory");
 #undef FXP_TG_STAGE
 
-    // ---- epilogue
+    // ---- epilogue.  A wait for a load also waits for the stores before it (one counter), and the compiler waits for a
+    // load right where it is used, so loads scattered between the stores make a chain of round trips at the end of a
+    // tile: the bias is read once and the residual (which may be the output buffer itself: no load can be moved across a
+    // store; a lane reads only the addresses it writes itself) for four token tiles at a time, ahead of their stores.
+    u32x2 bias_v[kTgRn];
 #pragma unroll
-    for (int mt = 0; mt < kTgRm; ++mt) {
-        const int m = m0 + mt * 16 + col;
-        if (m >= a.M) continue;
-        if constexpr (EPI == kEpiPartial) {
+    for (int r = 0; r < kTgRn; ++r)
+        bias_v[r] = (EPI != kEpiPartial && EPI != kEpiSwiglu && a.bias) ? *reinterpret_cast<const u32x2 *>(a.bias + min(nt0 + r, a.NT - 1) * 16 + 4 * c)
+                                                                        : u32x2{0u, 0u};
+    constexpr int kGroup = 4;
 #pragma unroll
-            for (int r = 0; r < kTgRn; ++r) {
-                if (nt0 + r >= a.NT) continue;
-                const int n = (nt0 + r) * 16 + 4 * c;
-                *reinterpret_cast<f32x4_t *>(a.P + ((int64_t)blockIdx.y * a.M + m) * (a.NT * 16) + n) = acc[r][mt];
-            }
-        } else if constexpr (EPI == kEpiSwiglu) {
+    for (int mg = 0; mg < kTgRm; mg += kGroup) {
+        u32x2 resid[kGroup][kTgRn];
+        if constexpr (EPI == kEpiResidual) {
 #pragma unroll
-            for (int r = 0; r < kTgRn; r += 2) {
-                if (nt0 + r >= a.NT) continue;          // NT is even and nt0 + r is even: the pair is inside together
-                const int f = ((nt0 + r) / 2) * 16 + 4 * c;
-                float y[4];
+            for (int g = 0; g < kGroup; ++g)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const float g = acc[r][mt][v];
-                    y[v] = g / (1.f + __expf(-g)) * acc[r + 1][mt][v];
+                for (int r = 0; r < kTgRn; ++r)
+                    resid[g][r] = *reinterpret_cast<const u32x2 *>(a.R + (int64_t)min(m0 + (mg + g) * 16 + col, a.M - 1) * a.ldc +
+                                                                   min(nt0 + r, a.NT - 1) * 16 + 4 * c);
+        }
+#pragma unroll
+        for (int g = 0; g < kGroup; ++g) {
+            const int mt = mg + g;
+            const int m = m0 + mt * 16 + col;
+            if (m >= a.M) continue;
+            if constexpr (EPI == kEpiPartial) {
+#pragma unroll
+                for (int r = 0; r < kTgRn; ++r) {
+                    if (nt0 + r >= a.NT) continue;
+                    const int n = (nt0 + r) * 16 + 4 * c;
+                    *reinterpret_cast<f32x4_t *>(a.P + ((int64_t)blockIdx.y * a.M + m) * (a.NT * 16) + n) = acc[r][mt];
                 }
-                *reinterpret_cast<u32x2 *>(a.C + (int64_t)m * a.ldc + f) = u32x2{pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3])};
-            }
-        } else {
+            } else if constexpr (EPI == kEpiSwiglu) {
 #pragma unroll
-            for (int r = 0; r < kTgRn; ++r) {
-                if (nt0 + r >= a.NT) continue;
-                const int n = (nt0 + r) * 16 + 4 * c;
-                float y[4] = {acc[r][mt][0], acc[r][mt][1], acc[r][mt][2], acc[r][mt][3]};
-                if (a.bias) {
-                    const u32x2 bv = *reinterpret_cast<const u32x2 *>(a.bias + n);
-                    y[0] += bf16_lo(bv.x); y[1] += bf16_hi(bv.x); y[2] += bf16_lo(bv.y); y[3] += bf16_hi(bv.y);
-                }
-                if constexpr (EPI == kEpiRelu) {
+                for (int r = 0; r < kTgRn; r += 2) {
+                    if (nt0 + r >= a.NT) continue;          // NT is even and nt0 + r is even: the pair is inside together
+                    const int f = ((nt0 + r) / 2) * 16 + 4 * c;
+                    float y[4];
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) y[v] = fmaxf(y[v], 0.f);
+                    for (int v = 0; v < 4; ++v) {
+                        const float gt = acc[r][mt][v];
+                        y[v] = gt / (1.f + __expf(-gt)) * acc[r + 1][mt][v];
+                    }
+                    *reinterpret_cast<u32x2 *>(a.C + (int64_t)m * a.ldc + f) = u32x2{pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3])};
                 }
-                if constexpr (EPI == kEpiResidual) {
-                    const u32x2 rv = *reinterpret_cast<const u32x2 *>(a.R + (int64_t)m * a.ldc + n);
-                    y[0] += bf16_lo(rv.x); y[1] += bf16_hi(rv.x); y[2] += bf16_lo(rv.y); y[3] += bf16_hi(rv.y);
+            } else {
+#pragma unroll
+                for (int r = 0; r < kTgRn; ++r) {
+                    if (nt0 + r >= a.NT) continue;
+                    const int n = (nt0 + r) * 16 + 4 * c;
+                    float y[4] = {acc[r][mt][0] + bf16_lo(bias_v[r].x), acc[r][mt][1] + bf16_hi(bias_v[r].x),
+                                  acc[r][mt][2] + bf16_lo(bias_v[r].y), acc[r][mt][3] + bf16_hi(bias_v[r].y)};
+                    if constexpr (EPI == kEpiRelu) {
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) y[v] = fmaxf(y[v], 0.f);
+                    }
+                    if constexpr (EPI == kEpiResidual) {
+                        const u32x2 rv = resid[g][r];
+                        y[0] += bf16_lo(rv.x); y[1] += bf16_hi(rv.x); y[2] += bf16_lo(rv.y); y[3] += bf16_hi(rv.y);
+                    }
+                    *reinterpret_cast<u32x2 *>(a.C + (int64_t)m * a.ldc + n) = u32x2{pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3])};
                 }
-                *reinterpret_cast<u32x2 *>(a.C + (int64_t)m * a.ldc + n) = u32x2{pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3])};
             }
         }
     }
@@ -525,92 +544,129 @@ __global__ __launch_bounds__(kTgThreads, 1) void gemm_wide_kernel(TiledArgs a)
 #pragma unroll
             for (int mt = 0; mt < kWdRm; ++mt) trow[mt] = ra.tok_row[min(m0 + mt * 16 + col, a.M - 1)];
         }
+        // Every wait for a load also waits for the stores before it (one counter), and the compiler waits for a load right
+        // where it is used: loads scattered between the stores made this epilogue a chain of round trips.  So the loads
+        // come in batches ahead of the stores: the bias once, the cos / sin rows of four token tiles at a time.
         if (nt0 < a.NT) {
+            u32x2 bias_v[kWdRn];
 #pragma unroll
-            for (int mt = 0; mt < kWdRm; ++mt) {
-                const int m = m0 + mt * 16 + col;
-                if (m >= a.M) continue;
-                // destination of dim 0 of this head for token m
-                uint16_t *dst;
-                if (sect == 0) dst = ra.q_out + (int64_t)m * Nq + (int64_t)head * D;
-                else dst = ra.pool + ((int64_t)ra.layer_local * ra.num_blocks * 2 * ra.n_kv_heads * kBlockTokens + trow[mt] +
-                                      ((sect - 1) * ra.n_kv_heads + head) * kBlockTokens) * D;
-                auto rounded = [&](int r, float (&y)[4]) {          // the projection's values as bf16 (+ bias), as the unfused path stores them
-                    y[0] = acc[r][mt][0]; y[1] = acc[r][mt][1]; y[2] = acc[r][mt][2]; y[3] = acc[r][mt][3];
-                    if (a.bias) {
-                        const u32x2 bv = *reinterpret_cast<const u32x2 *>(a.bias + (nt0 + r) * 16 + 4 * c);
-                        y[0] += bf16_lo(bv.x); y[1] += bf16_hi(bv.x); y[2] += bf16_lo(bv.y); y[3] += bf16_hi(bv.y);
-                    }
-                    const uint32_t p0 = pack_bf16x2(y[0], y[1]), p1 = pack_bf16x2(y[2], y[3]);
-                    y[0] = bf16_lo(p0); y[1] = bf16_hi(p0); y[2] = bf16_lo(p1); y[3] = bf16_hi(p1);
-                };
-                if (sect == 2) {
-                    // v rows: natural order, no rotation
+            for (int r = 0; r < kWdRn; ++r)
+                bias_v[r] = a.bias ? *reinterpret_cast<const u32x2 *>(a.bias + (nt0 + r) * 16 + 4 * c) : u32x2{0u, 0u};
+            auto rounded = [&](int r, int mt, float (&y)[4]) {     // the projection's values as bf16 (+ bias), as the unfused path stores them
+                y[0] = acc[r][mt][0] + bf16_lo(bias_v[r].x); y[1] = acc[r][mt][1] + bf16_hi(bias_v[r].x);
+                y[2] = acc[r][mt][2] + bf16_lo(bias_v[r].y); y[3] = acc[r][mt][3] + bf16_hi(bias_v[r].y);
+                const uint32_t p0 = pack_bf16x2(y[0], y[1]), p1 = pack_bf16x2(y[2], y[3]);
+                y[0] = bf16_lo(p0); y[1] = bf16_hi(p0); y[2] = bf16_lo(p1); y[3] = bf16_hi(p1);
+            };
+            constexpr int kGroup = 4;
 #pragma unroll
-                    for (int r = 0; r < kWdRn; ++r) {
-                        float y[4];
-                        rounded(r, y);
-                        *reinterpret_cast<u32x2 *>(dst + (j0 + r) * 16 + 4 * c) = u32x2{pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3])};
-                    }
-                } else {
+            for (int mg = 0; mg < kWdRm; mg += kGroup) {
+                f32x4_t co[kGroup][2], si[kGroup][2];
+                if (sect != 2) {
 #pragma unroll
-                    for (int r = 0; r < kWdRn; r += 2) {
-                        const int d = ((j0 + r) / 2) * 16 + 4 * c;          // dim of the first-half value; its partner is d + D/2
-                        float lo[4], hi[4];
-                        rounded(r, lo);
-                        rounded(r + 1, hi);
-                        const f32x4_t co = *reinterpret_cast<const f32x4_t *>(ra.cs + (int64_t)m * half + d);
-                        const f32x4_t si = *reinterpret_cast<const f32x4_t *>(ra.sn + (int64_t)m * half + d);
-                        float rl[4], rh[4];
+                    for (int g = 0; g < kGroup; ++g)
 #pragma unroll
-                        for (int v = 0; v < 4; ++v) {
-                            rl[v] = lo[v] * co[v] - hi[v] * si[v];
-                            rh[v] = hi[v] * co[v] + lo[v] * si[v];
+                        for (int pr = 0; pr < 2; ++pr) {
+                            const int64_t at = (int64_t)min(m0 + (mg + g) * 16 + col, a.M - 1) * half + ((j0 + 2 * pr) / 2) * 16 + 4 * c;
+                            co[g][pr] = *reinterpret_cast<const f32x4_t *>(ra.cs + at);
+                            si[g][pr] = *reinterpret_cast<const f32x4_t *>(ra.sn + at);
                         }
-                        *reinterpret_cast<u32x2 *>(dst + d) = u32x2{pack_bf16x2(rl[0], rl[1]), pack_bf16x2(rl[2], rl[3])};
-                        *reinterpret_cast<u32x2 *>(dst + d + half) = u32x2{pack_bf16x2(rh[0], rh[1]), pack_bf16x2(rh[2], rh[3])};
+                }
+#pragma unroll
+                for (int g = 0; g < kGroup; ++g) {
+                    const int mt = mg + g;
+                    const int m = m0 + mt * 16 + col;
+                    if (m >= a.M) continue;
+                    // destination of dim 0 of this head for token m
+                    uint16_t *dst;
+                    if (sect == 0) dst = ra.q_out + (int64_t)m * Nq + (int64_t)head * D;
+                    else dst = ra.pool + ((int64_t)ra.layer_local * ra.num_blocks * 2 * ra.n_kv_heads * kBlockTokens + trow[mt] +
+                                          ((sect - 1) * ra.n_kv_heads + head) * kBlockTokens) * D;
+                    if (sect == 2) {
+                        // v rows: natural order, no rotation
+#pragma unroll
+                        for (int r = 0; r < kWdRn; ++r) {
+                            float y[4];
+                            rounded(r, mt, y);
+                            *reinterpret_cast<u32x2 *>(dst + (j0 + r) * 16 + 4 * c) = u32x2{pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3])};
+                        }
+                    } else {
+#pragma unroll
+                        for (int pr = 0; pr < 2; ++pr) {
+                            const int r = 2 * pr;
+                            const int d = ((j0 + r) / 2) * 16 + 4 * c;          // dim of the first-half value; its partner is d + D/2
+                            float lo[4], hi[4];
+                            rounded(r, mt, lo);
+                            rounded(r + 1, mt, hi);
+                            float rl[4], rh[4];
+#pragma unroll
+                            for (int v = 0; v < 4; ++v) {
+                                rl[v] = lo[v] * co[g][pr][v] - hi[v] * si[g][pr][v];
+                                rh[v] = hi[v] * co[g][pr][v] + lo[v] * si[g][pr][v];
+                            }
+                            *reinterpret_cast<u32x2 *>(dst + d) = u32x2{pack_bf16x2(rl[0], rl[1]), pack_bf16x2(rl[2], rl[3])};
+                            *reinterpret_cast<u32x2 *>(dst + d + half) = u32x2{pack_bf16x2(rh[0], rh[1]), pack_bf16x2(rh[2], rh[3])};
+                        }
                     }
                 }
             }
         }
         return;
     }
+    // (loads in batches ahead of the stores, as in the rotary epilogue: the bias once, the residual -- which may be the
+    // output buffer itself, so that no load can be moved across a store -- for four token tiles at a time; a lane reads
+    // only the addresses it writes itself)
+    u32x2 bias_v[kWdRn];
 #pragma unroll
-    for (int mt = 0; mt < kWdRm; ++mt) {
-        const int m = m0 + mt * 16 + col;
-        if (m >= a.M) continue;
-        if constexpr (EPI == kEpiSwiglu) {
+    for (int r = 0; r < kWdRn; ++r)
+        bias_v[r] = (EPI != kEpiSwiglu && a.bias) ? *reinterpret_cast<const u32x2 *>(a.bias + min(nt0 + r, a.NT - 1) * 16 + 4 * c) : u32x2{0u, 0u};
+    constexpr int kGroup = 4;
 #pragma unroll
-            for (int r = 0; r < kWdRn; r += 2) {
-                if (nt0 + r >= a.NT) continue;
-                const int f = ((nt0 + r) / 2) * 16 + 4 * c;
-                float y[4];
+    for (int mg = 0; mg < kWdRm; mg += kGroup) {
+        u32x2 resid[kGroup][kWdRn];
+        if constexpr (EPI == kEpiResidual) {
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const float g = acc[r][mt][v];
-                    y[v] = g / (1.f + __expf(-g)) * acc[r + 1][mt][v];
+            for (int g = 0; g < kGroup; ++g)
+#pragma unroll
+                for (int r = 0; r < kWdRn; ++r)
+                    resid[g][r] = *reinterpret_cast<const u32x2 *>(a.R + (int64_t)min(m0 + (mg + g) * 16 + col, a.M - 1) * a.ldc +
+                                                                   min(nt0 + r, a.NT - 1) * 16 + 4 * c);
+        }
+#pragma unroll
+        for (int g = 0; g < kGroup; ++g) {
+            const int mt = mg + g;
+            const int m = m0 + mt * 16 + col;
+            if (m >= a.M) continue;
+            if constexpr (EPI == kEpiSwiglu) {
+#pragma unroll
+                for (int r = 0; r < kWdRn; r += 2) {
+                    if (nt0 + r >= a.NT) continue;
+                    const int f = ((nt0 + r) / 2) * 16 + 4 * c;
+                    float y[4];
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const float gt = acc[r][mt][v];
+                        y[v] = gt / (1.f + __expf(-gt)) * acc[r + 1][mt][v];
+                    }
+                    *reinterpret_cast<u32x2 *>(a.C + (int64_t)m * a.ldc + f) = u32x2{pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3])};
                 }
-                *reinterpret_cast<u32x2 *>(a.C + (int64_t)m * a.ldc + f) = u32x2{pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3])};
-            }
-        } else {
+            } else {
 #pragma unroll
-            for (int r = 0; r < kWdRn; ++r) {
-                if (nt0 + r >= a.NT) continue;
-                const int n = (nt0 + r) * 16 + 4 * c;
-                float y[4] = {acc[r][mt][0], acc[r][mt][1], acc[r][mt][2], acc[r][mt][3]};
-                if (a.bias) {
-                    const u32x2 bv = *reinterpret_cast<const u32x2 *>(a.bias + n);
-                    y[0] += bf16_lo(bv.x); y[1] += bf16_hi(bv.x); y[2] += bf16_lo(bv.y); y[3] += bf16_hi(bv.y);
-                }
-                if constexpr (EPI == kEpiRelu) {
+                for (int r = 0; r < kWdRn; ++r) {
+                    if (nt0 + r >= a.NT) continue;
+                    const int n = (nt0 + r) * 16 + 4 * c;
+                    float y[4] = {acc[r][mt][0] + bf16_lo(bias_v[r].x), acc[r][mt][1] + bf16_hi(bias_v[r].x),
+                                  acc[r][mt][2] + bf16_lo(bias_v[r].y), acc[r][mt][3] + bf16_hi(bias_v[r].y)};
+                    if constexpr (EPI == kEpiRelu) {
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) y[v] = fmaxf(y[v], 0.f);
+                        for (int v = 0; v < 4; ++v) y[v] = fmaxf(y[v], 0.f);
+                    }
+                    if constexpr (EPI == kEpiResidual) {
+                        const u32x2 rv = resid[g][r];
+                        y[0] += bf16_lo(rv.x); y[1] += bf16_hi(rv.x); y[2] += bf16_lo(rv.y); y[3] += bf16_hi(rv.y);
+                    }
+                    *reinterpret_cast<u32x2 *>(a.C + (int64_t)m * a.ldc + n) = u32x2{pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3])};
                 }
-                if constexpr (EPI == kEpiResidual) {
-                    const u32x2 rv = *reinterpret_cast<const u32x2 *>(a.R + (int64_t)m * a.ldc + n);
-                    y[0] += bf16_lo(rv.x); y[1] += bf16_hi(rv.x); y[2] += bf16_lo(rv.y); y[3] += bf16_hi(rv.y);
-                }
-                *reinterpret_cast<u32x2 *>(a.C + (int64_t)m * a.ldc + n) = u32x2{pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3])};
             }
         }
     }
