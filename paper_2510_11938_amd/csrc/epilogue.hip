@@ -142,6 +142,41 @@ __global__ __launch_bounds__(THREADS) void resid_norm_kernel(ResidNormArgs a)
     __shared__ float red[THREADS / 64];
     const int t = blockIdx.x;
     const int64_t row = (int64_t)t * a.H;
+    if (a.g && !a.nb && a.H / 8 <= THREADS) {
+        // RMSNorm behind the residual with at most one 8-wide chunk per thread (every launch of the decode path): the
+        // rounded hidden values stay in registers for the norm instead of being read back from the memory they were
+        // just stored to (a store, a wait for it, and a second memory round trip in a kernel that is all latency)
+        const int c = threadIdx.x;
+        const bool live = c < a.H / 8;
+        float f[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, gg[8];
+        float ss = 0.f;
+        if (live) {
+            float p[8];
+            unpack8(ld16(a.x + row + c * 8), f);
+            unpack8(ld16(a.g + c * 8), gg);
+            partial8(a.P, a.S, (int64_t)a.T * a.H, row + c * 8, p);
+            if (a.bias) {
+                float bb[8];
+                unpack8(ld16(a.bias + c * 8), bb);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) p[e] += bb[e];
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) f[e] += p[e];
+            const u32x4 hv = pack8(f);
+            st16(a.h + row + c * 8, hv);
+            unpack8(hv, f);                 // the norm sees the rounded hidden state, as the next stage would
+#pragma unroll
+            for (int e = 0; e < 8; ++e) ss += f[e] * f[e];
+        }
+        const float rstd = rsqrtf(block_sum<THREADS>(ss, red) / (float)a.H + a.eps);
+        if (live) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) f[e] = f[e] * rstd * gg[e];
+            st16(a.n + row + c * 8, pack8(f));
+        }
+        return;
+    }
     float ss = 0.f;
     for (int c = threadIdx.x; c < a.H / 8; c += THREADS) {
         float f[8], p[8];
