@@ -264,8 +264,8 @@ __global__ __launch_bounds__(kRopeTableThreads) void rope_table_kernel(RopeTable
     __shared__ int s_seq, s_pos;
     const int t = blockIdx.x, half = a.head_dim / 2;
     if (threadIdx.x == 0) {
-        // sequence that owns token t: cu[seq] <= t < cu[seq+1]
-        int lo = 0, hi = a.num_seqs;
+        // sequence that owns token t: cu[seq] <= t < cu[seq+1] (a chain of dependent loads; a decode step needs none)
+        int lo = a.one_token_each ? t : 0, hi = a.one_token_each ? t + 1 : a.num_seqs;
         while (hi - lo > 1) { const int mid = (lo + hi) >> 1; if (a.cu_seqlens_q[mid] <= t) lo = mid; else hi = mid; }
         s_seq = lo;
         s_pos = a.ctx_lens[lo] + (t - a.cu_seqlens_q[lo]);

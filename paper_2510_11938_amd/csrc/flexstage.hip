@@ -519,6 +519,7 @@ static int forward_impl(fxp_stage *stage, const fxp_kv_pool *pool, const fxp_bat
         rt.tok_row = w.tok_row; rt.block_table = batch->block_table; rt.max_blocks_per_seq = batch->max_blocks_per_seq; rt.n_kv_heads = d.n_kv_heads;
         rt.cs = w.rope_cs; rt.sn = w.rope_sn; rt.T = T; rt.num_seqs = B; rt.head_dim = D; rt.rope_base = d.rope_base;
         rt.identity = opt ? 1 : 0;
+        rt.one_token_each = decode ? 1 : 0;
         // the attention norm of the stage's first layer goes with it
         rt.norm_x = (const uint16_t *)hidden_in; rt.norm_g = (const uint16_t *)(stage->arena + stage->rec.g_attn);
         rt.norm_b = opt ? (const uint16_t *)(stage->arena + stage->rec.b_attn) : nullptr;

@@ -170,6 +170,7 @@ struct RopeTableArgs {
     int T, num_seqs, head_dim;
     float rope_base;
     int identity;                 // 1: no rotary embedding (cos = 1, sin = 0)
+    int one_token_each;           // 1: a pure decode step (token t belongs to sequence t): no search through cu_seqlens_q
     // the first layer's attention norm rides in the same launch (one launch less per step); skipped when norm_x is null
     const uint16_t *norm_x, *norm_g, *norm_b;   // rows [T][norm_H], gain, optional LayerNorm bias
     uint16_t *norm_out;
