@@ -176,6 +176,27 @@ def test_prefill_matches_oracle(name, ms, L, ctx, q):
     check_appended_rows(case, cache, opool)
 
 
+@pytest.mark.parametrize("seed", range(10))
+def test_random_long_prompt_calls_on_the_wide_tile_match_oracle(seed):
+    # seeded sweep over what the 256 x 256 projection tile and its rotary epilogue branch on: head geometry (query heads
+    # per kv head, head_dim 64 / 128, so the q, k and v sections end at different places inside a 256-row tile), widths
+    # (contraction lengths that fit the tile and some that do not: those projections fall back), both layer kinds,
+    # 1024 .. 3200 token rows in one to three prompts, some behind a cached prefix
+    rng = np.random.default_rng(7000 + seed)
+    D, hkv, g = int(rng.choice([64, 128])), int(rng.choice([1, 2, 4])), int(rng.choice([1, 2, 4]))
+    ms = synth.ModelShape(hidden=int(rng.choice([256, 512, 768])), n_q_heads=hkv * g, n_kv_heads=hkv, head_dim=D,
+                          ffn=int(rng.choice([256, 512, 1024, 1280, 688])), arch=int(rng.random() < 0.25))
+    nseq, T = int(rng.integers(1, 4)), int(rng.integers(1024, 3200))
+    cuts = np.sort(rng.choice(np.arange(1, T), size=nseq - 1, replace=False)) if nseq > 1 else np.array([], dtype=int)
+    q = np.diff(np.concatenate([[0], cuts, [T]])).astype(int).tolist()
+    ctx = [int(rng.choice([0, 0, 17, 300])) for _ in q]
+    case = Case(ms, int(rng.integers(1, 3)), ctx, q, seed=200 + seed)
+    want, opool = case.oracle_run()
+    got, cache = case.gpu_run()
+    assert rel_err(host_f64(got), want) <= TOL_OUT
+    check_appended_rows(case, cache, opool)
+
+
 RANDOM_SHAPES = [TINY, GQA64, MID128, GQA128, KV6, GQA_KV3, ODD_K, OPT_TINY, OPT_GQA]
 
 
