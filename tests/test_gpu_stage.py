@@ -474,31 +474,37 @@ def test_tiny_decode_step_and_merge_against_the_stored_oracle_values():
     assert hashlib.sha256(host_bits(merged.pool).tobytes()).hexdigest() == sha
 
 
-def test_decode_step_can_be_captured_in_a_graph_and_replayed():
+@pytest.mark.parametrize("kind", ["decode", "long-prompt"])
+def test_a_step_can_be_captured_in_a_graph_and_replayed(kind):
     """The library only enqueues kernels on the caller's stream (no allocation, no synchronisation, no
     memset), so a step can be recorded into a HIP graph by the caller.  Replays are interleaved with eager
-    steps and synchronisations and must reproduce the eager result bit for bit every time."""
-    case = Case(TINY, 2, [37, 128, 32, 100], [1] * 4, seed=31)
-    stage = make_stage(TINY, case.w, 0, 2)
+    steps and synchronisations and must reproduce the eager result bit for bit every time.  The long prompt
+    runs its projections on the wide tile (128 KiB of dynamic LDS, loads issued from inline assembly)."""
+    if kind == "decode":
+        shape, case = TINY, Case(TINY, 2, [37, 128, 32, 100], [1] * 4, seed=31)
+    else:
+        shape, case = WIDE_TILE, Case(WIDE_TILE, 2, [0, 40], [1100, 200], seed=31)
+    stage = make_stage(shape, case.w, 0, 2)
     cache = case.gpu_cache()
     cu, cl, x = dev_i32(case.cu), dev_i32(case.ctx), dev_bf16(case.hidden_bits)
-    y_eager = stage.forward(cache, cu, cl, x, 1).clone()            # also sizes the workspace before capture
+    mq = int(case.q_lens.max())
+    y_eager = stage.forward(cache, cu, cl, x, mq).clone()           # also sizes the workspace before capture
     torch.cuda.synchronize()
     y_graph = torch.empty_like(x)
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     g = torch.cuda.CUDAGraph()
     with torch.cuda.stream(side):
-        stage.forward(cache, cu, cl, x, 1, hidden_out=y_graph)      # warm-up on the capture stream
+        stage.forward(cache, cu, cl, x, mq, hidden_out=y_graph)     # warm-up on the capture stream
         side.synchronize()
         with torch.cuda.graph(g, stream=side):
-            stage.forward(cache, cu, cl, x, 1, hidden_out=y_graph)
+            stage.forward(cache, cu, cl, x, mq, hidden_out=y_graph)
     torch.cuda.current_stream().wait_stream(side)
     for rep in range(4):
         y_graph.zero_()
         g.replay()
         torch.cuda.synchronize()
         assert torch.equal(y_graph.view(torch.int16), y_eager.view(torch.int16)), rep
-        again = stage.forward(cache, cu, cl, x, 1)                  # eager work between the replays
+        again = stage.forward(cache, cu, cl, x, mq)                 # eager work between the replays
         torch.cuda.synchronize()
         assert torch.equal(again.view(torch.int16), y_eager.view(torch.int16))

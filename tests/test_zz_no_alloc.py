@@ -36,12 +36,13 @@ def both_ways(stage, ms, seed, ctx, q_lens, pool_bits, table):
     return outs, pools
 
 
-def test_static_scratch_forward_equals_workspace_forward_on_two_calls_in_a_row():
+def test_static_scratch_forward_equals_workspace_forward_on_calls_in_a_row():
     ms, L, seed = SHAPE, 2, 31
     w = make_weights(ms, seed, L, want_f32=False)
     stage = make_stage(ms, w, 0, L)
-    # first call: a mixed batch (one prompt chunk behind a prefix, decode rows); second call: a smaller decode batch
-    calls = [([300, 1100, 17, 640, 2047, 5], [70, 1, 1, 1, 1, 33]), ([513, 40, 900], [1, 1, 1])]
+    # first call: a mixed batch (one prompt chunk behind a prefix, decode rows); last call: a smaller decode batch
+    # ... and between them a long prompt whose projections run on the wide tile
+    calls = [([300, 1100, 17, 640, 2047, 5], [70, 1, 1, 1, 1, 33]), ([0, 64], [1200, 90]), ([513, 40, 900], [1, 1, 1])]
     for ctx, q_lens in calls:
         ctx_a, q_a = np.asarray(ctx, dtype=np.int32), np.asarray(q_lens, dtype=np.int32)
         table, nblk = synth.block_table(ctx_a + q_a, 16, seed, salt=len(ctx))
